@@ -1,0 +1,6 @@
+"""fp64 CPU oracle of the DualSparse-MoE layer forward pass.
+
+Test infrastructure only: the test-suite, the smoke check and the benchmark's CPU-baseline leg
+may import this package; the GPU library and its Python binding never do.
+"""
+from .oracle import build, route, forward, n_threads, RouteResult  # noqa: F401

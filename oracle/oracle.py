@@ -1,0 +1,129 @@
+"""ctypes wrapper around dsmoe_oracle.c (compiled with gcc on first use or by build())."""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dsmoe_oracle.c")
+_LIB = os.path.join(_HERE, "libdsmoe_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 -fopenmp.  Returns the path of the shared object."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.dsmoe_oracle_threads.restype = ctypes.c_int
+        L.dsmoe_oracle_route.restype = ctypes.c_int
+        L.dsmoe_oracle_forward.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def n_threads() -> int:
+    return int(_load().dsmoe_oracle_threads())
+
+
+@dataclass
+class RouteResult:
+    idx: np.ndarray          # [T][K] int32 expert ids, selection order
+    s: np.ndarray            # [T][K] softmax scores
+    n: np.ndarray            # [T][K] scores normalised over the K selected
+    g: np.ndarray            # [T][K] combine weights (s, or n with renorm)
+    keep: np.ndarray         # [T][K][P] uint8
+    group_count: np.ndarray  # [E*P] int64 kept units of sub-expert e*P+p
+    min_margin: float        # min |n - tau| over resident units
+
+    @property
+    def keep_bits(self) -> np.ndarray:
+        """[T][K] uint8, bit p set iff partition p is kept."""
+        P = self.keep.shape[2]
+        w = (1 << np.arange(P)).astype(np.uint32)
+        return (self.keep.astype(np.uint32) * w).sum(axis=2).astype(np.uint8)
+
+
+def route(logits: np.ndarray, K: int, P: int, tau: np.ndarray, lo: int = 0, hi: Optional[int] = None,
+          renorm: bool = False) -> RouteResult:
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    hi = E if hi is None else hi
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    assert tau.shape == (E, P), (tau.shape, (E, P))
+    idx = np.empty((T, K), dtype=np.int32)
+    s = np.empty((T, K), dtype=np.float64)
+    n = np.empty((T, K), dtype=np.float64)
+    g = np.empty((T, K), dtype=np.float64)
+    keep = np.empty((T, K, P), dtype=np.uint8)
+    gc = np.empty((E * P,), dtype=np.int64)
+    mm = ctypes.c_double(0.0)
+    rc = _load().dsmoe_oracle_route(_p(logits), T, E, K, P, _p(tau), lo, hi, int(bool(renorm)), _p(idx), _p(s), _p(n),
+                                    _p(g), _p(keep), _p(gc), ctypes.byref(mm))
+    if rc != 0:
+        raise ValueError("dsmoe_oracle_route: bad argument")
+    return RouteResult(idx, s, n, g, keep, gc, float(mm.value))
+
+
+def forward(x: np.ndarray, logits: np.ndarray, w1: np.ndarray, w3: np.ndarray, w2: np.ndarray, tau: np.ndarray, K: int,
+            P: int, perm: Optional[np.ndarray] = None, sh_w1: Optional[np.ndarray] = None,
+            sh_w3: Optional[np.ndarray] = None, sh_w2: Optional[np.ndarray] = None, lo: int = 0,
+            hi: Optional[int] = None, renorm: bool = False, tokens: Optional[np.ndarray] = None) -> np.ndarray:
+    """Layer output, float64 [n_tokens][D].  x / weights: float32 arrays, or uint16 arrays of bf16 bits."""
+    dtype = 1 if x.dtype == np.uint16 else 0
+    el = np.uint16 if dtype else np.float32
+    x = np.ascontiguousarray(x, dtype=el)
+    w1 = np.ascontiguousarray(w1, dtype=el)
+    w3 = np.ascontiguousarray(w3, dtype=el)
+    w2 = np.ascontiguousarray(w2, dtype=el)
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, D = x.shape
+    E = logits.shape[1]
+    hi = E if hi is None else hi
+    E_res, D2, F = w1.shape
+    assert D2 == D and E_res == hi - lo and w3.shape == w1.shape and w2.shape == (E_res, F, D)
+    assert logits.shape[0] == T
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    assert tau.shape == (E, P)
+    if perm is not None:
+        perm = np.ascontiguousarray(perm, dtype=np.int32)
+        assert perm.shape == (E_res, F)
+    n_shared, F_sh = 0, 0
+    if sh_w1 is not None:
+        sh_w1 = np.ascontiguousarray(sh_w1, dtype=el)
+        sh_w3 = np.ascontiguousarray(sh_w3, dtype=el)
+        sh_w2 = np.ascontiguousarray(sh_w2, dtype=el)
+        n_shared, _, F_sh = sh_w1.shape
+        assert sh_w1.shape == (n_shared, D, F_sh) and sh_w3.shape == sh_w1.shape and sh_w2.shape == (n_shared, F_sh, D)
+    if tokens is None:
+        n_tok = T
+    else:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        n_tok = int(tokens.shape[0])
+    y = np.empty((n_tok, D), dtype=np.float64)
+    rc = _load().dsmoe_oracle_forward(_p(x), _p(logits), _p(w1), _p(w3), _p(w2), _p(sh_w1), _p(sh_w3), _p(sh_w2),
+                                      _p(perm), _p(tau), T, D, F, E, K, P, n_shared, F_sh, lo, hi, int(bool(renorm)),
+                                      dtype, _p(tokens), n_tok, _p(y))
+    if rc != 0:
+        raise ValueError("dsmoe_oracle_forward: bad argument")
+    return y
