@@ -1,0 +1,140 @@
+/*
+ * dsmoe.h - C ABI of libdsmoe: forward pass of a partitioned, computation-dropping MoE FFN layer
+ * on one AMD MI355X (gfx950).
+ *
+ * The layer (DualSparse-MoE, arXiv 2508.18376):
+ *   gating      s = Softmax(router logits), Top-K experts per token            (Sec. 2.1.1, Eq. 1-2)
+ *   experts     f_e(x) = (Swish(x W1_e) * (x W3_e)) W2_e                       (Sec. 2.1.1, Eq. 4)
+ *   partition   expert e's neurons, put in the order of a static permutation (most important
+ *               first), are split evenly into P contiguous sub-experts e*P .. e*P+P-1; every
+ *               sub-expert inherits the gate score of its expert, W2 is not rescaled
+ *                                                                    (Sec. 3.2; Sec. 4.2 a, b)
+ *   dropping    n = score normalised over the K selected experts; unit (token, expert e,
+ *               partition p) is computed iff n >= tau[e][p]; tau equal across p is the single-
+ *               threshold drop, tau[.][0] < tau[.][1] the dual-threshold drop; per-expert rows of
+ *               tau carry load-aware thresholds                    (Sec. 4.1; Sec. 4.2 c; Sec. 4.3)
+ *   output      y = sum over kept units of g_e * f_{e,p}(x) (+ always-on shared experts), with
+ *               g_e the ORIGINAL gate score (or n, for models that normalise)   (Eq. 3; Sec. 4.1)
+ *
+ * Conventions
+ *   - Every pointer named "device" below is GPU memory on the current HIP device, owned by the
+ *     caller; the library allocates no device memory and keeps no reference after the call's
+ *     kernels have run.  "stream" is a hipStream_t passed as void* (NULL = the default stream).
+ *   - All calls return 0 (DSMOE_OK) or a negative dsmoe_status; they never throw.
+ *   - moe_route_and_mask and moe_dualsparse_forward only enqueue kernels: no host
+ *     synchronisation, no allocation.  moe_partition_weights synchronises the stream once
+ *     (it reads back the permutation check).
+ *   - NaN router logits give unspecified routing (not an error).
+ */
+#ifndef DSMOE_H
+#define DSMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dsmoe_ctx dsmoe_ctx; /* opaque; host memory owned by the library */
+
+typedef enum { DSMOE_F32 = 0, DSMOE_BF16 = 1 } dsmoe_dtype;
+
+typedef enum {
+  DSMOE_OK = 0,
+  DSMOE_EINVAL = -1, /* bad shape, divisibility, limit, NULL pointer, T > max_tokens */
+  DSMOE_EPERM = -2,  /* perm is not a permutation of 0..d_ff-1 for some expert */
+  DSMOE_ENOSPC = -3, /* reserved: workspace too small */
+  DSMOE_EHIP = -4    /* a HIP call or kernel launch failed; see dsmoe_last_hip_error */
+} dsmoe_status;
+
+typedef struct {
+  int32_t d_model;        /* D */
+  int32_t d_ff;           /* F: neurons of one routed expert; F % n_part == 0 */
+  int32_t n_experts;      /* E: width of the router (all experts of the layer), 1..512 */
+  int32_t top_k;          /* K: 1..min(E,16) */
+  int32_t n_part;         /* P: sub-experts per expert, 1..8 */
+  int32_t n_shared;       /* always-on experts (0 if none) */
+  int32_t d_ff_shared;    /* neurons of one shared expert */
+  int32_t expert_lo;      /* routed experts [expert_lo, expert_hi) are resident on this GPU; */
+  int32_t expert_hi;      /*   pairs routed elsewhere contribute nothing here. [0,E) = all */
+  int32_t renorm_combine; /* 0: combine weight = softmax score (Eq. 2); 1: = normalised score */
+  int32_t max_tokens;     /* largest T of any later call; sizes the workspace */
+  int32_t dtype;          /* dsmoe_dtype of x, weights and y */
+} dsmoe_config;
+
+/* Validates cfg and builds the host-side context.  No GPU call is made. */
+int dsmoe_create(const dsmoe_config* cfg, dsmoe_ctx** out);
+int dsmoe_destroy(dsmoe_ctx* ctx);
+
+/* Bytes of the packed-weight buffer / of the workspace the caller must allocate (device). */
+size_t dsmoe_packed_bytes(const dsmoe_ctx* ctx);
+size_t dsmoe_workspace_bytes(const dsmoe_ctx* ctx);
+
+const char* dsmoe_strerror(int status);
+/* hipError_t value of the last failed HIP call on this context (0 if none). */
+int dsmoe_last_hip_error(const dsmoe_ctx* ctx);
+/* 1 if this context runs the bf16 MFMA kernels, 0 if it runs the generic fp32-accumulate kernels
+ * (fp32 layers, or bf16 layers whose D or F/P is not a multiple of 64). */
+int dsmoe_uses_mfma(const dsmoe_ctx* ctx);
+
+/*
+ * Expert partition + reconstruction, once per layer (Sec. 3.2: even split into P sub-experts,
+ * no W2 scaling; Sec. 4.2 b: neurons reorganised by a static importance order).
+ *   w1, w3   device [E_res][D][F]   gate / up projections of the resident experts, row-major
+ *   w2       device [E_res][F][D]   down projection           (E_res = expert_hi - expert_lo)
+ *   sh_w1, sh_w3 device [n_shared][D][F_sh], sh_w2 device [n_shared][F_sh][D]; NULL iff n_shared == 0
+ *   perm     device int32 [E_res][F]: perm[e][j] = ORIGINAL neuron placed at new position j;
+ *            sub-expert p owns positions [p*F/P, (p+1)*F/P).  NULL = identity.
+ *   packed_out device, dsmoe_packed_bytes(ctx) bytes: receives the weights in the library's
+ *            kernel layout; inputs are not modified.
+ * Returns DSMOE_EPERM (packed_out contents then undefined) if perm is not a permutation.
+ */
+int moe_partition_weights(dsmoe_ctx* ctx, const void* w1, const void* w3, const void* w2, const void* sh_w1,
+                          const void* sh_w3, const void* sh_w2, const int32_t* perm, void* packed_out, void* stream);
+
+/*
+ * Gating, Top-K and drop mask (Eq. 1-2; Sec. 4.1; Sec. 4.2 c; index remap of Sec. 3.2).
+ *   logits  device float [T][E]
+ *   tau     device float [E][P], row = global expert id, column = partition (0 = major)
+ *   topk_idx   device int32 [T][K]  expert ids by (logit descending, index ascending)
+ *   topk_w     device float [T][K]  combine weight g (see renorm_combine)
+ *   keep_bits  device uint8 [T][K]  bit p set iff unit (t, k, p) is kept; 0 for non-resident experts
+ *   group_count device int32 [E*P]  kept units of sub-expert e*P+p
+ * T may be 0.  Arithmetic is fp32; the keep decision is (n >= tau) in fp32.
+ */
+int moe_route_and_mask(dsmoe_ctx* ctx, const float* logits, int32_t T, const float* tau, int32_t* topk_idx,
+                       float* topk_w, uint8_t* keep_bits, int32_t* group_count, void* stream);
+
+/*
+ * The whole layer: gating + mask, compacted per-expert row lists, grouped GEMM gate/up with
+ * Swish*mul, grouped GEMM down over the kept partitions only, gate-weighted combine (Eq. 1-4 with
+ * the dropped units of Sec. 4 removed).
+ *   packed  device, written by moe_partition_weights for this ctx
+ *   x       device [T][D] (cfg.dtype), logits device float [T][E], tau device float [E][P]
+ *   y       device [T][D] (cfg.dtype), fully overwritten; a token with every unit dropped gets
+ *           exact zeros (plus the shared experts' output)
+ *   workspace device, >= dsmoe_workspace_bytes(ctx), 256-byte aligned; contents need not be
+ *           preserved between calls; two calls that overlap in time need two workspaces
+ * bf16 layers accumulate in fp32 and round once (the intermediate activation is stored as bf16).
+ */
+int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, const float* tau,
+                           int32_t T, void* y, void* workspace, void* stream);
+
+/*
+ * Inspection of the last forward call's plan, for tests: byte offsets into the workspace.
+ * Fills out[0..DSMOE_PLAN_FIELDS-1]; returns the number of fields.
+ *   0 topk_idx int32[T*K]      1 topk_w float[T*K]        2 keep_bits uint8[T*K]
+ *   3 pair_row int32[T*K] (-1 = no kept unit)              4 row_token int32[rows]
+ *   5 row_bits uint8[rows]     6 expert_nrows int32[E_res] 7 expert_row0 int32[E_res]
+ *   8 row capacity (a count, not an offset)                9 row tile height (a count)
+ *  10 rows reserved at the start of the row space for the shared experts (a count)
+ *  11 counters int32[4]: items of GEMM-1, items of GEMM-2, row tiles, 0
+ */
+#define DSMOE_PLAN_FIELDS 12
+int dsmoe_plan_layout(const dsmoe_ctx* ctx, int64_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSMOE_H */

@@ -1,0 +1,21 @@
+"""DualSparse-MoE layer forward on MI355X: thin Python binding over libdsmoe.so.
+
+Every step of the layer runs in the HIP kernels of the shared library; this package only
+marshals arguments.  PyTorch is used for device memory and streams.  There is no CPU fallback:
+importing `binding` without a built library raises.
+"""
+from .binding import (  # noqa: F401
+    DsmoeError,
+    DualSparseLayer,
+    dsmoe_create,
+    dsmoe_destroy,
+    dsmoe_packed_bytes,
+    dsmoe_workspace_bytes,
+    dsmoe_strerror,
+    dsmoe_uses_mfma,
+    dsmoe_plan_layout,
+    moe_partition_weights,
+    moe_route_and_mask,
+    moe_dualsparse_forward,
+    lib_path,
+)

@@ -1,0 +1,226 @@
+"""ctypes marshalling for include/dsmoe.h.  Same names as the C ABI; tensors are torch tensors on
+the GPU, passed as raw device pointers."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdsmoe.so")
+
+DSMOE_F32, DSMOE_BF16 = 0, 1
+DSMOE_PLAN_FIELDS = 12
+
+
+class DsmoeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, dsmoe_strerror(status)))
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "d_model", "d_ff", "n_experts", "top_k", "n_part", "n_shared", "d_ff_shared", "expert_lo", "expert_hi",
+        "renorm_combine", "max_tokens", "dtype")]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libdsmoe.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
+    L.dsmoe_create.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
+    L.dsmoe_create.restype = ctypes.c_int
+    L.dsmoe_destroy.argtypes = [vp]
+    L.dsmoe_destroy.restype = ctypes.c_int
+    L.dsmoe_packed_bytes.argtypes = [vp]
+    L.dsmoe_packed_bytes.restype = ctypes.c_size_t
+    L.dsmoe_workspace_bytes.argtypes = [vp]
+    L.dsmoe_workspace_bytes.restype = ctypes.c_size_t
+    L.dsmoe_strerror.argtypes = [ctypes.c_int]
+    L.dsmoe_strerror.restype = ctypes.c_char_p
+    L.dsmoe_last_hip_error.argtypes = [vp]
+    L.dsmoe_last_hip_error.restype = ctypes.c_int
+    L.dsmoe_uses_mfma.argtypes = [vp]
+    L.dsmoe_uses_mfma.restype = ctypes.c_int
+    L.moe_partition_weights.argtypes = [vp] * 10
+    L.moe_partition_weights.restype = ctypes.c_int
+    L.moe_route_and_mask.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    L.moe_route_and_mask.restype = ctypes.c_int
+    L.moe_dualsparse_forward.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    L.moe_dualsparse_forward.restype = ctypes.c_int
+    L.dsmoe_plan_layout.argtypes = [vp, i64p]
+    L.dsmoe_plan_layout.restype = ctypes.c_int
+    return L
+
+
+_lib = _load()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous GPU tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def dsmoe_strerror(status: int) -> str:
+    return _lib.dsmoe_strerror(int(status)).decode()
+
+
+def dsmoe_create(*, d_model, d_ff, n_experts, top_k, n_part, max_tokens, dtype, n_shared=0, d_ff_shared=0,
+                 expert_lo=0, expert_hi=None, renorm_combine=0) -> ctypes.c_void_p:
+    cfg = _Config(d_model, d_ff, n_experts, top_k, n_part, n_shared, d_ff_shared, expert_lo,
+                  n_experts if expert_hi is None else expert_hi, int(renorm_combine), max_tokens, dtype)
+    out = ctypes.c_void_p()
+    rc = _lib.dsmoe_create(ctypes.byref(cfg), ctypes.byref(out))
+    if rc != 0:
+        raise DsmoeError(rc, "dsmoe_create")
+    return out
+
+
+def dsmoe_destroy(ctx) -> None:
+    _lib.dsmoe_destroy(ctx)
+
+
+def dsmoe_packed_bytes(ctx) -> int:
+    return int(_lib.dsmoe_packed_bytes(ctx))
+
+
+def dsmoe_workspace_bytes(ctx) -> int:
+    return int(_lib.dsmoe_workspace_bytes(ctx))
+
+
+def dsmoe_uses_mfma(ctx) -> bool:
+    return bool(_lib.dsmoe_uses_mfma(ctx))
+
+
+def dsmoe_plan_layout(ctx):
+    out = (ctypes.c_int64 * DSMOE_PLAN_FIELDS)()
+    n = _lib.dsmoe_plan_layout(ctx, out)
+    if n < 0:
+        raise DsmoeError(n, "dsmoe_plan_layout")
+    return [int(v) for v in out]
+
+
+def _check(rc: int, ctx, where: str) -> None:
+    if rc != 0:
+        e = DsmoeError(rc, where)
+        if rc == -4:
+            e.args = (e.args[0] + " hipError=%d" % _lib.dsmoe_last_hip_error(ctx),)
+        raise e
+
+
+def moe_partition_weights(ctx, w1, w3, w2, sh_w1, sh_w3, sh_w2, perm, packed_out, stream=None) -> None:
+    rc = _lib.moe_partition_weights(ctx, _ptr(w1), _ptr(w3), _ptr(w2), _ptr(sh_w1), _ptr(sh_w3), _ptr(sh_w2), _ptr(perm),
+                                    _ptr(packed_out), _stream(stream))
+    _check(rc, ctx, "moe_partition_weights")
+
+
+def moe_route_and_mask(ctx, logits, T, tau, topk_idx, topk_w, keep_bits, group_count, stream=None) -> None:
+    rc = _lib.moe_route_and_mask(ctx, _ptr(logits), int(T), _ptr(tau), _ptr(topk_idx), _ptr(topk_w), _ptr(keep_bits),
+                                 _ptr(group_count), _stream(stream))
+    _check(rc, ctx, "moe_route_and_mask")
+
+
+def moe_dualsparse_forward(ctx, packed, x, logits, tau, T, y, workspace, stream=None) -> None:
+    rc = _lib.moe_dualsparse_forward(ctx, _ptr(packed), _ptr(x), _ptr(logits), _ptr(tau), int(T), _ptr(y), _ptr(workspace),
+                                     _stream(stream))
+    _check(rc, ctx, "moe_dualsparse_forward")
+
+
+class DualSparseLayer:
+    """Owns a context plus its packed-weight and workspace buffers (torch allocations)."""
+
+    def __init__(self, *, d_model, d_ff, n_experts, top_k, n_part, max_tokens, dtype="bf16", n_shared=0, d_ff_shared=0,
+                 expert_lo=0, expert_hi=None, renorm_combine=False, device="cuda:0"):
+        self.device = torch.device(device)
+        self.dtype = dtype
+        self.D, self.F, self.E, self.K, self.P = d_model, d_ff, n_experts, top_k, n_part
+        self.lo, self.hi = expert_lo, (n_experts if expert_hi is None else expert_hi)
+        self.n_shared, self.F_sh = n_shared, d_ff_shared
+        self.max_tokens = max_tokens
+        self.ctx = dsmoe_create(d_model=d_model, d_ff=d_ff, n_experts=n_experts, top_k=top_k, n_part=n_part,
+                                max_tokens=max_tokens, dtype=DSMOE_BF16 if dtype == "bf16" else DSMOE_F32,
+                                n_shared=n_shared, d_ff_shared=d_ff_shared, expert_lo=expert_lo, expert_hi=self.hi,
+                                renorm_combine=int(bool(renorm_combine)))
+        self.packed = torch.empty(dsmoe_packed_bytes(self.ctx), dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(dsmoe_workspace_bytes(self.ctx), dtype=torch.uint8, device=self.device)
+        self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    @property
+    def uses_mfma(self) -> bool:
+        return dsmoe_uses_mfma(self.ctx)
+
+    def partition_weights(self, w1, w3, w2, perm=None, sh_w1=None, sh_w3=None, sh_w2=None) -> None:
+        with torch.cuda.device(self.device):
+            moe_partition_weights(self.ctx, w1, w3, w2, sh_w1, sh_w3, sh_w2, perm, self.packed)
+
+    def route_and_mask(self, logits, tau):
+        T = logits.shape[0]
+        n = max(T * self.K, 1)
+        idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        w = torch.empty(n, dtype=torch.float32, device=self.device)
+        keep = torch.empty(n, dtype=torch.uint8, device=self.device)
+        gc = torch.empty(self.E * self.P, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_route_and_mask(self.ctx, logits, T, tau, idx, w, keep, gc)
+        return idx[:T * self.K].view(T, self.K), w[:T * self.K].view(T, self.K), keep[:T * self.K].view(T, self.K), gc
+
+    def forward(self, x, logits, tau, out=None):
+        T = x.shape[0]
+        y = out if out is not None else torch.empty((T, self.D), dtype=self.torch_dtype, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_dualsparse_forward(self.ctx, self.packed, x, logits, tau, T, y, self.workspace)
+        return y
+
+    def plan(self, T):
+        """Copies of the last forward call's plan arrays (for tests)."""
+        lay = dsmoe_plan_layout(self.ctx)
+        ws = self.workspace
+        n = T * self.K
+        rows = lay[8]
+
+        def view(off, count, dt):
+            nbytes = count * torch.empty(0, dtype=dt).element_size()
+            return ws[off:off + nbytes].view(dt).clone()
+
+        E_res = self.hi - self.lo
+        return {
+            "topk_idx": view(lay[0], n, torch.int32).view(T, self.K),
+            "topk_w": view(lay[1], n, torch.float32).view(T, self.K),
+            "keep_bits": view(lay[2], n, torch.uint8).view(T, self.K),
+            "pair_row": view(lay[3], n, torch.int32).view(T, self.K),
+            "row_token": view(lay[4], rows, torch.int32),
+            "row_bits": view(lay[5], rows, torch.uint8),
+            "expert_nrows": view(lay[6], E_res, torch.int32),
+            "expert_row0": view(lay[7], E_res, torch.int32),
+            "row_cap": rows,
+            "tile_rows": lay[9],
+            "shared_rows": lay[10],
+            "counters": view(lay[11], 4, torch.int32),
+        }
+
+    def close(self) -> None:
+        if self.ctx is not None:
+            dsmoe_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

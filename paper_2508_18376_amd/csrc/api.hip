@@ -1,0 +1,264 @@
+// C ABI of libdsmoe (see include/dsmoe.h): argument checks, workspace / packed-buffer layout and
+// the kernel sequence of each entry point.  No device memory is allocated here.
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+using namespace dsmoe;
+
+namespace {
+
+inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+bool build_layout(const dsmoe_config& c, Layout& L) {
+  memset(&L, 0, sizeof(L));
+  if (c.d_model < 1 || c.d_ff < 1) return false;
+  if (c.n_experts < 1 || c.n_experts > kMaxExperts) return false;
+  if (c.top_k < 1 || c.top_k > c.n_experts || c.top_k > kMaxTopK) return false;
+  if (c.n_part < 1 || c.n_part > kMaxPart || c.d_ff % c.n_part != 0) return false;
+  if (c.n_shared < 0 || (c.n_shared > 0 && c.d_ff_shared < 1)) return false;
+  if (c.expert_lo < 0 || c.expert_hi > c.n_experts || c.expert_lo >= c.expert_hi) return false;
+  if (c.max_tokens < 1) return false;
+  if (c.dtype != DSMOE_F32 && c.dtype != DSMOE_BF16) return false;
+  if (c.renorm_combine != 0 && c.renorm_combine != 1) return false;
+  if ((int64_t)c.max_tokens * c.top_k * c.n_part > (int64_t)1 << 30) return false;
+  if ((int64_t)c.n_shared * c.d_ff_shared > (int64_t)1 << 30) return false;
+
+  L.D = c.d_model;
+  L.F = c.d_ff;
+  L.E = c.n_experts;
+  L.K = c.top_k;
+  L.P = c.n_part;
+  L.Fp = c.d_ff / c.n_part;
+  L.lo = c.expert_lo;
+  L.hi = c.expert_hi;
+  L.E_res = c.expert_hi - c.expert_lo;
+  L.n_shared = c.n_shared;
+  L.F_shT = c.n_shared * c.d_ff_shared;
+  L.renorm = c.renorm_combine;
+  L.dtype = c.dtype;
+  L.max_tokens = c.max_tokens;
+
+  const char* force = getenv("DSMOE_FORCE_GENERIC");
+  L.mfma = (c.dtype == DSMOE_BF16 && L.D % kBK == 0 && L.Fp % kBK == 0 && (L.n_shared == 0 || L.F_shT % kBK == 0) &&
+            (int64_t)c.max_tokens * L.D * 2 < ((int64_t)1 << 31) && !(force && force[0] == '1'))
+               ? 1
+               : 0;
+  const int64_t elem = c.dtype == DSMOE_F32 ? 4 : 2;
+  L.BM = L.mfma ? kMfmaBM : kGenBM;
+  const int neur = L.mfma ? kMfmaNeur : kGenBN;
+  const int bn2 = L.mfma ? kMfmaBN2 : kGenBN;
+  L.NT1 = cdiv(L.Fp, neur);
+  L.NT1_sh = L.n_shared > 0 ? cdiv(L.F_shT, neur) : 0;
+  L.ND2 = cdiv(L.D, bn2);
+  const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
+  L.nsub = 1 << nsub_bits;
+  L.nbins = L.E_res * L.nsub;
+  const int Tm = c.max_tokens;
+  L.sh_rows = L.n_shared > 0 ? (int)align_up(Tm, L.BM) : 0;
+  const int rt = routed_tiles_bound(L, Tm);
+  L.row_cap = L.sh_rows + rt * L.BM;
+  L.max_tiles = rt + shared_tiles(L, Tm);
+  L.max_items1 = rt * L.P * L.NT1 + shared_tiles(L, Tm) * L.NT1_sh;
+  L.max_items2 = L.max_tiles * L.ND2;
+
+  int64_t o = 0;
+  auto take = [&](int64_t bytes) {
+    int64_t at = o;
+    o = align_up(o + bytes, 256);
+    return at;
+  };
+  const int64_t npairs = (int64_t)Tm * L.K;
+  L.o_idx = take(npairs * 4);
+  L.o_w = take(npairs * 4);
+  L.o_keep = take(npairs);
+  L.o_pair_row = take(npairs * 4);
+  L.o_bin_count = take((int64_t)L.nbins * 4);
+  L.o_cursor = take((int64_t)L.nbins * 4);
+  L.o_exp_nrows = take((int64_t)L.E_res * 4);
+  L.o_exp_row0 = take((int64_t)L.E_res * 4);
+  L.o_counters = take(16);
+  L.o_tile_e = take((int64_t)L.max_tiles * 4);
+  L.o_tile_row0 = take((int64_t)L.max_tiles * 4);
+  L.o_tile_nrows = take((int64_t)L.max_tiles * 4);
+  L.o_tile_bits = take((int64_t)L.max_tiles * 4);
+  L.o_act_rank = take((int64_t)L.max_tiles * L.P * 4);
+  L.o_items1 = take((int64_t)L.max_items1 * sizeof(Item1));
+  L.o_items2 = take((int64_t)L.max_items2 * sizeof(Item2));
+  L.o_row_token = take((int64_t)L.row_cap * 4);
+  L.o_row_bits = take((int64_t)L.row_cap);
+  L.o_H = take((int64_t)(L.row_cap - L.sh_rows) * L.F * elem);
+  L.o_Hs = take((int64_t)L.sh_rows * L.F_shT * elem);
+  L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
+  L.ws_bytes = o;
+
+  // packed weights
+  int64_t q = 0;
+  auto takep = [&](int64_t bytes) {
+    int64_t at = q;
+    q = align_up(q + bytes, 256);
+    return at;
+  };
+  if (L.mfma) {
+    const int64_t KS1 = L.D / kBK;
+    L.w13_expert_bytes = (int64_t)L.P * L.NT1 * KS1 * kStageBytes;
+    L.w2_expert_bytes = (int64_t)L.ND2 * (L.F / kBK) * kStageBytes;
+    L.p_w13 = takep(L.w13_expert_bytes * L.E_res);
+    L.p_w2 = takep(L.w2_expert_bytes * L.E_res);
+    L.p_sw13 = takep((int64_t)L.NT1_sh * KS1 * kStageBytes);
+    L.p_sw2 = takep(L.n_shared > 0 ? (int64_t)L.ND2 * (L.F_shT / kBK) * kStageBytes : 0);
+  } else {
+    L.w13_expert_bytes = (int64_t)L.D * L.F * elem;
+    L.w2_expert_bytes = (int64_t)L.F * L.D * elem;
+    L.p_w13 = takep(2 * L.w13_expert_bytes * L.E_res);
+    L.p_w2 = takep(L.w2_expert_bytes * L.E_res);
+    L.p_sw13 = takep(2 * (int64_t)L.D * L.F_shT * elem);
+    L.p_sw2 = takep((int64_t)L.F_shT * L.D * elem);
+  }
+  // the permutation check borrows the start of the packed buffer for its counters
+  const int64_t need_check = ((int64_t)L.E_res * L.F + 1) * 4;
+  if (q < need_check) q = align_up(need_check, 256);
+  L.packed_bytes = q;
+  return true;
+}
+
+inline int hip_fail(Ctx* ctx, hipError_t e) {
+  ctx->last_hip = (int)e;
+  return DSMOE_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dsmoe_create(const dsmoe_config* cfg, dsmoe_ctx** out) {
+  if (!cfg || !out) return DSMOE_EINVAL;
+  *out = nullptr;
+  Ctx* c = new (std::nothrow) Ctx();
+  if (!c) return DSMOE_EINVAL;
+  c->cfg = *cfg;
+  c->last_hip = 0;
+  if (!build_layout(*cfg, c->L)) {
+    delete c;
+    return DSMOE_EINVAL;
+  }
+  *out = reinterpret_cast<dsmoe_ctx*>(c);
+  return DSMOE_OK;
+}
+
+int dsmoe_destroy(dsmoe_ctx* ctx) {
+  if (!ctx) return DSMOE_EINVAL;
+  delete reinterpret_cast<Ctx*>(ctx);
+  return DSMOE_OK;
+}
+
+size_t dsmoe_packed_bytes(const dsmoe_ctx* ctx) { return ctx ? (size_t) reinterpret_cast<const Ctx*>(ctx)->L.packed_bytes : 0; }
+size_t dsmoe_workspace_bytes(const dsmoe_ctx* ctx) { return ctx ? (size_t) reinterpret_cast<const Ctx*>(ctx)->L.ws_bytes : 0; }
+int dsmoe_last_hip_error(const dsmoe_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->last_hip : 0; }
+int dsmoe_uses_mfma(const dsmoe_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->L.mfma : 0; }
+
+const char* dsmoe_strerror(int status) {
+  switch (status) {
+    case DSMOE_OK: return "ok";
+    case DSMOE_EINVAL: return "invalid argument (shape, divisibility, limit, null pointer or T > max_tokens)";
+    case DSMOE_EPERM: return "perm is not a permutation of the expert's neurons";
+    case DSMOE_ENOSPC: return "workspace too small";
+    case DSMOE_EHIP: return "HIP call or kernel launch failed";
+    default: return "unknown dsmoe status";
+  }
+}
+
+int moe_partition_weights(dsmoe_ctx* ctx_, const void* w1, const void* w3, const void* w2, const void* sh_w1,
+                          const void* sh_w3, const void* sh_w2, const int32_t* perm, void* packed_out, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || !w1 || !w3 || !w2 || !packed_out) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  if (L.n_shared > 0 && (!sh_w1 || !sh_w3 || !sh_w2)) return DSMOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t err;
+  if (perm) {
+    int32_t* scratch = (int32_t*)packed_out;
+    err = launch_perm_check(L, perm, scratch, s);
+    if (err != hipSuccess) return hip_fail(ctx, err);
+    int32_t bad = 0;
+    err = hipMemcpyAsync(&bad, scratch + (size_t)L.E_res * L.F, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+    if (err != hipSuccess) return hip_fail(ctx, err);
+    err = hipStreamSynchronize(s);
+    if (err != hipSuccess) return hip_fail(ctx, err);
+    if (bad != 0) return DSMOE_EPERM;
+  }
+  err = launch_pack(L, w1, w3, w2, sh_w1, sh_w3, sh_w2, perm, (char*)packed_out, ctx->cfg.n_shared, ctx->cfg.d_ff_shared, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = hipStreamSynchronize(s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_route_and_mask(dsmoe_ctx* ctx_, const float* logits, int32_t T, const float* tau, int32_t* topk_idx, float* topk_w,
+                       uint8_t* keep_bits, int32_t* group_count, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !tau || !group_count) return DSMOE_EINVAL;
+  if (T > 0 && (!logits || !topk_idx || !topk_w || !keep_bits)) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  if (T > L.max_tokens) return DSMOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t err = launch_fill_i32(group_count, (int64_t)L.E * L.P, 0, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = launch_route(L, logits, T, tau, topk_idx, topk_w, keep_bits, nullptr, group_count, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, const float* logits, const float* tau,
+                           int32_t T, void* y, void* workspace, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !packed || !tau || !workspace) return DSMOE_EINVAL;
+  if (T > 0 && (!x || !logits || !y)) return DSMOE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  if (T > L.max_tokens) return DSMOE_EINVAL;
+  if (T == 0) return DSMOE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  hipError_t err;
+  // bin_count and cursor are adjacent: one fill clears both
+  err = launch_fill_i32((int32_t*)(ws + L.o_bin_count), (L.o_exp_nrows - L.o_bin_count) / 4, 0, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = launch_route(L, logits, T, tau, (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w), (uint8_t*)(ws + L.o_keep),
+                     (int32_t*)(ws + L.o_bin_count), nullptr, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = launch_plan(L, T, ws, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = launch_scatter(L, T, ws, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = L.mfma ? launch_gemm_mfma(L, T, (const char*)packed, x, ws, s) : launch_gemm_generic(L, T, (const char*)packed, x, ws, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  err = launch_combine(L, T, ws, y, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int dsmoe_plan_layout(const dsmoe_ctx* ctx_, int64_t* out) {
+  const Ctx* ctx = reinterpret_cast<const Ctx*>(ctx_);
+  if (!ctx || !out) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  out[0] = L.o_idx;
+  out[1] = L.o_w;
+  out[2] = L.o_keep;
+  out[3] = L.o_pair_row;
+  out[4] = L.o_row_token;
+  out[5] = L.o_row_bits;
+  out[6] = L.o_exp_nrows;
+  out[7] = L.o_exp_row0;
+  out[8] = L.row_cap;
+  out[9] = L.BM;
+  out[10] = L.sh_rows;
+  out[11] = L.o_counters;
+  return DSMOE_PLAN_FIELDS;
+}
+
+}  // extern "C"

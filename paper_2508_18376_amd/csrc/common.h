@@ -1,0 +1,102 @@
+// Internal declarations shared by the translation units of libdsmoe (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dsmoe.h"
+
+namespace dsmoe {
+
+constexpr int kMaxTopK = 16;
+constexpr int kMaxExperts = 512;
+constexpr int kMaxPart = 8;
+constexpr int kSubBits = 4;  // partitions that take part in the row sort key
+
+// MFMA path tile shape: 256 rows (token-expert pairs) x 128 neurons (gate+up = 256 weight rows)
+// for GEMM-1, 256 rows x 256 output columns for GEMM-2, K step 64.
+constexpr int kMfmaBM = 256;
+constexpr int kMfmaNeur = 128;
+constexpr int kMfmaBN2 = 256;
+constexpr int kBK = 64;
+constexpr int kStageBytes = 256 * kBK * 2;  // one operand tile of one K step (bf16)
+
+// generic path tile shape
+constexpr int kGenBM = 64;
+constexpr int kGenBN = 64;
+
+struct Item1 {  // one tile of GEMM-1: rows [row0, row0+nrows) x neurons tile jt of partition p
+  int32_t row0, nrows, e, p, jt, pad0, pad1, pad2;
+};
+struct Item2 {  // one tile of GEMM-2: rows x output column tile jd, summed over partitions in kmask
+  int32_t row0, nrows, e, jd, kmask, pad0, pad1, pad2;
+};
+
+// Everything the device code needs to know about the layer and the workspace.
+struct Layout {
+  // layer
+  int32_t D, F, E, K, P, Fp;
+  int32_t lo, hi, E_res;      // resident window
+  int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
+  int32_t renorm, dtype, mfma;
+  int32_t max_tokens;
+  // plan geometry
+  int32_t BM;                 // row tile height
+  int32_t NT1, NT1_sh;        // neuron tiles per partition (routed / shared)
+  int32_t ND2;                // output column tiles of GEMM-2
+  int32_t nsub, nbins;        // sort bins: E_res * nsub
+  int32_t sh_rows;            // rows reserved for the shared region (multiple of BM), first in the row space
+  int32_t row_cap;            // total row capacity
+  int32_t max_tiles, max_items1, max_items2;
+  // workspace byte offsets
+  int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
+  int64_t o_tile_e, o_tile_row0, o_tile_nrows, o_tile_bits, o_act_rank, o_items1, o_items2;
+  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, ws_bytes;
+  // packed weights byte offsets
+  int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes;
+  int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
+};
+
+struct Ctx {
+  dsmoe_config cfg;
+  Layout L;
+  int last_hip;
+};
+
+// upper bounds of the plan sizes for a call with T tokens (the exact sizes only exist on the device)
+inline int routed_tiles_bound(const Layout& L, int T) { return (int)(((int64_t)T * L.K) / L.BM) + L.E_res; }
+inline int shared_tiles(const Layout& L, int T) { return L.n_shared > 0 ? (T + L.BM - 1) / L.BM : 0; }
+inline int items1_bound(const Layout& L, int T) {
+  return routed_tiles_bound(L, T) * L.P * L.NT1 + shared_tiles(L, T) * L.NT1_sh;
+}
+inline int items2_bound(const Layout& L, int T) { return (routed_tiles_bound(L, T) + shared_tiles(L, T)) * L.ND2; }
+
+// launchers (each returns hipError_t of the launch)
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);
+hipError_t launch_route(const Layout& L, const float* logits, int T, const float* tau, int32_t* idx, float* w,
+                        uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s);
+hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s);
+hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s);
+hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s);
+hipError_t launch_gemm_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+hipError_t launch_gemm_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const void* w2, const void* sw1, const void* sw3,
+                       const void* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh, hipStream_t s);
+hipError_t launch_perm_check(const Layout& L, const int32_t* perm, int32_t* scratch, hipStream_t s);
+
+// ---- device helpers ---------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest, ties to even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float silu_f32(float a) { return a / (1.0f + expf(-a)); }       // Swish, beta = 1
+__device__ __forceinline__ float silu_fast(float a) { return a / (1.0f + __expf(-a)); }
+
+// Position of the 16-byte chunk `chunk` (0..7) of row `row` inside a [rows][64] bf16 LDS tile.
+// Chunks of a row are rotated by an XOR so that MFMA operand reads (32 rows, same logical chunk)
+// spread over all LDS banks.
+__device__ __host__ __forceinline__ int swz_chunk(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+}  // namespace dsmoe

@@ -1,0 +1,190 @@
+// moe_partition_weights kernels: neuron reorder through perm (Sec. 4.2 b), even split into P
+// sub-experts with no W2 scaling (Sec. 3.2), written in the layout the GEMM kernels read.
+//
+// Generic layout (element type = layer dtype):
+//   W1g, W3g [E_res][D][F], W2g [E_res][F][D] with neuron axis in permuted order;
+//   shared experts concatenated along the neuron axis: SW1g, SW3g [D][F_shT], SW2g [F_shT][D].
+// MFMA layout (bf16): 32 KiB "stage images", each the exact LDS contents of one operand tile of
+//   one K step, rows of 64 K-values with the 16-byte chunks XOR-rotated (swz_chunk):
+//   W13  stage ((e*P + p)*NT1 + jt)*(D/64) + ks : 256 weight rows x 64 values of d; weight row
+//        wm*128 + gu*64 + j  is neuron  p*Fp + jt*128 + wm*64 + j  of W1 (gu=0) or W3 (gu=1)
+//   W2   stage (e*ND2 + jd)*(F/64) + kt : 256 output columns x 64 neurons (positions kt*64..)
+//   neurons / columns past the end are zero.
+#include "common.h"
+
+namespace dsmoe {
+
+template <typename T>
+__global__ void pack_generic_kernel(Layout L, const T* w1, const T* w3, const T* w2, const T* sw1, const T* sw3,
+                                    const T* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh) {
+  const int64_t nW = (int64_t)L.E_res * L.D * L.F;
+  const int64_t nS = (int64_t)L.D * L.F_shT;
+  const int64_t total = 3 * nW + 3 * nS;
+  T* W1g = (T*)(packed + L.p_w13);
+  T* W3g = W1g + nW;
+  T* W2g = (T*)(packed + L.p_w2);
+  T* S1g = (T*)(packed + L.p_sw13);
+  T* S3g = S1g + nS;
+  T* S2g = (T*)(packed + L.p_sw2);
+  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
+    if (q < 2 * nW) {
+      const bool up = q >= nW;
+      int64_t r = up ? q - nW : q;
+      int j = (int)(r % L.F);
+      int64_t ed = r / L.F;  // e*D + d
+      int e = (int)(ed / L.D);
+      int src = perm ? perm[(size_t)e * L.F + j] : j;
+      (up ? W3g : W1g)[r] = (up ? w3 : w1)[ed * L.F + src];
+    } else if (q < 3 * nW) {
+      int64_t r = q - 2 * nW;
+      int d = (int)(r % L.D);
+      int64_t ej = r / L.D;  // e*F + j
+      int e = (int)(ej / L.F), j = (int)(ej % L.F);
+      int src = perm ? perm[(size_t)e * L.F + j] : j;
+      W2g[r] = w2[((size_t)e * L.F + src) * L.D + d];
+    } else if (q < 3 * nW + 2 * nS) {
+      int64_t r = q - 3 * nW;
+      const bool up = r >= nS;
+      if (up) r -= nS;
+      int c = (int)(r % L.F_shT);
+      int d = (int)(r / L.F_shT);
+      int s = c / F_sh, n = c % F_sh;
+      (up ? S3g : S1g)[r] = (up ? sw3 : sw1)[((size_t)s * L.D + d) * F_sh + n];
+    } else {
+      int64_t r = q - 3 * nW - 2 * nS;
+      int d = (int)(r % L.D);
+      int c = (int)(r / L.D);
+      int s = c / F_sh, n = c % F_sh;
+      S2g[r] = sw2[((size_t)s * F_sh + n) * L.D + d];
+    }
+  }
+}
+
+// One thread per 16-byte chunk of the packed MFMA buffers.
+__global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w3, const uint16_t* w2,
+                                 const uint16_t* sw1, const uint16_t* sw3, const uint16_t* sw2, const int32_t* perm,
+                                 char* packed, int n_shared, int F_sh) {
+  const int KS1 = L.D / kBK;
+  const int64_t chunks_per_stage = kStageBytes / 16;  // 2048
+  const int64_t st13 = (int64_t)L.E_res * L.P * L.NT1 * KS1;
+  const int64_t st2 = (int64_t)L.E_res * L.ND2 * (L.F / kBK);
+  const int64_t sts13 = (int64_t)(n_shared > 0 ? L.NT1_sh * KS1 : 0);
+  const int64_t sts2 = (int64_t)(n_shared > 0 ? L.ND2 * (L.F_shT / kBK) : 0);
+  const int64_t total = (st13 + st2 + sts13 + sts2) * chunks_per_stage;
+  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
+    int64_t stage = q / chunks_per_stage;
+    int c = (int)(q % chunks_per_stage);
+    const int row = c >> 3, pc = c & 7;
+    const int lc = swz_chunk(row, pc);  // XOR rotation is its own inverse
+    uint16_t v[8];
+    char* dst;
+    if (stage < st13 + sts13) {
+      const bool sh = stage >= st13;
+      if (sh) stage -= st13;
+      const int ks = (int)(stage % KS1);
+      int64_t r = stage / KS1;
+      const int nt1 = sh ? L.NT1_sh : L.NT1;
+      const int jt = (int)(r % nt1);
+      r /= nt1;
+      const int p = sh ? 0 : (int)(r % L.P);
+      const int e = sh ? 0 : (int)(r / L.P);
+      const int wm = row >> 7, gu = (row >> 6) & 1, j = row & 63;
+      const int Fp = sh ? L.F_shT : L.Fp;
+      const int nin = jt * kMfmaNeur + wm * 64 + j;  // neuron inside the partition
+      const int d0 = ks * kBK + lc * 8;
+      if (nin < Fp) {
+        if (!sh) {
+          const int pos = p * Fp + nin;
+          const int src = perm ? perm[(size_t)e * L.F + pos] : pos;
+          const uint16_t* w = gu ? w3 : w1;
+          for (int i = 0; i < 8; ++i) v[i] = w[((size_t)e * L.D + d0 + i) * L.F + src];
+        } else {
+          const int s = nin / F_sh, n = nin % F_sh;
+          const uint16_t* w = gu ? sw3 : sw1;
+          for (int i = 0; i < 8; ++i) v[i] = w[((size_t)s * L.D + d0 + i) * F_sh + n];
+        }
+      } else {
+        for (int i = 0; i < 8; ++i) v[i] = 0;
+      }
+      const int64_t sidx = sh ? ((int64_t)jt * KS1 + ks) : ((((int64_t)e * L.P + p) * L.NT1 + jt) * KS1 + ks);
+      dst = packed + (sh ? L.p_sw13 : L.p_w13) + sidx * kStageBytes + (int64_t)c * 16;
+    } else {
+      stage -= st13 + sts13;
+      const bool sh = stage >= st2;
+      if (sh) stage -= st2;
+      const int KT = (sh ? L.F_shT : L.F) / kBK;
+      const int kt = (int)(stage % KT);
+      int64_t r = stage / KT;
+      const int jd = (int)(r % L.ND2);
+      const int e = sh ? 0 : (int)(r / L.ND2);
+      const int d = jd * kMfmaBN2 + row;
+      const int pos0 = kt * kBK + lc * 8;
+      if (d < L.D) {
+        for (int i = 0; i < 8; ++i) {
+          const int pos = pos0 + i;
+          if (!sh) {
+            const int src = perm ? perm[(size_t)e * L.F + pos] : pos;
+            v[i] = w2[((size_t)e * L.F + src) * L.D + d];
+          } else {
+            const int s = pos / F_sh, n = pos % F_sh;
+            v[i] = sw2[((size_t)s * F_sh + n) * L.D + d];
+          }
+        }
+      } else {
+        for (int i = 0; i < 8; ++i) v[i] = 0;
+      }
+      const int64_t sidx = sh ? ((int64_t)jd * KT + kt) : (((int64_t)e * L.ND2 + jd) * KT + kt);
+      dst = packed + (sh ? L.p_sw2 : L.p_w2) + sidx * kStageBytes + (int64_t)c * 16;
+    }
+    uint4 o;
+    o.x = v[0] | ((uint32_t)v[1] << 16);
+    o.y = v[2] | ((uint32_t)v[3] << 16);
+    o.z = v[4] | ((uint32_t)v[5] << 16);
+    o.w = v[6] | ((uint32_t)v[7] << 16);
+    *(uint4*)dst = o;
+  }
+}
+
+hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const void* w2, const void* sw1, const void* sw3,
+                       const void* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh, hipStream_t s) {
+  dim3 block(256), grid(256 * 64);
+  if (L.mfma) {
+    pack_mfma_kernel<<<grid, block, 0, s>>>(L, (const uint16_t*)w1, (const uint16_t*)w3, (const uint16_t*)w2,
+                                            (const uint16_t*)sw1, (const uint16_t*)sw3, (const uint16_t*)sw2, perm, packed,
+                                            n_shared, F_sh > 0 ? F_sh : 1);
+  } else if (L.dtype == DSMOE_F32) {
+    pack_generic_kernel<float><<<grid, block, 0, s>>>(L, (const float*)w1, (const float*)w3, (const float*)w2,
+                                                      (const float*)sw1, (const float*)sw3, (const float*)sw2, perm, packed,
+                                                      n_shared, F_sh > 0 ? F_sh : 1);
+  } else {
+    pack_generic_kernel<uint16_t><<<grid, block, 0, s>>>(L, (const uint16_t*)w1, (const uint16_t*)w3, (const uint16_t*)w2,
+                                                         (const uint16_t*)sw1, (const uint16_t*)sw3, (const uint16_t*)sw2,
+                                                         perm, packed, n_shared, F_sh > 0 ? F_sh : 1);
+  }
+  return hipGetLastError();
+}
+
+// perm check: scratch[0 .. E_res*F) counts how often each neuron id is named (zeroed by the
+// caller), scratch[E_res*F] counts violations (out of range or named twice).
+__global__ void perm_check_kernel(Layout L, const int32_t* perm, int32_t* scratch) {
+  const int64_t n = (int64_t)L.E_res * L.F;
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n) return;
+  const int e = (int)(q / L.F);
+  const int v = perm[q];
+  if (v < 0 || v >= L.F) {
+    atomicAdd(&scratch[n], 1);
+  } else if (atomicAdd(&scratch[(size_t)e * L.F + v], 1) != 0) {
+    atomicAdd(&scratch[n], 1);
+  }
+}
+
+hipError_t launch_perm_check(const Layout& L, const int32_t* perm, int32_t* scratch, hipStream_t s) {
+  const int64_t n = (int64_t)L.E_res * L.F;
+  hipError_t err = launch_fill_i32(scratch, n + 1, 0, s);
+  if (err != hipSuccess) return err;
+  perm_check_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(L, perm, scratch);
+  return hipGetLastError();
+}
+
+}  // namespace dsmoe

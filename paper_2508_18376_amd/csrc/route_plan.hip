@@ -1,0 +1,580 @@
+// Gating + drop mask, row-list construction (histogram, scan, scatter) and the combine kernel.
+//
+// Gating follows Eq. 1-2 of the paper (softmax over all E logits, Top-K), the mask follows
+// Sec. 4.1 / 4.2 c (normalise the K selected scores, keep unit (t,k,p) iff n >= tau[e][p]).
+// The row lists realise the index remap of Sec. 3.2 without materialising K*P lists: the pairs of
+// one expert are sorted by their keep pattern, so the rows that need sub-expert p are (for
+// thresholds that grow with p) a prefix of the expert's list.
+#include "common.h"
+
+namespace dsmoe {
+
+// ------------------------------------------------------------------------------------- fill
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, n, v);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------- route
+struct RouteArgs {
+  const float* logits;
+  const float* tau;
+  int32_t* idx;
+  float* w;
+  uint8_t* keep;
+  int32_t* bin_count;    // forward: [nbins] sort-bin histogram (may be null)
+  int32_t* group_count;  // stand-alone: [E*P] kept units per sub-expert (may be null)
+  int T, E, K, P, lo, hi, renorm, nsub_bits, nsub, nhist;
+};
+
+// sort bin of a keep pattern inside its expert: patterns that keep the major partitions come first
+__device__ __forceinline__ int sub_of_bits(int bits, int nsub_bits) {
+  int rev = 0;
+  for (int p = 0; p < nsub_bits; ++p) rev |= ((bits >> p) & 1) << (nsub_bits - 1 - p);
+  return (1 << nsub_bits) - 1 - rev;
+}
+
+__device__ __forceinline__ int keep_bits_of(float n, int e, const RouteArgs& a) {
+  int bits = 0;
+  if (e >= a.lo && e < a.hi) {
+    for (int p = 0; p < a.P; ++p) bits |= (n >= a.tau[e * a.P + p] ? 1 : 0) << p;
+  }
+  return bits;
+}
+
+// histogram update of one pair into the block's LDS histogram
+__device__ __forceinline__ void count_pair(int32_t* hist, int bits, int e, const RouteArgs& a) {
+  if (bits == 0) return;
+  if (a.bin_count) atomicAdd(&hist[(e - a.lo) * a.nsub + sub_of_bits(bits, a.nsub_bits)], 1);
+  if (a.group_count) {
+    int32_t* h2 = hist + (a.bin_count ? (a.hi - a.lo) * a.nsub : 0);
+    for (int p = 0; p < a.P; ++p)
+      if ((bits >> p) & 1) atomicAdd(&h2[e * a.P + p], 1);
+  }
+}
+
+// One lane per token; all E logits of the token live in that lane's registers (E <= EPAD <= 64).
+template <int EPAD, int KMAX>
+__global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
+  extern __shared__ int32_t hist[];
+  for (int i = threadIdx.x; i < a.nhist; i += 64) hist[i] = 0;
+  __syncthreads();
+  const int t = blockIdx.x * 64 + threadIdx.x;
+  if (t < a.T) {
+    float l[EPAD];
+#pragma unroll
+    for (int e = 0; e < EPAD; ++e) l[e] = (e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
+    float m = l[0];
+#pragma unroll
+    for (int e = 1; e < EPAD; ++e) m = (e < a.E && l[e] > m) ? l[e] : m;
+    float z = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPAD; ++e)
+      if (e < a.E) z += expf(l[e] - m);
+    // Top-K: K rounds of "largest not yet taken"; a later index wins only if strictly larger.
+    float sk[KMAX];
+    int ik[KMAX];
+    unsigned long long taken = 0ull;
+    float sel = 0.f;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      sk[k] = 0.f;
+      ik[k] = 0;
+      if (k < a.K) {
+        float bv = 0.f;
+        int be = -1;
+#pragma unroll
+        for (int e = 0; e < EPAD; ++e) {
+          bool free_e = (e < a.E) && !((taken >> e) & 1ull);
+          if (free_e && (be < 0 || l[e] > bv)) {
+            bv = l[e];
+            be = e;
+          }
+        }
+        taken |= 1ull << be;
+        ik[k] = be;
+        sk[k] = expf(bv - m) / z;  // Eq. 1
+        sel += sk[k];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      if (k < a.K) {
+        float n = sk[k] / sel;  // Sec. 4.1: normalise over the K selected
+        int bits = keep_bits_of(n, ik[k], a);
+        size_t o = (size_t)t * a.K + k;
+        a.idx[o] = ik[k];
+        a.w[o] = a.renorm ? n : sk[k];
+        a.keep[o] = (uint8_t)bits;
+        count_pair(hist, bits, ik[k], a);
+      }
+    }
+  }
+  __syncthreads();
+  const int nb = a.bin_count ? (a.hi - a.lo) * a.nsub : 0;
+  for (int i = threadIdx.x; i < a.nhist; i += 64) {
+    int c = hist[i];
+    if (c) {
+      if (i < nb) atomicAdd(&a.bin_count[i], c);
+      else atomicAdd(&a.group_count[i - nb], c);
+    }
+  }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// One wavefront per token, LPT logits per lane (64 < E <= 64*LPT).  Every logit gets its rank
+// under (value descending, index ascending); ranks below K are the selected slots.
+template <int LPT>
+__global__ __launch_bounds__(64) void route_wave_kernel(RouteArgs a) {
+  const int t = blockIdx.x;
+  const int lane = threadIdx.x;
+  float l[LPT];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    int e = lane + 64 * i;
+    l[i] = (e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
+  }
+  float m = l[0];
+#pragma unroll
+  for (int i = 1; i < LPT; ++i) m = fmaxf(m, l[i]);
+  m = wave_max(m);
+  float z = 0.f;
+#pragma unroll
+  for (int i = 0; i < LPT; ++i)
+    if (lane + 64 * i < a.E) z += expf(l[i] - m);
+  z = wave_sum(z);
+  int rank[LPT];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) rank[i] = 0;
+  for (int j = 0; j < 64; ++j) {
+#pragma unroll
+    for (int i2 = 0; i2 < LPT; ++i2) {
+      float ov = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l[i2]), j));
+      int oe = j + 64 * i2;
+      if (oe < a.E) {
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+          int e = lane + 64 * i;
+          rank[i] += (ov > l[i] || (ov == l[i] && oe < e)) ? 1 : 0;
+        }
+      }
+    }
+  }
+  float ssum = 0.f;
+  float s[LPT];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    bool selq = (lane + 64 * i < a.E) && rank[i] < a.K;
+    s[i] = selq ? expf(l[i] - m) / z : 0.f;
+    ssum += s[i];
+  }
+  ssum = wave_sum(ssum);
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    int e = lane + 64 * i;
+    if (e < a.E && rank[i] < a.K) {
+      float n = s[i] / ssum;
+      int bits = keep_bits_of(n, e, a);
+      size_t o = (size_t)t * a.K + rank[i];
+      a.idx[o] = e;
+      a.w[o] = a.renorm ? n : s[i];
+      a.keep[o] = (uint8_t)bits;
+      if (bits) {
+        if (a.bin_count) atomicAdd(&a.bin_count[(e - a.lo) * a.nsub + sub_of_bits(bits, a.nsub_bits)], 1);
+        if (a.group_count)
+          for (int p = 0; p < a.P; ++p)
+            if ((bits >> p) & 1) atomicAdd(&a.group_count[e * a.P + p], 1);
+      }
+    }
+  }
+}
+
+hipError_t launch_route(const Layout& L, const float* logits, int T, const float* tau, int32_t* idx, float* w,
+                        uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  RouteArgs a;
+  a.logits = logits;
+  a.tau = tau;
+  a.idx = idx;
+  a.w = w;
+  a.keep = keep;
+  a.bin_count = bin_count;
+  a.group_count = group_count;
+  a.T = T;
+  a.E = L.E;
+  a.K = L.K;
+  a.P = L.P;
+  a.lo = L.lo;
+  a.hi = L.hi;
+  a.renorm = L.renorm;
+  a.nsub = L.nsub;
+  a.nsub_bits = L.P < kSubBits ? L.P : kSubBits;
+  a.nhist = (bin_count ? L.nbins : 0) + (group_count ? L.E * L.P : 0);
+  if (L.E <= 64) {
+    dim3 grid((T + 63) / 64), block(64);
+    size_t sh = sizeof(int32_t) * (size_t)(a.nhist > 0 ? a.nhist : 1);
+    if (L.E <= 8) route_lane_kernel<8, 8><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 16) route_lane_kernel<16, 16><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 32) route_lane_kernel<32, 16><<<grid, block, sh, s>>>(a);
+    else route_lane_kernel<64, 16><<<grid, block, sh, s>>>(a);
+  } else {
+    dim3 grid(T), block(64);
+    if (L.E <= 128) route_wave_kernel<2><<<grid, block, 0, s>>>(a);
+    else if (L.E <= 256) route_wave_kernel<4><<<grid, block, 0, s>>>(a);
+    else route_wave_kernel<8><<<grid, block, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------- plan
+// Single-workgroup kernel: turns the bin histogram into row offsets, the row-tile table and the
+// two work lists of the grouped GEMMs.  Everything stays on the device: the GEMM grids are sized
+// for the worst case and read their item count from the counters this kernel writes.
+constexpr int kPlanThreads = 1024;
+
+// exclusive scan of a[0..n) in LDS (n <= 8 * kPlanThreads); returns the total. tmp: kPlanThreads ints.
+__device__ int block_excl_scan(int32_t* a, int n, int32_t* tmp) {
+  const int tid = threadIdx.x;
+  const int per = (n + kPlanThreads - 1) / kPlanThreads;
+  int lo = tid * per, hi = min(n, lo + per);
+  int sum = 0;
+  for (int i = lo; i < hi; ++i) sum += a[i];
+  tmp[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < kPlanThreads; off <<= 1) {
+    int v = (tid >= off) ? tmp[tid - off] : 0;
+    __syncthreads();
+    tmp[tid] += v;
+    __syncthreads();
+  }
+  int total = tmp[kPlanThreads - 1];
+  int run = tmp[tid] - sum;
+  for (int i = lo; i < hi; ++i) {
+    int v = a[i];
+    a[i] = run;
+    run += v;
+  }
+  __syncthreads();
+  return total;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, char* ws) {
+  extern __shared__ int32_t sm[];
+  const int tid = threadIdx.x;
+  const int E_res = L.E_res;
+  const int has_sh = L.n_shared > 0 ? 1 : 0;
+  const int E_tot = E_res + has_sh;
+  const int NG = E_tot * L.P;  // (expert, partition) groups; the shared pseudo-expert only uses p = 0
+  int32_t* ne = sm;                 // [E_tot] rows of each expert
+  int32_t* rs = ne + E_tot + 1;     // [E_tot] first row (tile aligned)
+  int32_t* ts = rs + E_tot + 1;     // [E_tot] first tile
+  int32_t* pt = ts + E_tot + 1;     // [E_tot+1] first tile by POSITION in the row space
+  int32_t* ga = pt + E_tot + 2;     // [NG] active tiles of each group
+  int32_t* gb = ga + NG + 1;        // [NG+1] item base of each group
+  int32_t* tmp = gb + NG + 1;       // [kPlanThreads]
+
+  const int32_t* bin_count = (const int32_t*)(ws + L.o_bin_count);
+  int32_t* cursor = (int32_t*)(ws + L.o_cursor);
+  int32_t* exp_nrows = (int32_t*)(ws + L.o_exp_nrows);
+  int32_t* exp_row0 = (int32_t*)(ws + L.o_exp_row0);
+  int32_t* counters = (int32_t*)(ws + L.o_counters);
+  int32_t* tile_e = (int32_t*)(ws + L.o_tile_e);
+  int32_t* tile_row0 = (int32_t*)(ws + L.o_tile_row0);
+  int32_t* tile_nrows = (int32_t*)(ws + L.o_tile_nrows);
+  int32_t* tile_bits = (int32_t*)(ws + L.o_tile_bits);
+  int32_t* act_rank = (int32_t*)(ws + L.o_act_rank);
+  Item1* items1 = (Item1*)(ws + L.o_items1);
+  Item2* items2 = (Item2*)(ws + L.o_items2);
+  const int BM = L.BM;
+  const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
+
+  // 1. rows per expert.  Order of the experts in the row space: the shared pseudo-expert first
+  //    (its size is known without the histogram), then the resident experts by id.
+  //    position i -> expert: with shared experts, position 0 is id E_res and position i is id i-1.
+  for (int e = tid; e < E_tot; e += kPlanThreads) {
+    int n = 0;
+    if (e < E_res)
+      for (int sb = 0; sb < L.nsub; ++sb) n += bin_count[e * L.nsub + sb];
+    else
+      n = T;
+    ne[e] = n;
+  }
+  __syncthreads();
+  // 2. tile-aligned row starts: exclusive scan of the tile counts in position order
+  for (int i = tid; i < E_tot; i += kPlanThreads) {
+    int e = has_sh ? (i == 0 ? E_res : i - 1) : i;
+    pt[i] = (ne[e] + BM - 1) / BM;
+  }
+  __syncthreads();
+  const int total_tiles = block_excl_scan(pt, E_tot, tmp);
+  if (tid == 0) pt[E_tot] = total_tiles;
+  for (int i = tid; i < E_tot; i += kPlanThreads) {
+    int e = has_sh ? (i == 0 ? E_res : i - 1) : i;
+    ts[e] = pt[i];
+    rs[e] = pt[i] * BM;
+  }
+  __syncthreads();
+  for (int e = tid; e < E_res; e += kPlanThreads) {
+    exp_nrows[e] = ne[e];
+    exp_row0[e] = rs[e];
+  }
+  // 3. first row of every bin; the scatter kernel's cursors start there
+  for (int b = tid; b < L.nbins; b += kPlanThreads) {
+    int e = b / L.nsub, sb = b % L.nsub;
+    int off = rs[e];
+    for (int s2 = 0; s2 < sb; ++s2) off += bin_count[e * L.nsub + s2];
+    cursor[b] = off;
+  }
+  // 4. row tiles; tile g belongs to the expert at the last position whose first tile is <= g
+  for (int g = tid; g < total_tiles; g += kPlanThreads) {
+    int lo_i = 0, hi_i = E_tot;  // first position with pt > g
+    while (lo_i < hi_i) {
+      int mid = (lo_i + hi_i) >> 1;
+      if (pt[mid] > g) hi_i = mid;
+      else lo_i = mid + 1;
+    }
+    const int pos = lo_i - 1;
+    const int e = has_sh ? (pos == 0 ? E_res : pos - 1) : pos;
+    const int i = g - ts[e];
+    const int r0 = i * BM, r1 = min(ne[e], r0 + BM);
+    int bits = 0;
+    if (e < E_res) {
+      int off = 0;
+      for (int sb = 0; sb < L.nsub; ++sb) {
+        int c = bin_count[e * L.nsub + sb];
+        if (c > 0 && off < r1 && off + c > r0) {
+          int rev = L.nsub - 1 - sb;
+          int pat = 0;
+          for (int p = 0; p < nsub_bits; ++p) pat |= ((rev >> (nsub_bits - 1 - p)) & 1) << p;
+          if (L.P > nsub_bits) pat |= ((1 << L.P) - 1) & ~((1 << nsub_bits) - 1);  // partitions outside the sort key: assume kept
+          bits |= pat;
+        }
+        off += c;
+      }
+    } else {
+      bits = 1;
+    }
+    tile_e[g] = e;
+    tile_row0[g] = rs[e] + r0;
+    tile_nrows[g] = r1 - r0;
+    tile_bits[g] = bits;
+  }
+  __syncthreads();
+  // 5. GEMM-2 items: every tile x every output column tile, column tiles innermost
+  for (int it = tid; it < total_tiles * L.ND2; it += kPlanThreads) {
+    int g = it / L.ND2, jd = it % L.ND2;
+    Item2 v;
+    v.row0 = tile_row0[g];
+    v.nrows = tile_nrows[g];
+    v.e = tile_e[g];
+    v.jd = jd;
+    v.kmask = tile_bits[g];
+    v.pad0 = v.pad1 = v.pad2 = 0;
+    items2[it] = v;
+  }
+  // 6. per (expert, partition): rank of each active tile
+  for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
+    int e = gidx / L.P, p = gidx % L.P;
+    int nt = (ne[e] + BM - 1) / BM;
+    int cnt = 0;
+    for (int i = 0; i < nt; ++i) {
+      int g = ts[e] + i;
+      bool act = (tile_bits[g] >> p) & 1;
+      act_rank[(size_t)g * L.P + p] = act ? cnt : -1;
+      cnt += act ? 1 : 0;
+    }
+    ga[gidx] = cnt;
+    gb[gidx] = cnt * (e < E_res ? L.NT1 : L.NT1_sh);
+  }
+  __syncthreads();
+  int total1 = block_excl_scan(gb, NG, tmp);
+  // 7. GEMM-1 items in the order (expert, partition, neuron tile, row tile): the row tiles that
+  //    share one weight tile are adjacent.
+  const int NTmax = L.NT1 > L.NT1_sh ? L.NT1 : L.NT1_sh;
+  const int64_t span = (int64_t)total_tiles * L.P * NTmax;
+  for (int64_t q = tid; q < span; q += kPlanThreads) {
+    int jt = (int)(q % NTmax);
+    int64_t r = q / NTmax;
+    int p = (int)(r % L.P);
+    int g = (int)(r / L.P);
+    int e = tile_e[g];
+    int nt1 = e < E_res ? L.NT1 : L.NT1_sh;
+    int rk = act_rank[(size_t)g * L.P + p];
+    if (jt < nt1 && rk >= 0) {
+      int gi = e * L.P + p;
+      Item1 v;
+      v.row0 = tile_row0[g];
+      v.nrows = tile_nrows[g];
+      v.e = e;
+      v.p = p;
+      v.jt = jt;
+      v.pad0 = v.pad1 = v.pad2 = 0;
+      items1[gb[gi] + jt * ga[gi] + rk] = v;
+    }
+  }
+  if (tid == 0) {
+    counters[0] = total1;
+    counters[1] = total_tiles * L.ND2;
+    counters[2] = total_tiles;
+    counters[3] = 0;
+  }
+}
+
+hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
+  const int E_tot = L.E_res + (L.n_shared > 0 ? 1 : 0);
+  const int NG = E_tot * L.P;
+  size_t sh = sizeof(int32_t) * (size_t)(4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + 8);
+  plan_kernel<<<dim3(1), dim3(kPlanThreads), sh, s>>>(L, T, ws);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------- scatter
+// Places every pair with at least one kept unit into its bin's row range.  The order inside a bin
+// is arbitrary (it is decided by atomics); the layer output does not depend on it because every
+// row is computed independently of its tile neighbours.
+constexpr int kScatterThreads = 256;
+__global__ __launch_bounds__(kScatterThreads) void scatter_kernel(Layout L, int T, char* ws) {
+  extern __shared__ int32_t lh[];  // [nbins]
+  const int32_t* idx = (const int32_t*)(ws + L.o_idx);
+  const uint8_t* keep = (const uint8_t*)(ws + L.o_keep);
+  int32_t* cursor = (int32_t*)(ws + L.o_cursor);
+  int32_t* pair_row = (int32_t*)(ws + L.o_pair_row);
+  int32_t* row_token = (int32_t*)(ws + L.o_row_token);
+  uint8_t* row_bits = (uint8_t*)(ws + L.o_row_bits);
+  const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
+  const int64_t npairs = (int64_t)T * L.K;
+  const int64_t pr = (int64_t)blockIdx.x * kScatterThreads + threadIdx.x;
+  for (int i = threadIdx.x; i < L.nbins; i += kScatterThreads) lh[i] = 0;
+  __syncthreads();
+  int bin = -1, rank = 0, bits = 0;
+  if (pr < npairs) {
+    bits = keep[pr];
+    if (bits) {
+      bin = (idx[pr] - L.lo) * L.nsub + sub_of_bits(bits, nsub_bits);
+      rank = atomicAdd(&lh[bin], 1);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < L.nbins; i += kScatterThreads) {
+    int c = lh[i];
+    if (c) lh[i] = atomicAdd(&cursor[i], c);
+  }
+  __syncthreads();
+  if (pr < npairs) {
+    int row = -1;
+    if (bin >= 0) {
+      row = lh[bin] + rank;
+      row_token[row] = (int32_t)(pr / L.K);
+      row_bits[row] = (uint8_t)bits;
+    }
+    pair_row[pr] = row;
+  }
+  // the shared pseudo-expert's rows are the tokens themselves, at the start of the row space
+  if (L.n_shared > 0 && pr < T) {
+    row_token[pr] = (int32_t)pr;
+    row_bits[pr] = 1;
+  }
+}
+
+hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s) {
+  int64_t n = (int64_t)T * L.K;
+  if (n <= 0) return hipSuccess;
+  size_t sh = sizeof(int32_t) * (size_t)(L.nbins > 0 ? L.nbins : 1);
+  scatter_kernel<<<dim3((unsigned)((n + kScatterThreads - 1) / kScatterThreads)), dim3(kScatterThreads), sh, s>>>(L, T, ws);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------- combine
+// y[t] = sum_k g[t][k] * Yp[row(t,k)] (+ Yp[shared row t]); Eq. 3 restricted to the kept units.
+// One writer per output element, slots added in slot order: no atomics.
+template <typename OutT>
+__global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const char* ws, OutT* y) {
+  const float* Yp = (const float*)(ws + L.o_Yp);
+  const float* w = (const float*)(ws + L.o_w);
+  const int32_t* pair_row = (const int32_t*)(ws + L.o_pair_row);
+  const int D4 = L.D >> 2;  // D % 4 == 0 on this path
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (int64_t)T * D4) return;
+  const int t = (int)(q / D4);
+  const int d = (int)(q % D4) * 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int k = 0; k < L.K; ++k) {
+    int row = pair_row[(size_t)t * L.K + k];
+    if (row >= 0) {
+      float g = w[(size_t)t * L.K + k];
+      float4 v = *(const float4*)(Yp + (size_t)row * L.D + d);
+      acc.x += g * v.x;
+      acc.y += g * v.y;
+      acc.z += g * v.z;
+      acc.w += g * v.w;
+    }
+  }
+  if (L.n_shared > 0) {
+    float4 v = *(const float4*)(Yp + (size_t)t * L.D + d);
+    acc.x += v.x;
+    acc.y += v.y;
+    acc.z += v.z;
+    acc.w += v.w;
+  }
+  if constexpr (sizeof(OutT) == 4) {
+    *(float4*)((float*)y + (size_t)t * L.D + d) = acc;
+  } else {
+    ushort4 o;
+    o.x = f32_to_bf16(acc.x);
+    o.y = f32_to_bf16(acc.y);
+    o.z = f32_to_bf16(acc.z);
+    o.w = f32_to_bf16(acc.w);
+    *(ushort4*)((uint16_t*)y + (size_t)t * L.D + d) = o;
+  }
+}
+
+// any D (no vector access): one thread per output element
+template <typename OutT>
+__global__ __launch_bounds__(256) void combine_scalar_kernel(Layout L, int T, const char* ws, OutT* y) {
+  const float* Yp = (const float*)(ws + L.o_Yp);
+  const float* w = (const float*)(ws + L.o_w);
+  const int32_t* pair_row = (const int32_t*)(ws + L.o_pair_row);
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (int64_t)T * L.D) return;
+  const int t = (int)(q / L.D);
+  const int d = (int)(q % L.D);
+  float acc = 0.f;
+  for (int k = 0; k < L.K; ++k) {
+    int row = pair_row[(size_t)t * L.K + k];
+    if (row >= 0) acc += w[(size_t)t * L.K + k] * Yp[(size_t)row * L.D + d];
+  }
+  if (L.n_shared > 0) acc += Yp[(size_t)t * L.D + d];
+  if constexpr (sizeof(OutT) == 4) ((float*)y)[q] = acc;
+  else ((uint16_t*)y)[q] = f32_to_bf16(acc);
+}
+
+hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  if (L.D % 4 == 0) {
+    int64_t n = (int64_t)T * (L.D / 4);
+    dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (L.dtype == DSMOE_F32) combine_kernel<float><<<grid, block, 0, s>>>(L, T, ws, (float*)y);
+    else combine_kernel<uint16_t><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y);
+  } else {
+    int64_t n = (int64_t)T * L.D;
+    dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (L.dtype == DSMOE_F32) combine_scalar_kernel<float><<<grid, block, 0, s>>>(L, T, ws, (float*)y);
+    else combine_scalar_kernel<uint16_t><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace dsmoe

@@ -1,0 +1,219 @@
+"""GPU parity, layer output: moe_dualsparse_forward (through the C ABI) against the fp64 oracle,
+element by element, on seeded layers small enough for the oracle but spanning several row tiles,
+ragged tails, empty experts, fully dropped tokens, shared experts and a resident window.
+
+Tolerances (relative to the RMS of the oracle output): fp32 layers 1e-5, bf16 layers 2e-2.
+"""
+import numpy as np
+import pytest
+
+from synth import LayerSpec, LAYERS, make_layer, spread_thresholds
+from gpu_util import GUARD, make_gpu_layer, to_dev, to_host64, pick_tau, tau_table, rel_err, assert_output_close, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+
+def spec_of(**kw):
+    base = dict(name="f", T=300, D=128, F=256, E=4, K=2, P=2, dtype="bf16", seed=7, x_std=1.0, w_std=0.02)
+    base.update(kw)
+    return LayerSpec(**base)
+
+
+def oracle_forward(oracle, spec, t, tau, renorm=False, tokens=None):
+    return oracle.forward(t["x"], t["logits"], t["w1"], t["w3"], t["w2"], tau, spec.K, spec.P, perm=t["perm"],
+                          sh_w1=t.get("sh_w1"), sh_w3=t.get("sh_w3"), sh_w2=t.get("sh_w2"), lo=spec.lo, hi=spec.hi,
+                          renorm=renorm, tokens=tokens)
+
+
+def resolve_tau(oracle, spec, t, tau_kind):
+    if isinstance(tau_kind, str) and tau_kind.startswith("rate"):
+        r0 = oracle.route(t["logits"], spec.K, spec.P, np.zeros((spec.E, spec.P), np.float32), spec.lo, spec.hi)
+        return tau_table(spec, pick_tau(r0.n, spec.P, float(tau_kind[4:])))
+    if isinstance(tau_kind, str) and tau_kind == "ragged":
+        # thresholds that are NOT monotone in p and differ per expert: general keep patterns
+        # (re-drawn until no score sits inside the guard band)
+        for attempt in range(50):
+            rng = np.random.default_rng(spec.seed + 100 + attempt)
+            tau = rng.uniform(0.05, 0.6, (spec.E, spec.P)).astype(np.float32)
+            if oracle.route(t["logits"], spec.K, spec.P, tau, spec.lo, spec.hi).min_margin > 2 * GUARD:
+                return tau
+        raise AssertionError("no guard-band-free thresholds found")
+    return tau_table(spec, tau_kind)
+
+
+def run_case(oracle, spec, tau_kind, renorm=False, expect_mfma=None):
+    import torch
+    t = make_layer(spec)
+    tau = resolve_tau(oracle, spec, t, tau_kind)
+    ref_r = oracle.route(t["logits"], spec.K, spec.P, tau, spec.lo, spec.hi, renorm=renorm)
+    if ref_r.keep.size and 0 < ref_r.keep.sum() < ref_r.keep.size and spec.K > 1:
+        assert ref_r.min_margin > GUARD, ref_r.min_margin
+    y_ref = oracle_forward(oracle, spec, t, tau, renorm=renorm)
+    layer, dev = make_gpu_layer(spec, t, renorm=renorm)
+    if expect_mfma is not None:
+        assert layer.uses_mfma == expect_mfma
+    y = layer.forward(dev["x"], dev["logits"], to_dev(tau))
+    torch.cuda.synchronize()
+    y = to_host64(y, spec.dtype)
+    assert_output_close(y, y_ref, spec.dtype)
+    # tokens whose every unit is dropped (and no shared expert) are exact zeros
+    if spec.n_shared == 0:
+        dead = ref_r.keep.reshape(spec.T, -1).sum(axis=1) == 0
+        assert np.all(y[dead] == 0.0)
+    plan = layer.plan(spec.T)
+    layer.close()
+    return y, y_ref, ref_r, plan
+
+
+# ---------------------------------------------------------------------------------- fp32 layers
+@pytest.mark.parametrize("perm_kind", ["identity", "random"])
+@pytest.mark.parametrize("tau_kind", ["one", "two"])
+@pytest.mark.parametrize("renorm", [False, True])
+def test_config1_fp32(oracle, perm_kind, tau_kind, renorm):
+    spec = LAYERS["C1"].with_(perm_kind=perm_kind)
+    tau = 0.2 if tau_kind == "one" else spread_thresholds(0.2, 2)
+    run_case(oracle, spec, tau, renorm=renorm, expect_mfma=False)
+
+
+F32_CASES = [
+    ("ragged_shapes", spec_of(dtype="f32", T=131, D=72, F=120, E=5, K=3, P=3, x_std=0.5, w_std=0.1), "rate0.3"),
+    ("tiny", spec_of(dtype="f32", T=1, D=8, F=8, E=1, K=1, P=1, x_std=1.0, w_std=0.5), 0.0),
+    ("odd_D", spec_of(dtype="f32", T=33, D=7, F=10, E=3, K=2, P=2, x_std=1.0, w_std=0.5), "rate0.25"),
+    ("shared", spec_of(dtype="f32", T=70, D=40, F=48, E=6, K=2, P=2, n_shared=2, F_sh=20, x_std=0.5, w_std=0.1), "rate0.25"),
+    ("window", spec_of(dtype="f32", T=90, D=32, F=32, E=8, K=2, P=4, resident=(2, 5), x_std=0.5, w_std=0.1), "rate0.25"),
+    ("general_masks", spec_of(dtype="f32", T=200, D=32, F=64, E=4, K=3, P=4, x_std=0.5, w_std=0.1), "ragged"),
+    ("P8", spec_of(dtype="f32", T=150, D=32, F=64, E=4, K=2, P=8, x_std=0.5, w_std=0.1), "ragged"),
+    ("all_dropped", spec_of(dtype="f32", T=40, D=32, F=32, E=4, K=2, P=2, x_std=0.5, w_std=0.1), 2.0),
+    ("empty_experts", spec_of(dtype="f32", T=3, D=32, F=32, E=16, K=2, P=2, x_std=0.5, w_std=0.1), 0.0),
+]
+
+
+@pytest.mark.parametrize("name,spec,tau_kind", F32_CASES, ids=[c[0] for c in F32_CASES])
+def test_fp32_generic_path(oracle, name, spec, tau_kind):
+    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=False)
+    if name == "all_dropped":
+        assert np.all(y == 0.0)
+
+
+# ---------------------------------------------------------------------------------- bf16 layers
+BF16_CASES = [
+    # several 256-row tiles per expert with ragged tails; 2 neuron tiles per partition; 2 K steps
+    ("multi_tile", spec_of(T=1500, D=128, F=512, E=4, K=2, P=2), "rate0.25", True),
+    ("no_drop", spec_of(T=700, D=256, F=256, E=4, K=2, P=2, seed=8), 0.0, True),
+    ("half_drop_P4", spec_of(T=900, D=128, F=512, E=4, K=2, P=4, seed=9), "rate0.5", True),
+    ("fine_grained", spec_of(T=600, D=128, F=128, E=16, K=4, P=2, seed=10), "rate0.25", True),
+    ("Fp_704_like", spec_of(T=400, D=128, F=384, E=4, K=2, P=2, seed=11), "rate0.33", True),  # Fp=192: half-empty neuron tile
+    ("shared", spec_of(T=500, D=128, F=256, E=8, K=2, P=2, n_shared=2, F_sh=192, seed=12), "rate0.33", True),
+    ("window", spec_of(T=800, D=128, F=256, E=8, K=2, P=4, resident=(1, 3), seed=13), "rate0.25", True),
+    ("general_masks", spec_of(T=700, D=128, F=512, E=4, K=3, P=4, seed=14), "ragged", True),
+    ("P8", spec_of(T=500, D=64, F=512, E=4, K=2, P=8, seed=15), "ragged", True),
+    ("all_dropped", spec_of(T=300, D=64, F=128, E=4, K=2, P=2, seed=16), 2.0, True),
+    ("empty_experts", spec_of(T=3, D=64, F=128, E=16, K=2, P=2, seed=17), 0.0, True),
+    ("one_token", spec_of(T=1, D=64, F=64, E=2, K=1, P=1, seed=18), 0.0, True),
+    ("D_wider_than_tile", spec_of(T=300, D=320, F=128, E=4, K=2, P=2, seed=19), "rate0.25", True),
+    ("generic_fallback", spec_of(T=200, D=72, F=80, E=4, K=2, P=2, seed=20), "rate0.25", False),
+]
+
+
+@pytest.mark.parametrize("name,spec,tau_kind,mfma", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_bf16_layers(oracle, name, spec, tau_kind, mfma):
+    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=mfma)
+    if name == "all_dropped":
+        assert np.all(y == 0.0)
+
+
+def test_partition_and_reorder_invariance_on_gpu(oracle):
+    """No drop: the output must not depend on P or on the neuron order (paper Sec. 3.2 identity);
+    checked GPU-against-oracle for each variant, and the oracle outputs agree among themselves."""
+    base = spec_of(dtype="f32", T=50, D=32, F=48, E=4, K=2, P=1, x_std=0.5, w_std=0.1, perm_kind="identity")
+    t = make_layer(base)
+    y1 = oracle_forward(oracle, base, t, tau_table(base, 0.0))
+    for P, kind in ((2, "random"), (4, "reversed"), (8, "random")):
+        spec = base.with_(P=P, perm_kind=kind)
+        y, y_ref, _, _ = run_case(oracle, spec, 0.0)
+        assert rel_err(y_ref, y1) < 1e-12
+        assert rel_err(y, y1) <= TOL["f32"]
+
+
+# ---------------------------------------------------------------------------------- row lists
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_row_lists_match_oracle_as_sets(oracle, dtype):
+    spec = spec_of(dtype=dtype, T=1100, D=64, F=256, E=6, K=3, P=4, seed=21, resident=(1, 5))
+    y, y_ref, r, plan = run_case(oracle, spec, "ragged")
+    bits_ref = r.keep_bits
+    np.testing.assert_array_equal(plan["topk_idx"].cpu().numpy(), r.idx)
+    np.testing.assert_array_equal(plan["keep_bits"].cpu().numpy(), bits_ref)
+    row_token = plan["row_token"].cpu().numpy()
+    row_bits = plan["row_bits"].cpu().numpy()
+    pair_row = plan["pair_row"].cpu().numpy()
+    nrows = plan["expert_nrows"].cpu().numpy()
+    row0 = plan["expert_row0"].cpu().numpy()
+    BM = plan["tile_rows"]
+    seen_rows = set()
+    for i, e in enumerate(range(spec.lo, spec.hi)):
+        want = sorted((int(tok), int(bits_ref[tok, k])) for tok in range(spec.T) for k in range(spec.K)
+                      if r.idx[tok, k] == e and bits_ref[tok, k])
+        assert nrows[i] == len(want)
+        assert row0[i] % BM == 0
+        rows = range(row0[i], row0[i] + nrows[i])
+        got = sorted((int(row_token[q]), int(row_bits[q])) for q in rows)
+        assert got == want
+        # rows are grouped by keep pattern, patterns that keep partition 0 first
+        key = [int("".join(str((int(row_bits[q]) >> p) & 1) for p in range(min(spec.P, 4))), 2) for q in rows]
+        assert key == sorted(key, reverse=True)
+        seen_rows.update(rows)
+    # pair -> row is the inverse map; dropped or non-resident pairs have no row
+    for tok in range(spec.T):
+        for k in range(spec.K):
+            q = int(pair_row[tok, k])
+            if bits_ref[tok, k]:
+                assert q in seen_rows and row_token[q] == tok and row_bits[q] == bits_ref[tok, k]
+            else:
+                assert q == -1
+    assert len(set(pair_row[pair_row >= 0].tolist())) == int((pair_row >= 0).sum())
+
+
+# ---------------------------------------------------------------------------------- error paths
+def test_bad_permutation_is_rejected():
+    import torch
+    from paper_2508_18376_amd import DualSparseLayer, DsmoeError
+    spec = spec_of(dtype="f32", T=8, D=16, F=16, E=2, K=1, P=2)
+    t = make_layer(spec)
+    layer = DualSparseLayer(d_model=16, d_ff=16, n_experts=2, top_k=1, n_part=2, max_tokens=8, dtype="f32")
+    dev = {k: to_dev(v) for k, v in t.items()}
+    bad = t["perm"].copy()
+    bad[1, 3] = bad[1, 4]  # a neuron named twice
+    with pytest.raises(DsmoeError) as ei:
+        layer.partition_weights(dev["w1"], dev["w3"], dev["w2"], perm=to_dev(bad))
+    assert ei.value.status == -2
+    bad2 = t["perm"].copy()
+    bad2[0, 0] = 16  # out of range
+    with pytest.raises(DsmoeError) as ei:
+        layer.partition_weights(dev["w1"], dev["w3"], dev["w2"], perm=to_dev(bad2))
+    assert ei.value.status == -2
+    layer.partition_weights(dev["w1"], dev["w3"], dev["w2"], perm=dev["perm"])  # the good one passes
+    with pytest.raises(DsmoeError):  # T > max_tokens
+        layer.forward(torch.zeros((9, 16), device="cuda:0"), torch.zeros((9, 2), device="cuda:0"),
+                      torch.zeros((2, 2), device="cuda:0"))
+    layer.close()
+
+
+def test_forward_is_repeatable_and_workspace_reusable(oracle):
+    """Two calls with different T and tau on the same context: the second must not see the first."""
+    import torch
+    spec = spec_of(T=600, D=128, F=256, E=4, K=2, P=2, seed=22)
+    t = make_layer(spec)
+    layer, dev = make_gpu_layer(spec, t)
+    tau_a = tau_table(spec, 0.0)
+    r0 = oracle.route(t["logits"], spec.K, spec.P, tau_a)
+    tau_b = tau_table(spec, pick_tau(r0.n, spec.P, 0.4))
+    ya1 = layer.forward(dev["x"], dev["logits"], to_dev(tau_a)).clone()
+    yb = layer.forward(dev["x"][:257].contiguous(), dev["logits"][:257].contiguous(), to_dev(tau_b)).clone()
+    ya2 = layer.forward(dev["x"], dev["logits"], to_dev(tau_a)).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(ya1, ya2)
+    sub = {k: (v[:257] if k in ("x", "logits") else v) for k, v in t.items()}
+    y_ref = oracle_forward(oracle, spec.with_(T=257), sub, tau_b)
+    assert_output_close(to_host64(yb, "bf16"), y_ref, "bf16")
+    layer.close()
