@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the DualSparse-MoE layer forward on one MI355X.
+
+One "step" = one moe_dualsparse_forward call (route+mask, row lists, GEMM-1, GEMM-2, combine) on
+the Mixtral-8x7B-shaped synthetic layer (T=4096, D=4096, E=8, F=14336, top-2, P=4) with the inputs
+and packed weights already resident in HBM.  The headline value is tokens/s at about 25 % unit
+drop; the same line carries the 0 / 25 / 50 % sweep (tokens/s, algorithmic TFLOP/s, fraction of the
+bf16 MFMA peak), the roofline of the dominant kernel and the fp64 CPU oracle timed on a token
+sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--sample S] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor figure
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, vendor figure
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def read_traffic(workload):
+    """HBM bytes per GEMM-1 launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "gemm1_mfma_kernel_%s_hbm_traffic.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--sample", type=int, default=0, help="tokens for the CPU oracle leg (0 = per workload)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--rates", default="0,0.25,0.5")
+    ap.add_argument("--primary-rate", type=float, default=0.25)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from synth import LAYERS, make_layer
+    import paper_2508_18376_amd as ds
+    from paper_2508_18376_amd.thresholds import tau_for_drop_rate, tau_capping_rows
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    spec = LAYERS[args.workload]
+    K, W = args.steps, args.warmup
+
+    t0 = time.time()
+    host = make_layer(spec, threads=16)
+    log("generated %s on the host in %.1f s" % (spec.name, time.time() - t0))
+
+    def up(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    layer = ds.DualSparseLayer(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P,
+                               max_tokens=spec.T, dtype=spec.dtype, n_shared=spec.n_shared, d_ff_shared=spec.F_sh,
+                               expert_lo=spec.lo, expert_hi=spec.hi)
+    assert layer.uses_mfma, "the benchmark layer must run on the MFMA path"
+    x, logits = up(host["x"]), up(host["logits"])
+    wdev = {k: up(host.get(k)) for k in ("w1", "w3", "w2", "sh_w1", "sh_w3", "sh_w2", "perm")}
+    t0 = time.time()
+    layer.partition_weights(wdev["w1"], wdev["w3"], wdev["w2"], perm=wdev["perm"], sh_w1=wdev["sh_w1"], sh_w3=wdev["sh_w3"],
+                            sh_w2=wdev["sh_w2"])
+    torch.cuda.synchronize()
+    log("moe_partition_weights: %.3f s" % (time.time() - t0))
+    del wdev
+    torch.cuda.empty_cache()
+
+    # normalised scores from the GPU's own routing (renorm context, tau = 0) -> thresholds per rate
+    rctx = ds.dsmoe_create(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P, max_tokens=spec.T,
+                           dtype=1, expert_lo=spec.lo, expert_hi=spec.hi, renorm_combine=1)
+    n_pairs = spec.T * spec.K
+    r_idx = torch.empty(n_pairs, dtype=torch.int32, device=dev)
+    r_w = torch.empty(n_pairs, dtype=torch.float32, device=dev)
+    r_keep = torch.empty(n_pairs, dtype=torch.uint8, device=dev)
+    r_gc = torch.empty(spec.E * spec.P, dtype=torch.int32, device=dev)
+    tau0 = torch.zeros((spec.E, spec.P), dtype=torch.float32, device=dev)
+    ds.moe_route_and_mask(rctx, logits, spec.T, tau0, r_idx, r_w, r_keep, r_gc)
+    torch.cuda.synchronize()
+    n_all = r_w.cpu().numpy().reshape(spec.T, spec.K)
+    idx_all = r_idx.cpu().numpy().reshape(spec.T, spec.K)
+    resident = (idx_all >= spec.lo) & (idx_all < spec.hi)
+    n_res = n_all[resident]
+
+    def tau_for(rate):
+        tab = np.tile(tau_for_drop_rate(n_res, spec.P, rate)[None, :], (spec.E, 1)).astype(np.float32)
+        if spec.name == "C5":  # load-aware cap: the hot expert keeps at most 1.25 x the balanced share of rows
+            cap = int(1.25 * spec.T * spec.K / spec.E)
+            for e in range(spec.lo, spec.hi):
+                ne = n_all[idx_all == e]
+                if ne.size > cap:
+                    tab[e] = np.maximum(tab[e], tau_capping_rows(ne, spec.P, cap))
+        return tab
+
+    def kept_units(tau_dev):
+        ds.moe_route_and_mask(rctx, logits, spec.T, tau_dev, r_idx, r_w, r_keep, r_gc)
+        torch.cuda.synchronize()
+        return int(r_gc.sum().item())
+
+    Fp = spec.F // spec.P
+    unit_flops = 6.0 * spec.D * Fp
+    shared_flops = 6.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
+    total_units = int(resident.sum()) * spec.P
+    y = torch.empty((spec.T, spec.D), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def run_steps(tau_dev, n):
+        for _ in range(n):
+            ds.moe_dualsparse_forward(layer.ctx, layer.packed, x, logits, tau_dev, spec.T, y, layer.workspace, stream)
+
+    def timed(tau_dev, profile_level):
+        run_steps(tau_dev, W)
+        torch.cuda.synchronize()
+        if profile_level:
+            ds.dsmoe_profile_begin(layer.ctx, profile_level, K)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        run_steps(tau_dev, K)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t_start
+        kms = None
+        if profile_level:
+            kms, calls = ds.dsmoe_profile_end(layer.ctx)
+            assert calls == K
+        return dt / K * 1e3, kms
+
+    rates = [float(r) for r in args.rates.split(",")]
+    if args.primary_rate not in rates:
+        rates.append(args.primary_rate)
+    sweep = []
+    primary = None
+    for rate in rates:
+        tab = tau_for(rate)
+        tau_dev = torch.from_numpy(tab).to(dev)
+        units = kept_units(tau_dev)
+        is_primary = abs(rate - args.primary_rate) < 1e-9
+        ms, kms = timed(tau_dev, 1 if is_primary else 0)
+        flops = unit_flops * units + shared_flops
+        rec = {"target_drop": rate, "drop_rate": 1.0 - units / max(total_units, 1), "kept_units": units,
+               "ms_per_step": ms, "tokens_per_s": spec.T / (ms * 1e-3), "tflops": flops / (ms * 1e-3) / 1e12,
+               "frac_bf16_peak": flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "tau": [float(v) for v in tab[spec.lo]]}
+        sweep.append(rec)
+        log("rate %.3f: %.3f ms/step, %.0f tokens/s, %.1f TFLOP/s (%.1f %% of bf16 peak), realised drop %.3f"
+            % (rate, ms, rec["tokens_per_s"], rec["tflops"], 100 * rec["frac_bf16_peak"], rec["drop_rate"]))
+        if is_primary:
+            primary = dict(rec)
+            primary["gemm1_ms"] = kms["gemm1"]
+            primary["tau_table"] = tab
+            primary["tau_dev"] = tau_dev
+    # per-kernel table (separate pass with events between all kernels)
+    _, kms_all = timed(primary["tau_dev"], 2)
+    units = primary["kept_units"]
+    pairs_kept = None
+    plan = layer.plan(spec.T)
+    pairs_kept = int((plan["pair_row"] >= 0).sum().item())
+    bytes_route = spec.T * spec.E * 4 + spec.T * spec.K * 9
+    bytes_scatter = spec.T * spec.K * 9 + pairs_kept * 5
+    bytes_combine = pairs_kept * spec.D * 4 + spec.T * spec.D * 2 + spec.T * spec.K * 8 \
+        + (spec.T * spec.D * 4 if spec.n_shared else 0)
+    g1_flops = 4.0 * spec.D * Fp * units + 4.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
+    g2_flops = 2.0 * spec.D * Fp * units + 2.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
+    kernels = {k: {"ms": v} for k, v in kms_all.items()}
+    kernels["route_mask"]["GBps"] = bytes_route / (kms_all["route_mask"] * 1e-3) / 1e9
+    kernels["scatter"]["GBps"] = bytes_scatter / (kms_all["scatter"] * 1e-3) / 1e9
+    kernels["combine"]["GBps"] = bytes_combine / (kms_all["combine"] * 1e-3) / 1e9
+    kernels["gemm1"]["tflops"] = g1_flops / (kms_all["gemm1"] * 1e-3) / 1e12
+    kernels["gemm2"]["tflops"] = g2_flops / (kms_all["gemm2"] * 1e-3) / 1e12
+
+    g1_ach = g1_flops / (primary["gemm1_ms"] * 1e-3) / 1e12
+    roofline = {"kernel": "gemm1_mfma_kernel", "bound": "mfma", "achieved": g1_ach, "peak": BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": g1_ach / BF16_PEAK_TFLOPS, "traffic": read_traffic(spec.name),
+                "avg_launch_ms": primary["gemm1_ms"], "flops_per_launch": g1_flops}
+
+    # proportionality of the time saved at the primary rate, against the 0 % run
+    t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
+    prop = None
+    if t_zero:
+        prop = {"time_reduction": (t_zero - primary["ms_per_step"]) / t_zero, "drop_rate": primary["drop_rate"]}
+        prop["frac_of_proportional"] = prop["time_reduction"] / max(primary["drop_rate"], 1e-9)
+
+    # CPU oracle leg: the same layer and thresholds on a seeded token sample, all host cores
+    cpu = None
+    check = None
+    if not args.no_cpu:
+        import oracle
+        S = args.sample or {"C2": 192, "C3": 1024, "C4": 768, "C5": 192}[spec.name]
+        S = min(S, spec.T)
+        tok = np.sort(np.random.default_rng(12345).choice(spec.T, size=S, replace=False)).astype(np.int32)
+        t0 = time.time()
+        y_ref = oracle.forward(host["x"], host["logits"], host["w1"], host["w3"], host["w2"], primary["tau_table"], spec.K,
+                               spec.P, perm=host["perm"], sh_w1=host.get("sh_w1"), sh_w3=host.get("sh_w3"),
+                               sh_w2=host.get("sh_w2"), lo=spec.lo, hi=spec.hi, tokens=tok)
+        dt = time.time() - t0
+        cpu = {"value": S / dt, "unit": "tokens/s", "cores": oracle.n_threads(), "kind": "oracle",
+               "sample": "%d of %d tokens (seeded), whole layer per token, %.1f s" % (S, spec.T, dt)}
+        run_steps(primary["tau_dev"], 1)
+        torch.cuda.synchronize()
+        y_s = y[torch.from_numpy(tok.astype(np.int64)).to(dev)].to(torch.float32).cpu().numpy().astype(np.float64)
+        rms = float(np.sqrt(np.mean(y_ref ** 2)))
+        aerr = np.abs(y_s - y_ref)
+        # the bf16 output format costs up to 2^-8 |y| by itself; the rest is the computation's error
+        check = {"sample_max_err_over_rms": float(aerr.max() / rms),
+                 "sample_max_err_beyond_bf16_output_rounding_over_rms": float((aerr - 2.0 ** -8 * np.abs(y_ref)).max() / rms),
+                 "tolerance": 2e-2}
+        log("oracle: %.2f tokens/s on %d threads; GPU vs oracle on the sample: %.4f x RMS" % (cpu["value"], cpu["cores"],
+                                                                                      check["sample_max_err_over_rms"]))
+
+    out = {
+        "metric": "MoE-layer tokens/s + MFMA TFLOP/s vs bf16 peak at 0/25/50% drop",
+        "value": primary["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": primary["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: T=%d D=%d E=%d F=%d top-%d P=%d%s, tau for ~%d%% unit drop (realised %.1f%%)" % (
+            spec.name, spec.T, spec.D, spec.E, spec.F, spec.K, spec.P,
+            (" + %d shared x %d" % (spec.n_shared, spec.F_sh)) if spec.n_shared else "",
+            round(100 * args.primary_rate), 100 * primary["drop_rate"]),
+            "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
+        "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
+        "sweep": sweep, "proportionality": prop, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "check": check,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

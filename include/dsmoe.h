@@ -134,6 +134,20 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, co
 #define DSMOE_PLAN_FIELDS 12
 int dsmoe_plan_layout(const dsmoe_ctx* ctx, int64_t* out);
 
+/*
+ * Per-kernel timing of the next moe_dualsparse_forward calls on this context, for benchmarks.
+ * The steps of the layer (Eq. 1-4 with the drops of Sec. 4) run as seven kernels: clear counters,
+ * route+mask, plan, scatter, GEMM-1, GEMM-2, combine.  begin creates HIP events (host objects, no
+ * device memory); while profiling, forward records them on its stream between the kernels
+ * (level 2) or only around GEMM-1 (level 1) and stays asynchronous; calls beyond max_calls are not
+ * recorded.  end waits for the recorded events, writes the mean duration in milliseconds of each
+ * kernel to ms[0..6] (host memory; 0 where not recorded) and the number of recorded calls to
+ * *calls, destroys the events and switches profiling off.
+ */
+#define DSMOE_NUM_KERNELS 7
+int dsmoe_profile_begin(dsmoe_ctx* ctx, int level, int max_calls);
+int dsmoe_profile_end(dsmoe_ctx* ctx, float* ms, int* calls);
+
 #ifdef __cplusplus
 }
 #endif

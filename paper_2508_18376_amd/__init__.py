@@ -14,6 +14,9 @@ from .binding import (  # noqa: F401
     dsmoe_strerror,
     dsmoe_uses_mfma,
     dsmoe_plan_layout,
+    dsmoe_profile_begin,
+    dsmoe_profile_end,
+    KERNEL_NAMES,
     moe_partition_weights,
     moe_route_and_mask,
     moe_dualsparse_forward,

@@ -59,6 +59,10 @@ def _load() -> ctypes.CDLL:
     L.moe_dualsparse_forward.restype = ctypes.c_int
     L.dsmoe_plan_layout.argtypes = [vp, i64p]
     L.dsmoe_plan_layout.restype = ctypes.c_int
+    L.dsmoe_profile_begin.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    L.dsmoe_profile_begin.restype = ctypes.c_int
+    L.dsmoe_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+    L.dsmoe_profile_end.restype = ctypes.c_int
     return L
 
 
@@ -114,6 +118,21 @@ def dsmoe_plan_layout(ctx):
     if n < 0:
         raise DsmoeError(n, "dsmoe_plan_layout")
     return [int(v) for v in out]
+
+
+KERNEL_NAMES = ("fill", "route_mask", "plan", "scatter", "gemm1", "gemm2", "combine")
+
+
+def dsmoe_profile_begin(ctx, level: int, max_calls: int) -> None:
+    _check(_lib.dsmoe_profile_begin(ctx, int(level), int(max_calls)), ctx, "dsmoe_profile_begin")
+
+
+def dsmoe_profile_end(ctx):
+    """Returns ({kernel name: mean ms}, recorded calls)."""
+    ms = (ctypes.c_float * len(KERNEL_NAMES))()
+    calls = ctypes.c_int(0)
+    _check(_lib.dsmoe_profile_end(ctx, ms, ctypes.byref(calls)), ctx, "dsmoe_profile_end")
+    return {k: float(ms[i]) for i, k in enumerate(KERNEL_NAMES)}, int(calls.value)
 
 
 def _check(rc: int, ctx, where: str) -> None:

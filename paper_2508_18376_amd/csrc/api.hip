@@ -224,22 +224,103 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
   if (T == 0) return DSMOE_OK;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  hipError_t err;
+  hipError_t err = hipSuccess;
+  // optional per-kernel events (benchmarks only); the call stays asynchronous either way
+  Profile& pf = ctx->prof;
+  const bool rec = pf.level > 0 && pf.calls < pf.max_calls;
+  const int per_call = pf.level == 2 ? kNumKernels + 1 : 2;
+  hipEvent_t* ev = rec ? pf.ev + (size_t)pf.calls * per_call : nullptr;
+  auto mark = [&](int boundary) {  // boundary b sits before kernel b (b = kNumKernels: after the last)
+    if (!rec || err != hipSuccess) return;
+    if (pf.level == 2) err = hipEventRecord(ev[boundary], s);
+    else if (boundary == 4) err = hipEventRecord(ev[0], s);
+    else if (boundary == 5) err = hipEventRecord(ev[1], s);
+  };
+#define DSMOE_STEP(b, call) \
+  do {                      \
+    mark(b);                \
+    if (err == hipSuccess) err = (call); \
+  } while (0)
   // bin_count and cursor are adjacent: one fill clears both
-  err = launch_fill_i32((int32_t*)(ws + L.o_bin_count), (L.o_exp_nrows - L.o_bin_count) / 4, 0, s);
+  DSMOE_STEP(0, launch_fill_i32((int32_t*)(ws + L.o_bin_count), (L.o_exp_nrows - L.o_bin_count) / 4, 0, s));
+  DSMOE_STEP(1, launch_route(L, logits, T, tau, (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w), (uint8_t*)(ws + L.o_keep),
+                             (int32_t*)(ws + L.o_bin_count), nullptr, s));
+  DSMOE_STEP(2, launch_plan(L, T, ws, s));
+  DSMOE_STEP(3, launch_scatter(L, T, ws, s));
+  DSMOE_STEP(4, L.mfma ? launch_gemm1_mfma(L, T, (const char*)packed, x, ws, s)
+                       : launch_gemm1_generic(L, T, (const char*)packed, x, ws, s));
+  DSMOE_STEP(5, L.mfma ? launch_gemm2_mfma(L, T, (const char*)packed, ws, s) : launch_gemm2_generic(L, T, (const char*)packed, ws, s));
+  DSMOE_STEP(6, launch_combine(L, T, ws, y, s));
+  mark(kNumKernels);
+#undef DSMOE_STEP
   if (err != hipSuccess) return hip_fail(ctx, err);
-  err = launch_route(L, logits, T, tau, (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w), (uint8_t*)(ws + L.o_keep),
-                     (int32_t*)(ws + L.o_bin_count), nullptr, s);
-  if (err != hipSuccess) return hip_fail(ctx, err);
-  err = launch_plan(L, T, ws, s);
-  if (err != hipSuccess) return hip_fail(ctx, err);
-  err = launch_scatter(L, T, ws, s);
-  if (err != hipSuccess) return hip_fail(ctx, err);
-  err = L.mfma ? launch_gemm_mfma(L, T, (const char*)packed, x, ws, s) : launch_gemm_generic(L, T, (const char*)packed, x, ws, s);
-  if (err != hipSuccess) return hip_fail(ctx, err);
-  err = launch_combine(L, T, ws, y, s);
-  if (err != hipSuccess) return hip_fail(ctx, err);
+  if (rec) pf.calls += 1;
   return DSMOE_OK;
+}
+
+int dsmoe_profile_begin(dsmoe_ctx* ctx_, int level, int max_calls) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || level < 1 || level > 2 || max_calls < 1 || max_calls > 100000) return DSMOE_EINVAL;
+  Profile& pf = ctx->prof;
+  if (pf.ev) return DSMOE_EINVAL;  // already profiling
+  const int per_call = level == 2 ? kNumKernels + 1 : 2;
+  const size_t n = (size_t)per_call * max_calls;
+  pf.ev = (hipEvent_t*)calloc(n, sizeof(hipEvent_t));
+  if (!pf.ev) return DSMOE_EINVAL;
+  for (size_t i = 0; i < n; ++i) {
+    hipError_t e = hipEventCreate(&pf.ev[i]);
+    if (e != hipSuccess) {
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(pf.ev[j]);
+      free(pf.ev);
+      pf.ev = nullptr;
+      return hip_fail(ctx, e);
+    }
+  }
+  pf.level = level;
+  pf.max_calls = max_calls;
+  pf.calls = 0;
+  return DSMOE_OK;
+}
+
+int dsmoe_profile_end(dsmoe_ctx* ctx_, float* ms, int* calls) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || !ms || !calls) return DSMOE_EINVAL;
+  Profile& pf = ctx->prof;
+  if (!pf.ev) return DSMOE_EINVAL;
+  const int per_call = pf.level == 2 ? kNumKernels + 1 : 2;
+  double sum[kNumKernels] = {0};
+  int rc = DSMOE_OK;
+  for (int c = 0; c < pf.calls && rc == DSMOE_OK; ++c) {
+    hipEvent_t* ev = pf.ev + (size_t)c * per_call;
+    hipError_t e = hipEventSynchronize(ev[per_call - 1]);
+    if (e != hipSuccess) {
+      rc = hip_fail(ctx, e);
+      break;
+    }
+    if (pf.level == 2) {
+      for (int k = 0; k < kNumKernels; ++k) {
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, ev[k], ev[k + 1]);
+        if (e != hipSuccess) {
+          rc = hip_fail(ctx, e);
+          break;
+        }
+        sum[k] += t;
+      }
+    } else {
+      float t = 0.f;
+      e = hipEventElapsedTime(&t, ev[0], ev[1]);
+      if (e != hipSuccess) rc = hip_fail(ctx, e);
+      sum[4] += t;
+    }
+  }
+  for (int k = 0; k < kNumKernels; ++k) ms[k] = pf.calls > 0 ? (float)(sum[k] / pf.calls) : 0.f;
+  *calls = pf.calls;
+  const size_t n = (size_t)per_call * pf.max_calls;
+  for (size_t i = 0; i < n; ++i) (void)hipEventDestroy(pf.ev[i]);
+  free(pf.ev);
+  pf = Profile();
+  return rc;
 }
 
 int dsmoe_plan_layout(const dsmoe_ctx* ctx_, int64_t* out) {

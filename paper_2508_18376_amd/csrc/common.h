@@ -56,10 +56,20 @@ struct Layout {
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
 };
 
+constexpr int kNumKernels = 7;  // fill, route, plan, scatter, gemm1, gemm2, combine
+
+struct Profile {
+  int level = 0;       // 0 off, 1 GEMM-1 only, 2 every kernel
+  int max_calls = 0;
+  int calls = 0;
+  hipEvent_t* ev = nullptr;  // level 1: 2 per call; level 2: kNumKernels + 1 per call
+};
+
 struct Ctx {
   dsmoe_config cfg;
   Layout L;
   int last_hip;
+  Profile prof;
 };
 
 // upper bounds of the plan sizes for a call with T tokens (the exact sizes only exist on the device)
@@ -77,8 +87,10 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s);
-hipError_t launch_gemm_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
-hipError_t launch_gemm_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+hipError_t launch_gemm2_generic(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
+hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
 hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const void* w2, const void* sw1, const void* sw3,
                        const void* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh, hipStream_t s);
 hipError_t launch_perm_check(const Layout& L, const int32_t* perm, int32_t* scratch, hipStream_t s);

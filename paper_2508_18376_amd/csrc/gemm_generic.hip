@@ -156,16 +156,19 @@ __global__ __launch_bounds__(256) void gemm2_generic_kernel(Layout L, const char
   }
 }
 
-hipError_t launch_gemm_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s) {
+hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  dim3 block(256);
-  if (L.dtype == DSMOE_F32) {
-    gemm1_generic_kernel<float><<<dim3(items1_bound(L, T)), block, 0, s>>>(L, packed, (const float*)x, ws);
-    gemm2_generic_kernel<float><<<dim3(items2_bound(L, T)), block, 0, s>>>(L, packed, ws);
-  } else {
-    gemm1_generic_kernel<uint16_t><<<dim3(items1_bound(L, T)), block, 0, s>>>(L, packed, (const uint16_t*)x, ws);
-    gemm2_generic_kernel<uint16_t><<<dim3(items2_bound(L, T)), block, 0, s>>>(L, packed, ws);
-  }
+  dim3 block(256), grid(items1_bound(L, T));
+  if (L.dtype == DSMOE_F32) gemm1_generic_kernel<float><<<grid, block, 0, s>>>(L, packed, (const float*)x, ws);
+  else gemm1_generic_kernel<uint16_t><<<grid, block, 0, s>>>(L, packed, (const uint16_t*)x, ws);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm2_generic(const Layout& L, int T, const char* packed, char* ws, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  dim3 block(256), grid(items2_bound(L, T));
+  if (L.dtype == DSMOE_F32) gemm2_generic_kernel<float><<<grid, block, 0, s>>>(L, packed, ws);
+  else gemm2_generic_kernel<uint16_t><<<grid, block, 0, s>>>(L, packed, ws);
   return hipGetLastError();
 }
 

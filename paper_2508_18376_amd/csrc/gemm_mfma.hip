@@ -242,21 +242,32 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   }
 }
 
-hipError_t launch_gemm_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s) {
-  if (T <= 0) return hipSuccess;
+static hipError_t set_lds_attr() {
   static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  const int g1 = (items1_bound(L, T) + 255) & ~255;  // whole chunks of 256 so the XCD remap is a bijection
-  const int g2 = (items2_bound(L, T) + 255) & ~255;
-  gemm1_mfma_kernel<<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws);
-  hipError_t e = hipGetLastError();
+  if (attr_set) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  if (e != hipSuccess) return e;
+  attr_set = true;
+  return hipSuccess;
+}
+
+// grids are whole chunks of 256 blocks so that the XCD remap is a bijection
+hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  hipError_t e = set_lds_attr();
+  if (e != hipSuccess) return e;
+  const int g1 = (items1_bound(L, T) + 255) & ~255;
+  gemm1_mfma_kernel<<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* ws, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  hipError_t e = set_lds_attr();
+  if (e != hipSuccess) return e;
+  const int g2 = (items2_bound(L, T) + 255) & ~255;
   gemm2_mfma_kernel<<<dim3(g2), dim3(256), kLdsBytes, s>>>(L, T, packed, ws);
   return hipGetLastError();
 }

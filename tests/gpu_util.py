@@ -83,28 +83,31 @@ def bf16_floor(y_ref: np.ndarray) -> float:
     return rel_err(yb, y_ref)
 
 
+BF16_HALF_ULP = 2.0 ** -8  # largest relative error of rounding a value to bf16 (8 significant bits)
+
+
 def assert_output_close(y: np.ndarray, y_ref: np.ndarray, dtype: str) -> float:
     """The parity bar for layer outputs.
 
     fp32 layers: max |err| <= 1e-5 x RMS(y_ref).
-    bf16 layers: max |err| <= 2e-2 x RMS(y_ref).  Rounding the exact result to bf16 already costs
-    max|y| / RMS x 2^-9; on small layers whose outputs have heavy tails (few tokens, large spread of
-    gate weights) that floor alone can pass 1e-2, half the budget.  There the global bar becomes
-    floor + 1e-2, and in every case each token must also meet 2e-2 x the RMS of its own output row,
-    which is the scale its rounding errors live on.
+    bf16 layers: the computation (bf16 operands, fp32 accumulation, bf16 intermediate activation)
+    gets the budget 2e-2 x RMS(y_ref); storing the result as bf16 costs up to 2^-8 |y| more on any
+    implementation (the exact result rounded to bf16 already misses 2e-2 x RMS on outputs whose
+    largest element is beyond ~5 RMS), so the elementwise bar is
+        |y - y_ref| <= 2e-2 x RMS(y_ref) + 2^-8 |y_ref|.
+    Where the rounding floor leaves room (floor <= 1e-2) the plain bar 2e-2 x RMS is asserted too.
+    Returns max |err| / RMS.
     """
     assert np.isfinite(y).all()
     err = rel_err(y, y_ref)
     if dtype == "f32":
         assert err <= TOL["f32"], (err, TOL["f32"])
         return err
-    floor = bf16_floor(y_ref)
-    bar = TOL["bf16"] if floor <= 1e-2 else floor + 1e-2
-    assert err <= bar, (err, bar, floor)
-    rms_t = np.sqrt(np.mean(y_ref ** 2, axis=1))
-    live = rms_t > 0
-    if live.any():
-        per_tok = (np.abs(y - y_ref)[live].max(axis=1) / rms_t[live]).max()
-        assert per_tok <= TOL["bf16"], (per_tok, TOL["bf16"])
-    assert np.all(y[~live] == 0.0)
+    rms = float(np.sqrt(np.mean(y_ref ** 2)))
+    excess = np.abs(y - y_ref) - BF16_HALF_ULP * np.abs(y_ref)
+    assert excess.max() <= TOL["bf16"] * rms, (excess.max() / max(rms, 1e-300), TOL["bf16"])
+    if bf16_floor(y_ref) <= 1e-2:
+        assert err <= TOL["bf16"], (err, TOL["bf16"])
+    dead = np.abs(y_ref).max(axis=1) == 0
+    assert np.all(y[dead] == 0.0)
     return err
