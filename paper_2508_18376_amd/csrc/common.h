@@ -13,12 +13,13 @@ constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
 
 // MFMA path tile shape: 256 rows (token-expert pairs) x 128 neurons (gate+up = 256 weight rows)
-// for GEMM-1, 256 rows x 256 output columns for GEMM-2, K step 64.
+// for GEMM-1, 256 rows x 256 output columns for GEMM-2, K stage 32.
 constexpr int kMfmaBM = 256;
 constexpr int kMfmaNeur = 128;
 constexpr int kMfmaBN2 = 256;
-constexpr int kBK = 64;
-constexpr int kStageBytes = 256 * kBK * 2;  // one operand tile of one K step (bf16)
+constexpr int kBK = 32;                     // K values per pipeline stage
+constexpr int kChunksPerRow = kBK / 8;      // 16-byte chunks in one tile row
+constexpr int kStageBytes = 256 * kBK * 2;  // one operand tile of one stage (bf16): 16 KiB
 
 // generic path tile shape
 constexpr int kGenBM = 64;
@@ -106,9 +107,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest,
 __device__ __forceinline__ float silu_f32(float a) { return a / (1.0f + expf(-a)); }       // Swish, beta = 1
 __device__ __forceinline__ float silu_fast(float a) { return a / (1.0f + __expf(-a)); }
 
-// Position of the 16-byte chunk `chunk` (0..7) of row `row` inside a [rows][64] bf16 LDS tile.
-// Chunks of a row are rotated by an XOR so that MFMA operand reads (32 rows, same logical chunk)
-// spread over all LDS banks.
-__device__ __host__ __forceinline__ int swz_chunk(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+// Position of the 16-byte chunk `chunk` (0..3) of row `row` inside a [rows][32] bf16 LDS tile
+// (64-byte rows).  The chunks of a row are XOR-rotated by bits 2..3 of the row so that an MFMA
+// operand read (consecutive rows, same logical chunk) touches every LDS bank once per 16 lanes.
+// XOR is its own inverse: the same function maps physical to logical positions.
+__device__ __host__ __forceinline__ int swz_chunk(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
 }  // namespace dsmoe

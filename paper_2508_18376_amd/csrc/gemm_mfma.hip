@@ -6,30 +6,63 @@
 //           one work item = 256 rows x 256 output columns; dropped partitions are skipped whole
 //
 // Both kernels: 256 threads = 4 wavefronts in a 2 x 2 grid, each wavefront owns a 128 x 128 block
-// of the 256 x 256 tile as 4 x 4 v_mfma_f32_32x32x16_bf16 accumulators (fp32).  Operand tiles
-// [256][64] bf16 are brought HBM -> LDS with buffer loads that write LDS directly, double
-// buffered (2 x 64 KiB of the CU's 160 KiB LDS).  Weight tiles are stored pre-swizzled by
-// moe_partition_weights, so their copy is a linear 32 KiB stream; activation rows are gathered
+// of the 256 x 256 tile as 4 x 4 v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 registers).
+// Operand tiles [256][32] bf16 travel HBM/L2 -> LDS by buffer loads that write LDS directly (no
+// registers in between), through a ring of 4 stages (4 x 32 KiB of the CU's 160 KiB LDS), three
+// stages in flight ahead of the one being multiplied.  Weight tiles are stored pre-swizzled by
+// moe_partition_weights, so their copy is a linear 16 KiB stream; activation rows are gathered
 // through the row list (GEMM-1) or read in place (GEMM-2) with the same chunk rotation.
+//
+// The loads are written as inline assembly so that their completion can be awaited per stage
+// (s_waitcnt vmcnt(N)): the compiler never sees them and must not be allowed to move LDS reads
+// across the hand-placed waits and barriers, which is what the "memory" clobbers are for.
 #include "common.h"
 
 namespace dsmoe {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 
-constexpr int kLdsBytes = 4 * kStageBytes;  // 2 buffers x (A tile + B tile) = 128 KiB
-constexpr uint32_t kRsrcFlags = 0x00020000u;  // raw buffer, 32-bit elements
+constexpr int kStages = 4;                          // LDS ring depth
+constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
+constexpr int kLdsBytes = kStages * kStagePair;     // 128 KiB
+constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
+constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, kRsrcFlags);
+__device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t bytes) {
+  // buffer descriptor: base address (48 bits), stride 0, size in bytes, format flags
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((a >> 32) & 0xffffu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = (int)kRsrcFlags;
+  return r;
 }
 
-// 16 bytes per lane from (rsrc base + voff + soff) into LDS at (lds_uniform + lane * 16)
-__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, char* lds_uniform, uint32_t voff, uint32_t soff) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)lds_uniform, 16, voff, soff, 0, 0);
+// 16 bytes per lane from (rsrc base + voff + soff) straight into LDS at (lds_addr + lane * 16);
+// lds_addr (byte address inside the workgroup's LDS) must be wave-uniform.
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "buffer_load_dwordx4 %1, %2, %3 offen lds"
+      :
+      : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+      : "memory");
 }
+
+// byte offset of a __shared__ object inside the workgroup's LDS allocation (what M0 wants)
+__device__ __forceinline__ uint32_t lds_offset(const char* p) {
+  return (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const char*)p);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // XCD-aware order: consecutive block ids land on different XCDs (round robin over 8), so give
 // each XCD a run of 32 consecutive work items out of every 256: items that share a weight tile
@@ -39,24 +72,114 @@ __device__ __forceinline__ int xcd_remap(int b) {
   return (chunk << 8) + ((within & 7) << 5) + (within >> 3);
 }
 
-// One K step of the 256 x 256 tile for this wavefront: A rows wm*128.., B rows wn*128..
-__device__ __forceinline__ void mma_step(const char* ldsA, const char* ldsB, int wm, int wn, int lane, f32x16 (&acc)[4][4]) {
-  const int r32 = lane & 31, half = lane >> 5;
+struct Frags {
+  bf16x8 a[4], b[4];
+};
+
+// operand fragments of K substep s (16 values of K) of one stage: A rows wm*128 + i*32 + lane%32
+__device__ __forceinline__ void load_frags(Frags& f, const char* stage, uint32_t offA, uint32_t offB) {
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    bf16x8 a[4], b[4];
+  for (int i = 0; i < 4; ++i) {
+    f.a[i] = *(const bf16x8*)(stage + offA + i * (32 * kBK * 2));
+    f.b[i] = *(const bf16x8*)(stage + kStageBytes + offB + i * (32 * kBK * 2));
+  }
+}
+
+__device__ __forceinline__ void mma16(const Frags& f, f32x16 (&acc)[4][4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+
+// interleave hint for one half stage: 16 MFMAs with 8 LDS reads spread between them
+__device__ __forceinline__ void sched_half_stage() {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
+  }
+}
+
+// The pipelined main loop shared by both GEMMs.
+//   begin(st): fix the ring slot and the K offsets of stage st (called once per stage, in order);
+//   one(q):    enqueue this thread's q-th DMA load (0..kLoadsPerStage-1) of the stage begun last.
+// On return every DMA has completed and acc holds the tile.
+//
+// Per stage a wavefront issues 32 MFMAs (1024 matrix-core cycles), 16 LDS reads and 8 DMA loads.
+// With one wavefront per SIMD nothing else hides an instruction that stalls the stream, so the
+// reads and loads are threaded between the MFMAs by hand and pinned with scheduling barriers.
+template <class Begin, class One>
+__device__ __forceinline__ void mainloop(int n, Begin&& begin, One&& one, const char* lds, int wm, int wn, int lane,
+                                         f32x16 (&acc)[4][4]) {
+  const int r32 = lane & 31, half = lane >> 5;
+  const int sw = (r32 >> 2) & 3;
+  // byte offsets inside a stage's A / B tile for substep 0 and 1
+  const uint32_t rowA = (uint32_t)(wm * 128 + r32) * (kBK * 2), rowB = (uint32_t)(wn * 128 + r32) * (kBK * 2);
+  const uint32_t c0 = (uint32_t)((half ^ sw) * 16), c1 = (uint32_t)(((2 + half) ^ sw) * 16);
+  Frags f0, f1;
+  if (n <= 0) return;
+  auto issue_all = [&](int st) {
+    begin(st);
+#pragma unroll
+    for (int q = 0; q < kLoadsPerStage; ++q) one(q);
+  };
+  issue_all(0);
+  if (n > 1) issue_all(1);
+  if (n > 2) issue_all(2);
+  if (n > 2) wait_vm<2 * kLoadsPerStage>();
+  else if (n > 1) wait_vm<kLoadsPerStage>();
+  else wait_vm<0>();
+  block_barrier();
+  load_frags(f0, lds, rowA + c0, rowB + c0);
+
+  // first half of a stage: multiply substep 0 while the substep 1 operands stream in from LDS
+  auto first_half = [&](int st) {
+    const char* cur = lds + (st % kStages) * kStagePair;
+    load_frags(f1, cur, rowA + c1, rowB + c1);
+    mma16(f0, acc);
+    sched_half_stage();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int st = 0;
+  for (; st + 3 < n; ++st) {
+    first_half(st);
+    // stage st+1 must have landed for every wave (st+2 may still be in flight); after the barrier
+    // every wave has also finished reading stage st-1, whose slot stage st+3 takes
+    wait_vm<kLoadsPerStage>();
+    block_barrier();
+    begin(st + 3);
+    // second half: multiply substep 1; between the MFMAs, enqueue stage st+3 and fetch substep 0 of stage st+1
+    const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int ra = wm * 128 + i * 32 + r32;
-      a[i] = *(const bf16x8*)(ldsA + ra * 128 + swz_chunk(ra, s * 2 + half) * 16);
-      const int rb = wn * 128 + i * 32 + r32;
-      b[i] = *(const bf16x8*)(ldsB + rb * 128 + swz_chunk(rb, s * 2 + half) * 16);
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[0], acc[i][0], 0, 0, 0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[1], acc[i][1], 0, 0, 0);
+      one(2 * i);
+      f0.a[i] = *(const bf16x8*)(nxt + rowA + c0 + i * (32 * kBK * 2));
+      __builtin_amdgcn_sched_barrier(0);
+      acc[i][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[2], acc[i][2], 0, 0, 0);
+      acc[i][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[3], acc[i][3], 0, 0, 0);
+      one(2 * i + 1);
+      f0.b[i] = *(const bf16x8*)(nxt + kStageBytes + rowB + c0 + i * (32 * kBK * 2));
+      __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   }
+  for (; st + 1 < n; ++st) {  // last stages: nothing left to enqueue
+    first_half(st);
+    if (st + 2 < n) wait_vm<kLoadsPerStage>();
+    else wait_vm<0>();
+    block_barrier();
+    const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
+    load_frags(f0, nxt, rowA + c0, rowB + c0);
+    mma16(f1, acc);
+    sched_half_stage();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  const char* last = lds + ((n - 1) % kStages) * kStagePair;
+  load_frags(f1, last, rowA + c1, rowB + c1);
+  mma16(f0, acc);
+  mma16(f1, acc);
 }
 
 // ------------------------------------------------------------------------------------- GEMM-1
@@ -74,30 +197,33 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   const int ld = sh ? L.F_shT : L.F;
   const char* wbase = sh ? packed + L.p_sw13 + (int64_t)it.jt * KS1 * kStageBytes
                          : packed + L.p_w13 + (((int64_t)it.e * L.P + it.p) * L.NT1 + it.jt) * KS1 * kStageBytes;
-  const __amdgpu_buffer_rsrc_t rsW = make_rsrc(wbase, (uint32_t)(KS1 * kStageBytes));
-  const __amdgpu_buffer_rsrc_t rsX = make_rsrc(x, (uint32_t)((int64_t)T * L.D * 2));
+  const i32x4 rsW = make_rsrc(wbase, (uint32_t)(KS1 * kStageBytes));
+  const i32x4 rsX = make_rsrc(x, (uint32_t)((int64_t)T * L.D * 2));
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = w >> 1, wn = w & 1;
-  // activation gather: this thread copies chunk (tid & 7) of rows i*32 + (tid >> 3)
-  uint32_t xoff[8];
+  // activation gather: this thread copies chunk (tid & 3) of rows i*64 + (tid >> 2)
+  uint32_t xoff[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = i * 32 + (tid >> 3);
+  for (int i = 0; i < 4; ++i) {
+    const int r = i * 64 + (tid >> 2);
     const int rr = r < it.nrows ? r : it.nrows - 1;  // rows past the end re-read the last valid row
     const int tok = row_token[it.row0 + rr];
-    xoff[i] = (uint32_t)tok * (uint32_t)(L.D * 2) + (uint32_t)(swz_chunk(r, tid & 7) * 16);
+    xoff[i] = (uint32_t)tok * (uint32_t)(L.D * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
   }
   const uint32_t woff = (uint32_t)tid * 16;
-  char* lds_w = lds + w * 1024;  // this wavefront's 1 KiB slice of every 4 KiB slab
+  // LDS byte address of this wavefront's 1 KiB slice of each 4 KiB slab
+  const uint32_t lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
 
-  auto issue = [&](int ks, int buf) {
-    char* la = lds_w + buf * (2 * kStageBytes);
-    char* lb = la + kStageBytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) load16_to_lds(rsW, la + i * 4096, woff, (uint32_t)(ks * kStageBytes + i * 4096));
-#pragma unroll
-    for (int i = 0; i < 8; ++i) load16_to_lds(rsX, lb + i * 4096, xoff[i], (uint32_t)(ks * (kBK * 2)));
+  uint32_t slot = 0, sW = 0, sX = 0;
+  auto begin = [&](int st) {
+    slot = (uint32_t)(st % kStages) * kStagePair + lds_w;
+    sW = (uint32_t)(st * kStageBytes);
+    sX = (uint32_t)(st * (kBK * 2));
+  };
+  auto one = [&](int q) {
+    if (q < 4) dma16(rsW, slot + q * 4096, woff, sW + q * 4096);
+    else dma16(rsX, slot + kStageBytes + (q - 4) * 4096, xoff[q - 4], sX);
   };
 
   f32x16 acc[4][4];
@@ -108,13 +234,7 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  issue(0, 0);
-  for (int ks = 0; ks < KS1; ++ks) {
-    __syncthreads();  // stage ks has landed (all waves' loads), buffer (ks+1)&1 is free
-    if (ks + 1 < KS1) issue(ks + 1, (ks + 1) & 1);
-    const char* la = lds + (ks & 1) * (2 * kStageBytes);
-    mma_step(la, la + kStageBytes, wm, wn, lane, acc);
-  }
+  mainloop(KS1, begin, one, lds, wm, wn, lane, acc);
 
   // epilogue: MFMA A = weight rows (gate rows 0..63, up rows 64..127 of this wave), B = pair rows.
   // acc[i][j][v]: weight row i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row wn*128 + j*32 + lane%32.
@@ -158,35 +278,50 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   const bool sh = it.e == L.E_res;
   const int Fp = sh ? L.F_shT : L.Fp;
   const int ld = sh ? L.F_shT : L.F;
-  const int KT = ld / kBK;        // K steps of the whole expert
-  const int KSp = Fp / kBK;       // K steps of one partition
+  const int KT = ld / kBK;        // stages of the whole expert
+  const int KSp = Fp / kBK;       // stages of one partition
   const char* wbase = sh ? packed + L.p_sw2 + (int64_t)it.jd * KT * kStageBytes
                          : packed + L.p_w2 + ((int64_t)it.e * L.ND2 + it.jd) * KT * kStageBytes;
   const uint16_t* H = sh ? (const uint16_t*)(ws + L.o_Hs) : (const uint16_t*)(ws + L.o_H);
   const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
   const char* hbase = (const char*)(H + (size_t)hrow0 * ld);
-  const __amdgpu_buffer_rsrc_t rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
-  const __amdgpu_buffer_rsrc_t rsH = make_rsrc(hbase, (uint32_t)((int64_t)it.nrows * ld * 2));
+  const i32x4 rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
+  const i32x4 rsH = make_rsrc(hbase, (uint32_t)((int64_t)it.nrows * ld * 2));
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = w >> 1, wn = w & 1;
-  uint32_t hoff[8];
+  uint32_t hoff[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = i * 32 + (tid >> 3);
+  for (int i = 0; i < 4; ++i) {
+    const int r = i * 64 + (tid >> 2);
     const int rr = r < it.nrows ? r : it.nrows - 1;
-    hoff[i] = (uint32_t)rr * (uint32_t)(ld * 2) + (uint32_t)(swz_chunk(r, tid & 7) * 16);
+    hoff[i] = (uint32_t)rr * (uint32_t)(ld * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
   }
   const uint32_t woff = (uint32_t)tid * 16;
-  char* lds_w = lds + w * 1024;
+  const uint32_t lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
 
-  auto issue = [&](int kt, int buf) {  // kt = K step in the expert's neuron positions
-    char* la = lds_w + buf * (2 * kStageBytes);
-    char* lb = la + kStageBytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) load16_to_lds(rsH, la + i * 4096, hoff[i], (uint32_t)(kt * (kBK * 2)));
-#pragma unroll
-    for (int i = 0; i < 8; ++i) load16_to_lds(rsW, lb + i * 4096, woff, (uint32_t)(kt * kStageBytes + i * 4096));
+  // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
+  // begin() is called with increasing st, so a running cursor maps st -> K position.
+  const int np = sh ? 1 : L.P;
+  int nstages = 0;
+  for (int p = 0; p < np; ++p) nstages += ((it.kmask >> p) & 1) ? KSp : 0;
+  int p_cur = 0, k_in = 0;
+  while (p_cur < np && !((it.kmask >> p_cur) & 1)) ++p_cur;
+  uint32_t slot = 0, sW = 0, sH = 0;
+  auto begin = [&](int st) {
+    const int kt = p_cur * KSp + k_in;
+    if (++k_in == KSp) {
+      k_in = 0;
+      ++p_cur;
+      while (p_cur < np && !((it.kmask >> p_cur) & 1)) ++p_cur;
+    }
+    slot = (uint32_t)(st % kStages) * kStagePair + lds_w;
+    sH = (uint32_t)(kt * (kBK * 2));
+    sW = (uint32_t)(kt * kStageBytes);
+  };
+  auto one = [&](int q) {
+    if (q < 4) dma16(rsH, slot + q * 4096, hoff[q], sH);
+    else dma16(rsW, slot + kStageBytes + (q - 4) * 4096, woff, sW + (q - 4) * 4096);
   };
 
   f32x16 acc[4][4];
@@ -197,32 +332,7 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // K steps run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing)
-  const int np = sh ? 1 : L.P;
-  int nsteps = 0;
-  for (int p = 0; p < np; ++p) nsteps += ((it.kmask >> p) & 1) ? KSp : 0;
-  // step -> kt: walk the kept partitions in order
-  int p_cur = 0, k_in = 0;
-  auto advance_to_kept = [&]() {
-    while (p_cur < np && !((it.kmask >> p_cur) & 1)) ++p_cur;
-  };
-  advance_to_kept();
-  auto next_kt = [&]() {
-    int kt = p_cur * KSp + k_in;
-    if (++k_in == KSp) {
-      k_in = 0;
-      ++p_cur;
-      advance_to_kept();
-    }
-    return kt;
-  };
-  if (nsteps > 0) issue(next_kt(), 0);
-  for (int st = 0; st < nsteps; ++st) {
-    __syncthreads();
-    if (st + 1 < nsteps) issue(next_kt(), (st + 1) & 1);
-    const char* la = lds + (st & 1) * (2 * kStageBytes);
-    mma_step(la, la + kStageBytes, wm, wn, lane, acc);
-  }
+  mainloop(nstages, begin, one, lds, wm, wn, lane, acc);
 
   // epilogue: acc[i][j][v]: pair row wm*128 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, column wn*128 + j*32 + lane%32
   float* Yp = (float*)(ws + L.o_Yp);

@@ -4,11 +4,11 @@
 // Generic layout (element type = layer dtype):
 //   W1g, W3g [E_res][D][F], W2g [E_res][F][D] with neuron axis in permuted order;
 //   shared experts concatenated along the neuron axis: SW1g, SW3g [D][F_shT], SW2g [F_shT][D].
-// MFMA layout (bf16): 32 KiB "stage images", each the exact LDS contents of one operand tile of
-//   one K step, rows of 64 K-values with the 16-byte chunks XOR-rotated (swz_chunk):
-//   W13  stage ((e*P + p)*NT1 + jt)*(D/64) + ks : 256 weight rows x 64 values of d; weight row
+// MFMA layout (bf16): 16 KiB "stage images", each the exact LDS contents of one operand tile of
+//   one pipeline stage, rows of kBK = 32 K-values with the 16-byte chunks XOR-rotated (swz_chunk):
+//   W13  stage ((e*P + p)*NT1 + jt)*(D/32) + ks : 256 weight rows x 32 values of d; weight row
 //        wm*128 + gu*64 + j  is neuron  p*Fp + jt*128 + wm*64 + j  of W1 (gu=0) or W3 (gu=1)
-//   W2   stage (e*ND2 + jd)*(F/64) + kt : 256 output columns x 64 neurons (positions kt*64..)
+//   W2   stage (e*ND2 + jd)*(F/32) + kt : 256 output columns x 32 neurons (positions kt*32..)
 //   neurons / columns past the end are zero.
 #include "common.h"
 
@@ -74,7 +74,7 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
   for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
     int64_t stage = q / chunks_per_stage;
     int c = (int)(q % chunks_per_stage);
-    const int row = c >> 3, pc = c & 7;
+    const int row = c / kChunksPerRow, pc = c % kChunksPerRow;
     const int lc = swz_chunk(row, pc);  // XOR rotation is its own inverse
     uint16_t v[8];
     char* dst;
