@@ -23,6 +23,7 @@ namespace dsmoe {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 constexpr int kStages = 4;                          // LDS ring depth
 constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
@@ -238,31 +239,46 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
 
   // epilogue: MFMA A = weight rows (gate rows 0..63, up rows 64..127 of this wave), B = pair rows.
   // acc[i][j][v]: weight row i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row wn*128 + j*32 + lane%32.
-  uint16_t* H = sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
-  const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
-  const int nbase = it.jt * kMfmaNeur + wm * 64;  // first neuron (inside the partition) of this wave
+  // Swish(gate) * up is rounded to bf16 and parked in LDS as a [256 rows][128 neurons] tile
+  // (rows padded to 272 bytes against bank conflicts), then written out in whole 256-byte row
+  // segments: 16 lanes per row, 16 bytes per lane.
+  constexpr int kHsRow = kMfmaNeur * 2 + 16;
+  block_barrier();  // every wave is done reading the last stage
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int r = wn * 128 + j * 32 + (lane & 31);
-    if (r >= it.nrows) continue;
-    const bool kept = (row_bits[it.row0 + r] >> it.p) & 1;
-    uint16_t* hrow = H + (size_t)(hrow0 + r) * ld + (size_t)it.p * Fp;
+    const bool kept = r < it.nrows && ((row_bits[it.row0 + (r < it.nrows ? r : 0)] >> it.p) & 1);
+    char* srow = lds + r * kHsRow + (wm * 64 + (lane >> 5) * 4) * 2;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        const int n0 = nbase + i * 32 + vq * 8 + (lane >> 5) * 4;
-        if (n0 >= Fp) continue;
-        uint16_t o[4];
+        bf16x2 lo, hi;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const float g = acc[i][j][vq * 4 + c], u = acc[i + 2][j][vq * 4 + c];
-          o[c] = kept ? f32_to_bf16(silu_fast(g) * u) : (uint16_t)0;
+          const float h = kept ? g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u : 0.f;  // Swish(g) * u, Eq. 4
+          if (c < 2) lo[c] = (__bf16)h;
+          else hi[c - 2] = (__bf16)h;
         }
         uint2 pk;
-        pk.x = o[0] | ((uint32_t)o[1] << 16);
-        pk.y = o[2] | ((uint32_t)o[3] << 16);
-        *(uint2*)(hrow + n0) = pk;
+        pk.x = __builtin_bit_cast(uint32_t, lo);
+        pk.y = __builtin_bit_cast(uint32_t, hi);
+        *(uint2*)(srow + (i * 32 + vq * 8) * 2) = pk;
+      }
+    }
+  }
+  __syncthreads();
+  uint16_t* H = sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
+  const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
+  const int n_in = it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
+  if (n_in < Fp) {
+#pragma unroll 4
+    for (int c = 0; c < 16; ++c) {
+      const int r = c * 16 + (tid >> 4);
+      if (r < it.nrows) {
+        const uint4 v = *(const uint4*)(lds + r * kHsRow + (tid & 15) * 16);
+        *(uint4*)(H + (size_t)(hrow0 + r) * ld + (size_t)it.p * Fp + n_in) = v;
       }
     }
   }
