@@ -1,12 +1,18 @@
 // bf16 MFMA grouped GEMMs for gfx950 (the hot loops of the layer).
 //
 //   GEMM-1  H[row][p*Fp + j] = Swish(x_row . W1[:, j]) * (x_row . W3[:, j])   (Eq. 4: gate, up, Swish*mul)
-//           one work item = 256 rows (token-expert pairs of one expert) x 128 neurons of partition p
+//           one work item = up to 256 rows (token-expert pairs of one expert) x 128 neurons of partition p
 //   GEMM-2  Yp[row][d] = sum over the partitions p kept by some row of the tile, sum_j H[row][p*Fp+j] W2[p*Fp+j][d]
-//           one work item = 256 rows x 256 output columns; dropped partitions are skipped whole
+//           one work item = up to 256 rows x 256 output columns; dropped partitions are skipped whole
 //
-// Both kernels: 256 threads = 4 wavefronts in a 2 x 2 grid, each wavefront owns a 128 x 128 block
-// of the 256 x 256 tile as 4 x 4 v_mfma_f32_32x32x16_bf16 accumulators (fp32, 256 registers).
+// Both kernels: 256 threads = 4 wavefronts, one per SIMD, 256 fp32 accumulator registers each,
+// v_mfma_f32_32x32x16_bf16.  A full 256-row tile is split 2 x 2 (each wavefront a 128 x 128 block,
+// 4 x 4 MFMA blocks).  The last tile of an expert's (or sub-expert's) row list is ragged: there the
+// wavefronts split the weight dimension four ways and all walk the same rows, skipping the
+// 32-row blocks past the end, so that a tile with r rows costs about ceil(r/32)/8 of a full one
+// (with drops every sub-expert has its own ragged tail: this is what keeps time proportional to
+// the kept work).
+//
 // Operand tiles [256][32] bf16 travel HBM/L2 -> LDS by buffer loads that write LDS directly (no
 // registers in between), through a ring of 4 stages (4 x 32 KiB of the CU's 160 KiB LDS), three
 // stages in flight ahead of the one being multiplied.  Weight tiles are stored pre-swizzled by
@@ -21,15 +27,16 @@
 namespace dsmoe {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 constexpr int kStages = 4;                          // LDS ring depth
 constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
 constexpr int kLdsBytes = kStages * kStagePair;     // 128 KiB
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
+constexpr int kRowBytes = kBK * 2;                  // one tile row in LDS: 64 bytes
 
 __device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t bytes) {
   // buffer descriptor: base address (48 bits), stride 0, size in bytes, format flags
@@ -73,297 +80,373 @@ __device__ __forceinline__ int xcd_remap(int b) {
   return (chunk << 8) + ((within & 7) << 5) + (within >> 3);
 }
 
+// Operand fragments of one K substep (16 values of K): I blocks of 32 A rows, J blocks of 32 B rows.
+template <int I, int J>
 struct Frags {
-  bf16x8 a[4], b[4];
+  bf16x8 a[I], b[J];
 };
 
-// operand fragments of K substep s (16 values of K) of one stage: A rows wm*128 + i*32 + lane%32
-__device__ __forceinline__ void load_frags(Frags& f, const char* stage, uint32_t offA, uint32_t offB) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    f.a[i] = *(const bf16x8*)(stage + offA + i * (32 * kBK * 2));
-    f.b[i] = *(const bf16x8*)(stage + kStageBytes + offB + i * (32 * kBK * 2));
-  }
-}
-
-__device__ __forceinline__ void mma16(const Frags& f, f32x16 (&acc)[4][4]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
-}
-
-// interleave hint for one half stage: 16 MFMAs with 8 LDS reads spread between them
-__device__ __forceinline__ void sched_half_stage() {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
-  }
-}
-
-// The pipelined main loop shared by both GEMMs.
+// One wavefront's share of the tile product.
+//   I x J   MFMA blocks (32 x 32) of this wavefront; I * J == 16.
+//   NI / NJ: only the first NI (NJ) blocks of that dimension hold rows (ragged tile); the others
+//   are neither read nor multiplied.  They are template parameters, not run-time values: branches
+//   around single MFMAs would push the accumulators out of their registers.
+// The main loop below is shared by both GEMMs:
 //   begin(st): fix the ring slot and the K offsets of stage st (called once per stage, in order);
-//   one(q):    enqueue this thread's q-th DMA load (0..kLoadsPerStage-1) of the stage begun last.
+//   one(q):    enqueue this thread's q-th DMA load (0..NLOADS-1) of the stage begun last; loads 0..3
+//              bring the weight tile, load 4+g brings pair rows 64g .. 64g+63 (only those that exist).
 // On return every DMA has completed and acc holds the tile.
 //
-// Per stage a wavefront issues 32 MFMAs (1024 matrix-core cycles), 16 LDS reads and 8 DMA loads.
-// With one wavefront per SIMD nothing else hides an instruction that stalls the stream, so the
-// reads and loads are threaded between the MFMAs by hand and pinned with scheduling barriers.
-template <class Begin, class One>
-__device__ __forceinline__ void mainloop(int n, Begin&& begin, One&& one, const char* lds, int wm, int wn, int lane,
-                                         f32x16 (&acc)[4][4]) {
-  const int r32 = lane & 31, half = lane >> 5;
-  const int sw = (r32 >> 2) & 3;
-  // byte offsets inside a stage's A / B tile for substep 0 and 1
-  const uint32_t rowA = (uint32_t)(wm * 128 + r32) * (kBK * 2), rowB = (uint32_t)(wn * 128 + r32) * (kBK * 2);
-  const uint32_t c0 = (uint32_t)((half ^ sw) * 16), c1 = (uint32_t)(((2 + half) ^ sw) * 16);
-  Frags f0, f1;
-  if (n <= 0) return;
-  auto issue_all = [&](int st) {
-    begin(st);
-#pragma unroll
-    for (int q = 0; q < kLoadsPerStage; ++q) one(q);
-  };
-  issue_all(0);
-  if (n > 1) issue_all(1);
-  if (n > 2) issue_all(2);
-  if (n > 2) wait_vm<2 * kLoadsPerStage>();
-  else if (n > 1) wait_vm<kLoadsPerStage>();
-  else wait_vm<0>();
-  block_barrier();
-  load_frags(f0, lds, rowA + c0, rowB + c0);
+// Per stage a wavefront issues 32 MFMAs (1024 matrix-core cycles), I+J LDS reads per substep and 8
+// DMA loads.  With one wavefront per SIMD nothing else hides an instruction that stalls the
+// stream, so the reads and loads are threaded between the MFMAs by hand and pinned with
+// scheduling barriers.
+template <int I, int J, int NI, int NJ, int NLOADS>
+struct WaveTile {
+  static_assert(I * J == 16, "256 accumulator registers");
+  static_assert(NLOADS >= 1 && NLOADS <= kLoadsPerStage, "DMA loads per thread and stage");
+  f32x16 acc[I][J];
+  uint32_t offA, offB;  // byte offset of this lane's row in the A / B tile of a stage (block 0)
+  uint32_t c0, c1;      // swizzled chunk offset of substep 0 / 1
 
-  // first half of a stage: multiply substep 0 while the substep 1 operands stream in from LDS
-  auto first_half = [&](int st) {
-    const char* cur = lds + (st % kStages) * kStagePair;
-    load_frags(f1, cur, rowA + c1, rowB + c1);
-    mma16(f0, acc);
-    sched_half_stage();
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  int st = 0;
-  for (; st + 3 < n; ++st) {
-    first_half(st);
-    // stage st+1 must have landed for every wave (st+2 may still be in flight); after the barrier
-    // every wave has also finished reading stage st-1, whose slot stage st+3 takes
-    wait_vm<kLoadsPerStage>();
-    block_barrier();
-    begin(st + 3);
-    // second half: multiply substep 1; between the MFMAs, enqueue stage st+3 and fetch substep 0 of stage st+1
-    const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
+  __device__ __forceinline__ void init(int a_row0, int b_row0, int lane) {
+    const int r32 = lane & 31, half = lane >> 5;
+    const int sw = (r32 >> 2) & 3;
+    offA = (uint32_t)(a_row0 + r32) * kRowBytes;
+    offB = (uint32_t)(b_row0 + r32) * kRowBytes + kStageBytes;
+    c0 = (uint32_t)((half ^ sw) * 16);
+    c1 = (uint32_t)(((2 + half) ^ sw) * 16);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[0], acc[i][0], 0, 0, 0);
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[1], acc[i][1], 0, 0, 0);
-      one(2 * i);
-      f0.a[i] = *(const bf16x8*)(nxt + rowA + c0 + i * (32 * kBK * 2));
-      __builtin_amdgcn_sched_barrier(0);
-      acc[i][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[2], acc[i][2], 0, 0, 0);
-      acc[i][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[i], f1.b[3], acc[i][3], 0, 0, 0);
-      one(2 * i + 1);
-      f0.b[i] = *(const bf16x8*)(nxt + kStageBytes + rowB + c0 + i * (32 * kBK * 2));
-      __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < I; ++i)
+#pragma unroll
+      for (int j = 0; j < J; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  }
+
+  static constexpr __device__ __forceinline__ bool act_i(int i) { return i < NI; }
+  static constexpr __device__ __forceinline__ bool act_j(int j) { return j < NJ; }
+
+  // k-th fragment read of a substep, in the order the MFMA sequence first needs them:
+  // a0, b0 .. b(J-1), a1 .. a(I-1)
+  __device__ __forceinline__ void read_k(Frags<I, J>& f, const char* stage, uint32_t c, int k) const {
+    if (k == 0) {
+      f.a[0] = *(const bf16x8*)(stage + offA + c);
+    } else if (k <= J) {
+      const int j = k - 1;
+      if (act_j(j)) f.b[j] = *(const bf16x8*)(stage + offB + c + j * (32 * kRowBytes));
+    } else {
+      const int i = k - J;
+      if (act_i(i)) f.a[i] = *(const bf16x8*)(stage + offA + c + i * (32 * kRowBytes));
     }
   }
-  for (; st + 1 < n; ++st) {  // last stages: nothing left to enqueue
-    first_half(st);
-    if (st + 2 < n) wait_vm<kLoadsPerStage>();
+
+  __device__ __forceinline__ void read_all(Frags<I, J>& f, const char* stage, uint32_t c) const {
+#pragma unroll
+    for (int k = 0; k < I + J; ++k) read_k(f, stage, c, k);
+  }
+
+  // 16 MFMAs on `cur`; between them the I+J reads of the next substep into `nxt` and, if DMA,
+  // the 8 loads of a later stage.
+  template <bool READS, bool DMA, class One>
+  __device__ __forceinline__ void half_stage(const Frags<I, J>& cur, Frags<I, J>& nxt, const char* nxt_stage, uint32_t nxt_c,
+                                            One&& one) {
+    constexpr int R = I + J;
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      const int i = m / J, j = m % J;
+      if (act_i(i) && act_j(j)) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      if (DMA && (m & 1) && (m >> 1) < NLOADS) one(m >> 1);
+      if (READS) {
+#pragma unroll
+        for (int k = (m * R) / 16; k < ((m + 1) * R) / 16; ++k) read_k(nxt, nxt_stage, nxt_c, k);
+      }
+      if (m & 1) __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  template <class Begin, class One>
+  __device__ __forceinline__ void mainloop(int n, Begin&& begin, One&& one, const char* lds) {
+    Frags<I, J> f0, f1;
+    if (n <= 0) return;
+    auto issue_all = [&](int st) {
+      begin(st);
+#pragma unroll
+      for (int q = 0; q < NLOADS; ++q) one(q);
+    };
+    issue_all(0);
+    if (n > 1) issue_all(1);
+    if (n > 2) issue_all(2);
+    if (n > 2) wait_vm<2 * NLOADS>();
+    else if (n > 1) wait_vm<NLOADS>();
     else wait_vm<0>();
     block_barrier();
-    const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
-    load_frags(f0, nxt, rowA + c0, rowB + c0);
-    mma16(f1, acc);
-    sched_half_stage();
-    __builtin_amdgcn_sched_barrier(0);
+    read_all(f0, lds, c0);
+    // c1 is first needed inside the loop; if the register allocator parked it in scratch, make it
+    // come back (and be waited for) here, so that no s_waitcnt vmcnt(0) lands inside the loop
+    // and drains the DMA queue every iteration
+    asm volatile("" ::"v"(c1), "v"(offA), "v"(offB));
+    int st = 0;
+    for (; st + 3 < n; ++st) {
+      const char* cur = lds + (st % kStages) * kStagePair;
+      // first half: multiply substep 0 while the substep 1 operands stream in from LDS
+      half_stage<true, false>(f0, f1, cur, c1, one);
+      // stage st+1 must have landed for every wave (st+2 may still be in flight); after the barrier
+      // every wave has also finished reading stage st-1, whose slot stage st+3 takes
+      wait_vm<NLOADS>();
+      block_barrier();
+      begin(st + 3);
+      // second half: multiply substep 1; between the MFMAs enqueue stage st+3 and fetch substep 0 of stage st+1
+      const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
+      half_stage<true, true>(f1, f0, nxt, c0, one);
+    }
+    for (; st + 1 < n; ++st) {  // last stages: nothing left to enqueue
+      const char* cur = lds + (st % kStages) * kStagePair;
+      half_stage<true, false>(f0, f1, cur, c1, one);
+      if (st + 2 < n) wait_vm<NLOADS>();
+      else wait_vm<0>();
+      block_barrier();
+      const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
+      half_stage<true, false>(f1, f0, nxt, c0, one);
+    }
+    const char* last = lds + ((n - 1) % kStages) * kStagePair;
+    half_stage<true, false>(f0, f1, last, c1, one);
+    half_stage<false, false>(f1, f0, last, c0, one);
   }
-  const char* last = lds + ((n - 1) % kStages) * kStagePair;
-  load_frags(f1, last, rowA + c1, rowB + c1);
-  mma16(f0, acc);
-  mma16(f1, acc);
-}
+};
 
 // ------------------------------------------------------------------------------------- GEMM-1
-__global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int32_t* counters = (const int32_t*)(ws + L.o_counters);
-  const int item_id = xcd_remap(blockIdx.x);
-  if (item_id >= counters[0]) return;
-  const Item1 it = ((const Item1*)(ws + L.o_items1))[item_id];
-  const int32_t* row_token = (const int32_t*)(ws + L.o_row_token);
-  const uint8_t* row_bits = (const uint8_t*)(ws + L.o_row_bits);
-  const bool sh = it.e == L.E_res;
-  const int KS1 = L.D / kBK;
-  const int Fp = sh ? L.F_shT : L.Fp;
-  const int ld = sh ? L.F_shT : L.F;
-  const char* wbase = sh ? packed + L.p_sw13 + (int64_t)it.jt * KS1 * kStageBytes
-                         : packed + L.p_w13 + (((int64_t)it.e * L.P + it.p) * L.NT1 + it.jt) * KS1 * kStageBytes;
-  const i32x4 rsW = make_rsrc(wbase, (uint32_t)(KS1 * kStageBytes));
-  const i32x4 rsX = make_rsrc(x, (uint32_t)((int64_t)T * L.D * 2));
+struct G1Args {
+  Item1 it;
+  bool sh;
+  int KS1, Fp, ld, hrow0;
+  i32x4 rsW, rsX;
+  uint32_t xoff[4], woff, lds_w;
+  const uint8_t* row_bits;
+  uint16_t* H;
+};
 
-  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = w >> 1, wn = w & 1;
-  // activation gather: this thread copies chunk (tid & 3) of rows i*64 + (tid >> 2)
-  uint32_t xoff[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = i * 64 + (tid >> 2);
-    const int rr = r < it.nrows ? r : it.nrows - 1;  // rows past the end re-read the last valid row
-    const int tok = row_token[it.row0 + rr];
-    xoff[i] = (uint32_t)tok * (uint32_t)(L.D * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
-  }
-  const uint32_t woff = (uint32_t)tid * 16;
-  // LDS byte address of this wavefront's 1 KiB slice of each 4 KiB slab
-  const uint32_t lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
-
+// MFMA A = weight rows, B = pair rows.  Weight rows come in blocks of 32: block 2b is the gate
+// projection of neurons 32b .. 32b+31 of the tile, block 2b+1 their up projection.
+template <int I, int J, int NJ>
+__device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int tid) {
+  // Each instantiation derives its lane-dependent offsets from its own opaque copy of the thread
+  // id: shared, they would stay live across all the instantiations of the kernel and be parked in
+  // scratch, and a scratch reload inside a main loop waits for vmcnt(0), which drains the DMA queue.
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  // the ragged layout (J == 8) walks all pair rows: only the 64-row groups that exist are loaded
+  WaveTile<I, J, I, NJ, (J == 8 ? 4 + (NJ * 32 + 63) / 64 : kLoadsPerStage)> t;
+  t.init(a_row0, b_row0, lane);
   uint32_t slot = 0, sW = 0, sX = 0;
   auto begin = [&](int st) {
-    slot = (uint32_t)(st % kStages) * kStagePair + lds_w;
+    slot = (uint32_t)(st % kStages) * kStagePair + g.lds_w;
     sW = (uint32_t)(st * kStageBytes);
-    sX = (uint32_t)(st * (kBK * 2));
+    sX = (uint32_t)(st * kRowBytes);
   };
   auto one = [&](int q) {
-    if (q < 4) dma16(rsW, slot + q * 4096, woff, sW + q * 4096);
-    else dma16(rsX, slot + kStageBytes + (q - 4) * 4096, xoff[q - 4], sX);
+    if (q < 4) dma16(g.rsW, slot + q * 4096, g.woff, sW + q * 4096);
+    else dma16(g.rsX, slot + kStageBytes + (q - 4) * 4096, g.xoff[q - 4], sX);
   };
+  t.mainloop(g.KS1, begin, one, lds);
 
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  mainloop(KS1, begin, one, lds, wm, wn, lane, acc);
-
-  // epilogue: MFMA A = weight rows (gate rows 0..63, up rows 64..127 of this wave), B = pair rows.
-  // acc[i][j][v]: weight row i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row wn*128 + j*32 + lane%32.
-  // Swish(gate) * up is rounded to bf16 and parked in LDS as a [256 rows][128 neurons] tile
-  // (rows padded to 272 bytes against bank conflicts), then written out in whole 256-byte row
-  // segments: 16 lanes per row, 16 bytes per lane.
+  // epilogue.  acc[i][j][v]: weight row a_row0 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row
+  // b_row0 + j*32 + lane%32.  Swish(gate) * up is rounded to bf16 and parked in LDS as a
+  // [256 rows][128 neurons] tile (rows padded to 272 bytes against bank conflicts), then written
+  // out in whole 256-byte row segments: 16 lanes per row, 16 bytes per lane.
   constexpr int kHsRow = kMfmaNeur * 2 + 16;
   block_barrier();  // every wave is done reading the last stage
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int r = wn * 128 + j * 32 + (lane & 31);
-    const bool kept = r < it.nrows && ((row_bits[it.row0 + (r < it.nrows ? r : 0)] >> it.p) & 1);
-    char* srow = lds + r * kHsRow + (wm * 64 + (lane >> 5) * 4) * 2;
+  for (int j = 0; j < NJ; ++j) {
+    const int r = b_row0 + j * 32 + (lane & 31);
+    const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < I; i += 2) {
+      const int nb = (a_row0 >> 5) + i;  // weight block index; neurons of the tile: (nb/2)*32 ..
+      char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (lane >> 5) * 4) * 2;
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
         bf16x2 lo, hi;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const float g = acc[i][j][vq * 4 + c], u = acc[i + 2][j][vq * 4 + c];
-          const float h = kept ? g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u : 0.f;  // Swish(g) * u, Eq. 4
+          const float gt = t.acc[i][j][vq * 4 + c], up = t.acc[i + 1][j][vq * 4 + c];
+          const float h = kept ? gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up : 0.f;  // Swish(gate) * up, Eq. 4
           if (c < 2) lo[c] = (__bf16)h;
           else hi[c - 2] = (__bf16)h;
         }
         uint2 pk;
         pk.x = __builtin_bit_cast(uint32_t, lo);
         pk.y = __builtin_bit_cast(uint32_t, hi);
-        *(uint2*)(srow + (i * 32 + vq * 8) * 2) = pk;
+        *(uint2*)(srow + vq * 16) = pk;
       }
     }
+    __builtin_amdgcn_sched_barrier(0);  // one block of rows at a time: keeps the register pressure of the epilogue low
   }
   __syncthreads();
-  uint16_t* H = sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
-  const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
-  const int n_in = it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
-  if (n_in < Fp) {
+  const int n_in = g.it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
+  if (n_in < g.Fp) {
 #pragma unroll 4
     for (int c = 0; c < 16; ++c) {
       const int r = c * 16 + (tid >> 4);
-      if (r < it.nrows) {
+      if (r < g.it.nrows) {
         const uint4 v = *(const uint4*)(lds + r * kHsRow + (tid & 15) * 16);
-        *(uint4*)(H + (size_t)(hrow0 + r) * ld + (size_t)it.p * Fp + n_in) = v;
+        *(uint4*)(g.H + (size_t)(g.hrow0 + r) * g.ld + (size_t)g.it.p * g.Fp + n_in) = v;
       }
     }
   }
 }
 
+__global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int32_t* counters = (const int32_t*)(ws + L.o_counters);
+  const int item_id = xcd_remap(blockIdx.x);
+  if (item_id >= counters[0]) return;
+  G1Args g;
+  g.it = ((const Item1*)(ws + L.o_items1))[item_id];
+  const int32_t* row_token = (const int32_t*)(ws + L.o_row_token);
+  g.row_bits = (const uint8_t*)(ws + L.o_row_bits);
+  g.sh = g.it.e == L.E_res;
+  g.KS1 = L.D / kBK;
+  g.Fp = g.sh ? L.F_shT : L.Fp;
+  g.ld = g.sh ? L.F_shT : L.F;
+  const char* wbase = g.sh ? packed + L.p_sw13 + (int64_t)g.it.jt * g.KS1 * kStageBytes
+                           : packed + L.p_w13 + (((int64_t)g.it.e * L.P + g.it.p) * L.NT1 + g.it.jt) * g.KS1 * kStageBytes;
+  g.rsW = make_rsrc(wbase, (uint32_t)(g.KS1 * kStageBytes));
+  g.rsX = make_rsrc(x, (uint32_t)((int64_t)T * L.D * 2));
+  g.H = g.sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
+  g.hrow0 = g.sh ? g.it.row0 : g.it.row0 - L.sh_rows;
+
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // activation gather: this thread copies chunk (tid & 3) of rows i*64 + (tid >> 2)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = i * 64 + (tid >> 2);
+    const int rr = r < g.it.nrows ? r : g.it.nrows - 1;  // rows past the end re-read the last valid row
+    const int tok = row_token[g.it.row0 + rr];
+    g.xoff[i] = (uint32_t)tok * (uint32_t)(L.D * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
+  }
+  g.woff = (uint32_t)tid * 16;
+  g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
+
+  if (g.it.nrows == kMfmaBM) {
+    gemm1_tile<4, 4, 4>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts, 128 x 128 each
+  } else {  // 4 x 1: 64 weight rows x the ceil(nrows/32) blocks of pair rows that exist
+    switch ((g.it.nrows + 31) >> 5) {
+      case 1: gemm1_tile<2, 8, 1>(g, lds, w * 64, 0, tid); break;
+      case 2: gemm1_tile<2, 8, 2>(g, lds, w * 64, 0, tid); break;
+      case 3: gemm1_tile<2, 8, 3>(g, lds, w * 64, 0, tid); break;
+      case 4: gemm1_tile<2, 8, 4>(g, lds, w * 64, 0, tid); break;
+      case 5: gemm1_tile<2, 8, 5>(g, lds, w * 64, 0, tid); break;
+      case 6: gemm1_tile<2, 8, 6>(g, lds, w * 64, 0, tid); break;
+      case 7: gemm1_tile<2, 8, 7>(g, lds, w * 64, 0, tid); break;
+      default: gemm1_tile<2, 8, 8>(g, lds, w * 64, 0, tid); break;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------- GEMM-2
+struct G2Args {
+  Item2 it;
+  int np, KSp, nstages, D;
+  i32x4 rsW, rsH;
+  uint32_t hoff[4], woff, lds_w;
+  float* Yp;
+};
+
+// MFMA A = pair rows of H, B = output columns of W2.
+template <int I, int J, int NI>
+__device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
+  asm volatile("" : "+v"(tid));  // see gemm1_tile
+  const int lane = tid & 63;
+  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage)> t;
+  t.init(a_row0, b_row0, lane);
+  // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
+  // begin() is called with increasing st, so a running cursor maps st -> K position.
+  int p_cur = 0, k_in = 0;
+  while (p_cur < g.np && !((g.it.kmask >> p_cur) & 1)) ++p_cur;
+  uint32_t slot = 0, sW = 0, sH = 0;
+  auto begin = [&](int st) {
+    const int kt = p_cur * g.KSp + k_in;
+    if (++k_in == g.KSp) {
+      k_in = 0;
+      ++p_cur;
+      while (p_cur < g.np && !((g.it.kmask >> p_cur) & 1)) ++p_cur;
+    }
+    slot = (uint32_t)(st % kStages) * kStagePair + g.lds_w;
+    sH = (uint32_t)(kt * kRowBytes);
+    sW = (uint32_t)(kt * kStageBytes);
+  };
+  auto one = [&](int q) {
+    if (q < 4) dma16(g.rsW, slot + kStageBytes + q * 4096, g.woff, sW + q * 4096);
+    else dma16(g.rsH, slot + (q - 4) * 4096, g.hoff[q - 4], sH);
+  };
+  t.mainloop(g.nstages, begin, one, lds);
+
+  // epilogue: acc[i][j][v]: pair row a_row0 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, column b_row0 + j*32 + lane%32
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = a_row0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      if (r >= g.it.nrows) continue;
+      float* yrow = g.Yp + (size_t)(g.it.row0 + r) * g.D + g.it.jd * kMfmaBN2;
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int c = b_row0 + j * 32 + (lane & 31);
+        if (g.it.jd * kMfmaBN2 + c < g.D) yrow[c] = t.acc[i][j][v];
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const char* packed, char* ws) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   const int item_id = xcd_remap(blockIdx.x);
   if (item_id >= counters[1]) return;
-  const Item2 it = ((const Item2*)(ws + L.o_items2))[item_id];
-  const bool sh = it.e == L.E_res;
+  G2Args g;
+  g.it = ((const Item2*)(ws + L.o_items2))[item_id];
+  const bool sh = g.it.e == L.E_res;
   const int Fp = sh ? L.F_shT : L.Fp;
   const int ld = sh ? L.F_shT : L.F;
-  const int KT = ld / kBK;        // stages of the whole expert
-  const int KSp = Fp / kBK;       // stages of one partition
-  const char* wbase = sh ? packed + L.p_sw2 + (int64_t)it.jd * KT * kStageBytes
-                         : packed + L.p_w2 + ((int64_t)it.e * L.ND2 + it.jd) * KT * kStageBytes;
+  const int KT = ld / kBK;  // stages of the whole expert
+  g.KSp = Fp / kBK;         // stages of one partition
+  g.np = sh ? 1 : L.P;
+  g.D = L.D;
+  const char* wbase = sh ? packed + L.p_sw2 + (int64_t)g.it.jd * KT * kStageBytes
+                         : packed + L.p_w2 + ((int64_t)g.it.e * L.ND2 + g.it.jd) * KT * kStageBytes;
   const uint16_t* H = sh ? (const uint16_t*)(ws + L.o_Hs) : (const uint16_t*)(ws + L.o_H);
-  const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
+  const int hrow0 = sh ? g.it.row0 : g.it.row0 - L.sh_rows;
   const char* hbase = (const char*)(H + (size_t)hrow0 * ld);
-  const i32x4 rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
-  const i32x4 rsH = make_rsrc(hbase, (uint32_t)((int64_t)it.nrows * ld * 2));
+  g.rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
+  g.rsH = make_rsrc(hbase, (uint32_t)((int64_t)g.it.nrows * ld * 2));
+  g.Yp = (float*)(ws + L.o_Yp);
 
-  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = w >> 1, wn = w & 1;
-  uint32_t hoff[4];
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = i * 64 + (tid >> 2);
-    const int rr = r < it.nrows ? r : it.nrows - 1;
-    hoff[i] = (uint32_t)rr * (uint32_t)(ld * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
+    const int rr = r < g.it.nrows ? r : g.it.nrows - 1;
+    g.hoff[i] = (uint32_t)rr * (uint32_t)(ld * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
   }
-  const uint32_t woff = (uint32_t)tid * 16;
-  const uint32_t lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
+  g.woff = (uint32_t)tid * 16;
+  g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
+  g.nstages = 0;
+  for (int p = 0; p < g.np; ++p) g.nstages += ((g.it.kmask >> p) & 1) ? g.KSp : 0;
 
-  // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
-  // begin() is called with increasing st, so a running cursor maps st -> K position.
-  const int np = sh ? 1 : L.P;
-  int nstages = 0;
-  for (int p = 0; p < np; ++p) nstages += ((it.kmask >> p) & 1) ? KSp : 0;
-  int p_cur = 0, k_in = 0;
-  while (p_cur < np && !((it.kmask >> p_cur) & 1)) ++p_cur;
-  uint32_t slot = 0, sW = 0, sH = 0;
-  auto begin = [&](int st) {
-    const int kt = p_cur * KSp + k_in;
-    if (++k_in == KSp) {
-      k_in = 0;
-      ++p_cur;
-      while (p_cur < np && !((it.kmask >> p_cur) & 1)) ++p_cur;
-    }
-    slot = (uint32_t)(st % kStages) * kStagePair + lds_w;
-    sH = (uint32_t)(kt * (kBK * 2));
-    sW = (uint32_t)(kt * kStageBytes);
-  };
-  auto one = [&](int q) {
-    if (q < 4) dma16(rsH, slot + q * 4096, hoff[q], sH);
-    else dma16(rsW, slot + kStageBytes + (q - 4) * 4096, woff, sW + (q - 4) * 4096);
-  };
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  mainloop(nstages, begin, one, lds, wm, wn, lane, acc);
-
-  // epilogue: acc[i][j][v]: pair row wm*128 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, column wn*128 + j*32 + lane%32
-  float* Yp = (float*)(ws + L.o_Yp);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int r = wm * 128 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-      if (r >= it.nrows) continue;
-      float* yrow = Yp + (size_t)(it.row0 + r) * L.D + it.jd * kMfmaBN2;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int c = wn * 128 + j * 32 + (lane & 31);
-        if (it.jd * kMfmaBN2 + c < L.D) yrow[c] = acc[i][j][v];
-      }
+  if (g.it.nrows == kMfmaBM) {
+    gemm2_tile<4, 4, 4>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
+  } else {  // 1 x 4: the ceil(nrows/32) blocks of pair rows that exist x 64 columns
+    switch ((g.it.nrows + 31) >> 5) {
+      case 1: gemm2_tile<8, 2, 1>(g, lds, 0, w * 64, tid); break;
+      case 2: gemm2_tile<8, 2, 2>(g, lds, 0, w * 64, tid); break;
+      case 3: gemm2_tile<8, 2, 3>(g, lds, 0, w * 64, tid); break;
+      case 4: gemm2_tile<8, 2, 4>(g, lds, 0, w * 64, tid); break;
+      case 5: gemm2_tile<8, 2, 5>(g, lds, 0, w * 64, tid); break;
+      case 6: gemm2_tile<8, 2, 6>(g, lds, 0, w * 64, tid); break;
+      case 7: gemm2_tile<8, 2, 7>(g, lds, 0, w * 64, tid); break;
+      default: gemm2_tile<8, 2, 8>(g, lds, 0, w * 64, tid); break;
     }
   }
 }

@@ -7,7 +7,8 @@
 // MFMA layout (bf16): 16 KiB "stage images", each the exact LDS contents of one operand tile of
 //   one pipeline stage, rows of kBK = 32 K-values with the 16-byte chunks XOR-rotated (swz_chunk):
 //   W13  stage ((e*P + p)*NT1 + jt)*(D/32) + ks : 256 weight rows x 32 values of d; weight row
-//        wm*128 + gu*64 + j  is neuron  p*Fp + jt*128 + wm*64 + j  of W1 (gu=0) or W3 (gu=1)
+//        q*64 + gu*32 + j  is neuron  p*Fp + jt*128 + q*32 + j  of W1 (gu=0) or W3 (gu=1): every 64
+//        weight rows hold the gate and the up projection of the same 32 neurons
 //   W2   stage (e*ND2 + jd)*(F/32) + kt : 256 output columns x 32 neurons (positions kt*32..)
 //   neurons / columns past the end are zero.
 #include "common.h"
@@ -88,9 +89,9 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
       r /= nt1;
       const int p = sh ? 0 : (int)(r % L.P);
       const int e = sh ? 0 : (int)(r / L.P);
-      const int wm = row >> 7, gu = (row >> 6) & 1, j = row & 63;
+      const int q = row >> 6, gu = (row >> 5) & 1, j = row & 31;
       const int Fp = sh ? L.F_shT : L.Fp;
-      const int nin = jt * kMfmaNeur + wm * 64 + j;  // neuron inside the partition
+      const int nin = jt * kMfmaNeur + q * 32 + j;  // neuron inside the partition
       const int d0 = ks * kBK + lc * 8;
       if (nin < Fp) {
         if (!sh) {
