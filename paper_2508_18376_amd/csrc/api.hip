@@ -77,7 +77,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_w = take(npairs * 4);
   L.o_keep = take(npairs);
   L.o_pair_row = take(npairs * 4);
-  L.o_bin_count = take((int64_t)L.nbins * 4);
+  L.o_bin_count = take((int64_t)cdiv(Tm, kRouteBlockTokens) * L.nbins * 4);  // one histogram row per route block
   L.o_cursor = take((int64_t)L.nbins * 4);
   L.o_exp_nrows = take((int64_t)L.E_res * 4);
   L.o_exp_row0 = take((int64_t)L.E_res * 4);
@@ -241,8 +241,7 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
     mark(b);                \
     if (err == hipSuccess) err = (call); \
   } while (0)
-  // bin_count and cursor are adjacent: one fill clears both
-  DSMOE_STEP(0, launch_fill_i32((int32_t*)(ws + L.o_bin_count), (L.o_exp_nrows - L.o_bin_count) / 4, 0, s));
+  mark(0);  // (slot 0 was a clearing kernel; the route kernel now writes whole histogram rows)
   DSMOE_STEP(1, launch_route(L, logits, T, tau, (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w), (uint8_t*)(ws + L.o_keep),
                              (int32_t*)(ws + L.o_bin_count), nullptr, s));
   DSMOE_STEP(2, launch_plan(L, T, ws, s));

@@ -11,6 +11,7 @@ constexpr int kMaxTopK = 16;
 constexpr int kMaxExperts = 512;
 constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
+constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels (one histogram row each)
 
 // MFMA path tile shape: 256 rows (token-expert pairs) x 128 neurons (gate+up = 256 weight rows)
 // for GEMM-1, 256 rows x 256 output columns for GEMM-2, K stage 32.

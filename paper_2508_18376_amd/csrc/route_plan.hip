@@ -27,7 +27,7 @@ struct RouteArgs {
   int32_t* idx;
   float* w;
   uint8_t* keep;
-  int32_t* bin_count;    // forward: [nbins] sort-bin histogram (may be null)
+  int32_t* bin_count;    // forward: [blocks][nbins] sort-bin histogram, one row per block (may be null)
   int32_t* group_count;  // stand-alone: [E*P] kept units per sub-expert (may be null)
   int T, E, K, P, lo, hi, renorm, nsub_bits, nsub, nhist;
 };
@@ -58,7 +58,7 @@ __device__ __forceinline__ void count_pair(int32_t* hist, int bits, int e, const
   }
 }
 
-// One lane per token; all E logits of the token live in that lane's registers (E <= EPAD <= 64).
+// One lane per token; all E logits of the token live in that lane's registers (E <= EPAD <= 32).
 template <int EPAD, int KMAX>
 __global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
   extern __shared__ int32_t hist[];
@@ -119,10 +119,8 @@ __global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
   const int nb = a.bin_count ? (a.hi - a.lo) * a.nsub : 0;
   for (int i = threadIdx.x; i < a.nhist; i += 64) {
     int c = hist[i];
-    if (c) {
-      if (i < nb) atomicAdd(&a.bin_count[i], c);
-      else atomicAdd(&a.group_count[i - nb], c);
-    }
+    if (i < nb) a.bin_count[(size_t)blockIdx.x * nb + i] = c;  // this block's row of the histogram: no atomics
+    else if (c) atomicAdd(&a.group_count[i - nb], c);
   }
 }
 
@@ -135,70 +133,92 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One wavefront per token, LPT logits per lane (64 < E <= 64*LPT).  Every logit gets its rank
-// under (value descending, index ascending); ranks below K are the selected slots.
+// One wavefront per token, LPT logits per lane (E <= 64*LPT).  Every logit gets its rank under
+// (value descending, index ascending); ranks below K are the selected slots.  A block is sixteen
+// wavefronts that walk kWaveTokens tokens and share one LDS histogram.
+constexpr int kWaveTokens = kRouteBlockTokens;  // tokens per block
+
 template <int LPT>
-__global__ __launch_bounds__(64) void route_wave_kernel(RouteArgs a) {
-  const int t = blockIdx.x;
-  const int lane = threadIdx.x;
-  float l[LPT];
+__global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
+  extern __shared__ int32_t hist[];
+  for (int i = threadIdx.x; i < a.nhist; i += 1024) hist[i] = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int t_end = min(a.T, ((int)blockIdx.x + 1) * kWaveTokens);
+  // all logits of this wavefront's tokens are requested before the first is used
+  constexpr int kTokPerWave = kWaveTokens / 16;
+  float lall[kTokPerWave][LPT];
 #pragma unroll
-  for (int i = 0; i < LPT; ++i) {
-    int e = lane + 64 * i;
-    l[i] = (e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
+  for (int u = 0; u < kTokPerWave; ++u) {
+    const int t = blockIdx.x * kWaveTokens + wv + 16 * u;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      int e = lane + 64 * i;
+      lall[u][i] = (t < t_end && e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
+    }
   }
-  float m = l[0];
 #pragma unroll
-  for (int i = 1; i < LPT; ++i) m = fmaxf(m, l[i]);
-  m = wave_max(m);
-  float z = 0.f;
+  for (int u = 0; u < kTokPerWave; ++u) {
+    const int t = blockIdx.x * kWaveTokens + wv + 16 * u;
+    if (t >= t_end) break;
+    float l[LPT];
 #pragma unroll
-  for (int i = 0; i < LPT; ++i)
-    if (lane + 64 * i < a.E) z += expf(l[i] - m);
-  z = wave_sum(z);
-  int rank[LPT];
+    for (int i = 0; i < LPT; ++i) l[i] = lall[u][i];
+    float m = l[0];
 #pragma unroll
-  for (int i = 0; i < LPT; ++i) rank[i] = 0;
-  for (int j = 0; j < 64; ++j) {
+    for (int i = 1; i < LPT; ++i) m = fmaxf(m, l[i]);
+    m = wave_max(m);
+    float z = 0.f;
 #pragma unroll
-    for (int i2 = 0; i2 < LPT; ++i2) {
-      float ov = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l[i2]), j));
-      int oe = j + 64 * i2;
-      if (oe < a.E) {
+    for (int i = 0; i < LPT; ++i)
+      if (lane + 64 * i < a.E) z += expf(l[i] - m);
+    z = wave_sum(z);
+    int rank[LPT];
 #pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-          int e = lane + 64 * i;
-          rank[i] += (ov > l[i] || (ov == l[i] && oe < e)) ? 1 : 0;
+    for (int i = 0; i < LPT; ++i) rank[i] = 0;
+    for (int j = 0; j < 64; ++j) {
+#pragma unroll
+      for (int i2 = 0; i2 < LPT; ++i2) {
+        float ov = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l[i2]), j));
+        int oe = j + 64 * i2;
+        if (oe < a.E) {
+#pragma unroll
+          for (int i = 0; i < LPT; ++i) {
+            int e = lane + 64 * i;
+            rank[i] += (ov > l[i] || (ov == l[i] && oe < e)) ? 1 : 0;
+          }
         }
       }
     }
-  }
-  float ssum = 0.f;
-  float s[LPT];
+    float ssum = 0.f;
+    float s[LPT];
 #pragma unroll
-  for (int i = 0; i < LPT; ++i) {
-    bool selq = (lane + 64 * i < a.E) && rank[i] < a.K;
-    s[i] = selq ? expf(l[i] - m) / z : 0.f;
-    ssum += s[i];
-  }
-  ssum = wave_sum(ssum);
+    for (int i = 0; i < LPT; ++i) {
+      bool selq = (lane + 64 * i < a.E) && rank[i] < a.K;
+      s[i] = selq ? expf(l[i] - m) / z : 0.f;  // Eq. 1
+      ssum += s[i];
+    }
+    ssum = wave_sum(ssum);
 #pragma unroll
-  for (int i = 0; i < LPT; ++i) {
-    int e = lane + 64 * i;
-    if (e < a.E && rank[i] < a.K) {
-      float n = s[i] / ssum;
-      int bits = keep_bits_of(n, e, a);
-      size_t o = (size_t)t * a.K + rank[i];
-      a.idx[o] = e;
-      a.w[o] = a.renorm ? n : s[i];
-      a.keep[o] = (uint8_t)bits;
-      if (bits) {
-        if (a.bin_count) atomicAdd(&a.bin_count[(e - a.lo) * a.nsub + sub_of_bits(bits, a.nsub_bits)], 1);
-        if (a.group_count)
-          for (int p = 0; p < a.P; ++p)
-            if ((bits >> p) & 1) atomicAdd(&a.group_count[e * a.P + p], 1);
+    for (int i = 0; i < LPT; ++i) {
+      int e = lane + 64 * i;
+      if (e < a.E && rank[i] < a.K) {
+        float n = s[i] / ssum;  // Sec. 4.1: normalise over the K selected
+        int bits = keep_bits_of(n, e, a);
+        size_t o = (size_t)t * a.K + rank[i];
+        a.idx[o] = e;
+        a.w[o] = a.renorm ? n : s[i];
+        a.keep[o] = (uint8_t)bits;
+        count_pair(hist, bits, e, a);
       }
     }
+  }
+  __syncthreads();
+  const int nb = a.bin_count ? (a.hi - a.lo) * a.nsub : 0;
+  for (int i = threadIdx.x; i < a.nhist; i += 1024) {
+    int c = hist[i];
+    if (i < nb) a.bin_count[(size_t)blockIdx.x * nb + i] = c;  // this block's row of the histogram: no atomics
+    else if (c) atomicAdd(&a.group_count[i - nb], c);
   }
 }
 
@@ -223,18 +243,18 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
   a.nsub = L.nsub;
   a.nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   a.nhist = (bin_count ? L.nbins : 0) + (group_count ? L.E * L.P : 0);
-  if (L.E <= 64) {
+  const size_t sh = sizeof(int32_t) * (size_t)(a.nhist > 0 ? a.nhist : 1);
+  if (L.E <= 32) {  // few experts: a lane per token, no cross-lane traffic
     dim3 grid((T + 63) / 64), block(64);
-    size_t sh = sizeof(int32_t) * (size_t)(a.nhist > 0 ? a.nhist : 1);
     if (L.E <= 8) route_lane_kernel<8, 8><<<grid, block, sh, s>>>(a);
     else if (L.E <= 16) route_lane_kernel<16, 16><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 32) route_lane_kernel<32, 16><<<grid, block, sh, s>>>(a);
-    else route_lane_kernel<64, 16><<<grid, block, sh, s>>>(a);
-  } else {
-    dim3 grid(T), block(64);
-    if (L.E <= 128) route_wave_kernel<2><<<grid, block, 0, s>>>(a);
-    else if (L.E <= 256) route_wave_kernel<4><<<grid, block, 0, s>>>(a);
-    else route_wave_kernel<8><<<grid, block, 0, s>>>(a);
+    else route_lane_kernel<32, 16><<<grid, block, sh, s>>>(a);
+  } else {  // many experts: a wavefront per token
+    dim3 grid((T + kWaveTokens - 1) / kWaveTokens), block(1024);
+    if (L.E <= 64) route_wave_kernel<1><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 128) route_wave_kernel<2><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 256) route_wave_kernel<4><<<grid, block, sh, s>>>(a);
+    else route_wave_kernel<8><<<grid, block, sh, s>>>(a);
   }
   return hipGetLastError();
 }
@@ -273,12 +293,26 @@ __device__ int block_excl_scan(int32_t* a, int n, int32_t* tmp) {
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, char* ws) {
   extern __shared__ int32_t sm[];
+  // 0. column sums of the route kernel's per-block histograms -> bins[] in LDS
+  int32_t* bin_count = sm;  // [nbins]
+  {
+    const int32_t* blk_hist = (const int32_t*)(ws + L.o_bin_count);
+    const int nblk = (T + kRouteBlockTokens - 1) / kRouteBlockTokens;
+    for (int i = threadIdx.x; i < L.nbins; i += kPlanThreads) bin_count[i] = 0;
+    __syncthreads();
+    const int total = nblk * L.nbins;
+    for (int i = threadIdx.x; i < total; i += kPlanThreads) {
+      int c = blk_hist[i];
+      if (c) atomicAdd(&bin_count[i % L.nbins], c);
+    }
+    __syncthreads();
+  }
   const int tid = threadIdx.x;
   const int E_res = L.E_res;
   const int has_sh = L.n_shared > 0 ? 1 : 0;
   const int E_tot = E_res + has_sh;
   const int NG = E_tot * L.P;  // (expert, partition) groups; the shared pseudo-expert only uses p = 0
-  int32_t* ne = sm;                 // [E_tot] rows of each expert
+  int32_t* ne = sm + L.nbins;       // [E_tot] rows of each expert
   int32_t* rs = ne + E_tot + 1;     // [E_tot] first row (tile aligned)
   int32_t* ts = rs + E_tot + 1;     // [E_tot] first tile
   int32_t* pt = ts + E_tot + 1;     // [E_tot+1] first tile by POSITION in the row space
@@ -286,15 +320,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   int32_t* gb = ga + NG + 1;        // [NG+1] item base of each group
   int32_t* tmp = gb + NG + 1;       // [kPlanThreads]
 
-  const int32_t* bin_count = (const int32_t*)(ws + L.o_bin_count);
   int32_t* cursor = (int32_t*)(ws + L.o_cursor);
   int32_t* exp_nrows = (int32_t*)(ws + L.o_exp_nrows);
   int32_t* exp_row0 = (int32_t*)(ws + L.o_exp_row0);
   int32_t* counters = (int32_t*)(ws + L.o_counters);
-  int32_t* tile_e = (int32_t*)(ws + L.o_tile_e);
-  int32_t* tile_row0 = (int32_t*)(ws + L.o_tile_row0);
-  int32_t* tile_nrows = (int32_t*)(ws + L.o_tile_nrows);
-  int32_t* tile_bits = (int32_t*)(ws + L.o_tile_bits);
   int32_t* act_rank = (int32_t*)(ws + L.o_act_rank);
   Item1* items1 = (Item1*)(ws + L.o_items1);
   Item2* items2 = (Item2*)(ws + L.o_items2);
@@ -338,8 +367,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     for (int s2 = 0; s2 < sb; ++s2) off += bin_count[e * L.nsub + s2];
     cursor[b] = off;
   }
-  // 4. row tiles; tile g belongs to the expert at the last position whose first tile is <= g
-  for (int g = tid; g < total_tiles; g += kPlanThreads) {
+  // 4. row tiles are described on the fly from the LDS tables (no round trip through global memory):
+  //    tile g belongs to the expert at the last position whose first tile is <= g
+  auto tile_expert = [&](int g) {
     int lo_i = 0, hi_i = E_tot;  // first position with pt > g
     while (lo_i < hi_i) {
       int mid = (lo_i + hi_i) >> 1;
@@ -347,41 +377,37 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       else lo_i = mid + 1;
     }
     const int pos = lo_i - 1;
-    const int e = has_sh ? (pos == 0 ? E_res : pos - 1) : pos;
-    const int i = g - ts[e];
+    return has_sh ? (pos == 0 ? E_res : pos - 1) : pos;
+  };
+  // partitions kept by some row of tile i of expert e (OR of the keep patterns of the bins it overlaps)
+  auto tile_bits_of = [&](int e, int i) {
+    if (e >= E_res) return 1;
     const int r0 = i * BM, r1 = min(ne[e], r0 + BM);
-    int bits = 0;
-    if (e < E_res) {
-      int off = 0;
-      for (int sb = 0; sb < L.nsub; ++sb) {
-        int c = bin_count[e * L.nsub + sb];
-        if (c > 0 && off < r1 && off + c > r0) {
-          int rev = L.nsub - 1 - sb;
-          int pat = 0;
-          for (int p = 0; p < nsub_bits; ++p) pat |= ((rev >> (nsub_bits - 1 - p)) & 1) << p;
-          if (L.P > nsub_bits) pat |= ((1 << L.P) - 1) & ~((1 << nsub_bits) - 1);  // partitions outside the sort key: assume kept
-          bits |= pat;
-        }
-        off += c;
+    int bits = 0, off = 0;
+    for (int sb = 0; sb < L.nsub; ++sb) {
+      int c = bin_count[e * L.nsub + sb];
+      if (c > 0 && off < r1 && off + c > r0) {
+        int rev = L.nsub - 1 - sb;
+        int pat = 0;
+        for (int p = 0; p < nsub_bits; ++p) pat |= ((rev >> (nsub_bits - 1 - p)) & 1) << p;
+        if (L.P > nsub_bits) pat |= ((1 << L.P) - 1) & ~((1 << nsub_bits) - 1);  // partitions outside the sort key: assume kept
+        bits |= pat;
       }
-    } else {
-      bits = 1;
+      off += c;
     }
-    tile_e[g] = e;
-    tile_row0[g] = rs[e] + r0;
-    tile_nrows[g] = r1 - r0;
-    tile_bits[g] = bits;
-  }
-  __syncthreads();
+    return bits;
+  };
   // 5. GEMM-2 items: every tile x every output column tile, column tiles innermost
   for (int it = tid; it < total_tiles * L.ND2; it += kPlanThreads) {
-    int g = it / L.ND2, jd = it % L.ND2;
+    const int g = it / L.ND2, jd = it % L.ND2;
+    const int e = tile_expert(g);
+    const int i = g - ts[e];
     Item2 v;
-    v.row0 = tile_row0[g];
-    v.nrows = tile_nrows[g];
-    v.e = tile_e[g];
+    v.row0 = rs[e] + i * BM;
+    v.nrows = min(ne[e] - i * BM, BM);
+    v.e = e;
     v.jd = jd;
-    v.kmask = tile_bits[g];
+    v.kmask = tile_bits_of(e, i);
     v.pad0 = v.pad1 = v.pad2 = 0;
     items2[it] = v;
   }
@@ -391,9 +417,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     int nt = (ne[e] + BM - 1) / BM;
     int cnt = 0;
     for (int i = 0; i < nt; ++i) {
-      int g = ts[e] + i;
-      bool act = (tile_bits[g] >> p) & 1;
-      act_rank[(size_t)g * L.P + p] = act ? cnt : -1;
+      bool act = (tile_bits_of(e, i) >> p) & 1;
+      act_rank[(size_t)(ts[e] + i) * L.P + p] = act ? cnt : -1;
       cnt += act ? 1 : 0;
     }
     ga[gidx] = cnt;
@@ -402,27 +427,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   __syncthreads();
   int total1 = block_excl_scan(gb, NG, tmp);
   // 7. GEMM-1 items in the order (expert, partition, neuron tile, row tile): the row tiles that
-  //    share one weight tile are adjacent.
-  const int NTmax = L.NT1 > L.NT1_sh ? L.NT1 : L.NT1_sh;
-  const int64_t span = (int64_t)total_tiles * L.P * NTmax;
-  for (int64_t q = tid; q < span; q += kPlanThreads) {
-    int jt = (int)(q % NTmax);
-    int64_t r = q / NTmax;
-    int p = (int)(r % L.P);
-    int g = (int)(r / L.P);
-    int e = tile_e[g];
-    int nt1 = e < E_res ? L.NT1 : L.NT1_sh;
-    int rk = act_rank[(size_t)g * L.P + p];
-    if (jt < nt1 && rk >= 0) {
-      int gi = e * L.P + p;
-      Item1 v;
-      v.row0 = tile_row0[g];
-      v.nrows = tile_nrows[g];
-      v.e = e;
-      v.p = p;
+  //    share one weight tile are adjacent.  One thread per (row tile, partition): it looks its
+  //    tile up once and writes the items of all neuron tiles.
+  for (int q = tid; q < total_tiles * L.P; q += kPlanThreads) {
+    const int p = q % L.P, g = q / L.P;
+    const int rk = act_rank[(size_t)g * L.P + p];
+    if (rk < 0) continue;
+    const int e = tile_expert(g);
+    const int nt1 = e < E_res ? L.NT1 : L.NT1_sh;
+    const int gi = e * L.P + p;
+    const int i = g - ts[e];
+    Item1 v;
+    v.row0 = rs[e] + i * BM;
+    v.nrows = min(ne[e] - i * BM, BM);
+    v.e = e;
+    v.p = p;
+    v.pad0 = v.pad1 = v.pad2 = 0;
+    Item1* dst = items1 + gb[gi] + rk;
+    for (int jt = 0; jt < nt1; ++jt) {
       v.jt = jt;
-      v.pad0 = v.pad1 = v.pad2 = 0;
-      items1[gb[gi] + jt * ga[gi] + rk] = v;
+      dst[(size_t)jt * ga[gi]] = v;
     }
   }
   if (tid == 0) {
@@ -436,7 +460,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
   const int E_tot = L.E_res + (L.n_shared > 0 ? 1 : 0);
   const int NG = E_tot * L.P;
-  size_t sh = sizeof(int32_t) * (size_t)(4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + 8);
+  size_t sh = sizeof(int32_t) * (size_t)(L.nbins + 4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + 8);
   plan_kernel<<<dim3(1), dim3(kPlanThreads), sh, s>>>(L, T, ws);
   return hipGetLastError();
 }
@@ -500,7 +524,7 @@ hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s) {
 // ------------------------------------------------------------------------------------- combine
 // y[t] = sum_k g[t][k] * Yp[row(t,k)] (+ Yp[shared row t]); Eq. 3 restricted to the kept units.
 // One writer per output element, slots added in slot order: no atomics.
-template <typename OutT>
+template <typename OutT, int KB>
 __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const char* ws, OutT* y) {
   const float* Yp = (const float*)(ws + L.o_Yp);
   const float* w = (const float*)(ws + L.o_w);
@@ -510,24 +534,28 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
   if (q >= (int64_t)T * D4) return;
   const int t = (int)(q / D4);
   const int d = (int)(q % D4) * 4;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int k = 0; k < L.K; ++k) {
-    int row = pair_row[(size_t)t * L.K + k];
-    if (row >= 0) {
-      float g = w[(size_t)t * L.K + k];
-      float4 v = *(const float4*)(Yp + (size_t)row * L.D + d);
-      acc.x += g * v.x;
-      acc.y += g * v.y;
-      acc.z += g * v.z;
-      acc.w += g * v.w;
-    }
+  // all row indices first, then all row loads in flight together, then the sum in slot order
+  int row[KB];
+  float g[KB];
+#pragma unroll
+  for (int k = 0; k < KB; ++k) {
+    row[k] = k < L.K ? pair_row[(size_t)t * L.K + k] : -1;
+    g[k] = k < L.K ? w[(size_t)t * L.K + k] : 0.f;
   }
-  if (L.n_shared > 0) {
-    float4 v = *(const float4*)(Yp + (size_t)t * L.D + d);
-    acc.x += v.x;
-    acc.y += v.y;
-    acc.z += v.z;
-    acc.w += v.w;
+  float4 v[KB];
+#pragma unroll
+  for (int k = 0; k < KB; ++k)
+    v[k] = row[k] >= 0 ? *(const float4*)(Yp + (size_t)row[k] * L.D + d) : make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (L.n_shared > 0) acc = *(const float4*)(Yp + (size_t)t * L.D + d);  // shared rows sit first in the row space
+#pragma unroll
+  for (int k = 0; k < KB; ++k) {
+    if (row[k] >= 0) {
+      acc.x += g[k] * v[k].x;
+      acc.y += g[k] * v[k].y;
+      acc.z += g[k] * v[k].z;
+      acc.w += g[k] * v[k].w;
+    }
   }
   if constexpr (sizeof(OutT) == 4) {
     *(float4*)((float*)y + (size_t)t * L.D + d) = acc;
@@ -566,8 +594,16 @@ hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t
   if (L.D % 4 == 0) {
     int64_t n = (int64_t)T * (L.D / 4);
     dim3 grid((unsigned)((n + 255) / 256)), block(256);
-    if (L.dtype == DSMOE_F32) combine_kernel<float><<<grid, block, 0, s>>>(L, T, ws, (float*)y);
-    else combine_kernel<uint16_t><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y);
+#define DSMOE_COMBINE(KB)                                                                      \
+  do {                                                                                          \
+    if (L.dtype == DSMOE_F32) combine_kernel<float, KB><<<grid, block, 0, s>>>(L, T, ws, (float*)y); \
+    else combine_kernel<uint16_t, KB><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y);             \
+  } while (0)
+    if (L.K <= 2) DSMOE_COMBINE(2);
+    else if (L.K <= 4) DSMOE_COMBINE(4);
+    else if (L.K <= 8) DSMOE_COMBINE(8);
+    else DSMOE_COMBINE(16);
+#undef DSMOE_COMBINE
   } else {
     int64_t n = (int64_t)T * L.D;
     dim3 grid((unsigned)((n + 255) / 256)), block(256);
