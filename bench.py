@@ -197,6 +197,30 @@ def main():
                 "unit": "TFLOP/s", "frac": g1_ach / BF16_PEAK_TFLOPS, "traffic": read_traffic(spec.name),
                 "avg_launch_ms": primary["gemm1_ms"], "flops_per_launch": g1_flops}
 
+    # reconstruction step that precedes the path (Sec. 4.2 b): importance of this batch used as the
+    # calibration set (every routed pair, no drops) and the order made from it; timed on its own
+    def ev_ms(fn, n):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    imp = torch.empty((spec.E_res, spec.F), dtype=torch.float32, device=dev)
+    perm_out = torch.empty((spec.E_res, spec.F), dtype=torch.int32, device=dev)
+    n_rec = max(2, K // 5)
+    rec_ms = ev_ms(lambda: ds.moe_profile_importance(layer.ctx, layer.packed, x, logits, spec.T, 3, imp, layer.workspace,
+                                                     stream), n_rec)
+    perm_ms = ev_ms(lambda: ds.moe_importance_to_perm(layer.ctx, imp, perm_out, stream), n_rec)
+    rec_flops = 4.0 * spec.D * spec.F * int(resident.sum())
+    reconstruction = {"profile_importance_ms": rec_ms, "profile_importance_tflops": rec_flops / (rec_ms * 1e-3) / 1e12,
+                      "importance_to_perm_ms": perm_ms, "calibration_tokens": spec.T, "metric": 3}
+    log("reconstruction: importance of %d tokens %.3f ms (%.0f TFLOP/s), order %.3f ms"
+        % (spec.T, rec_ms, reconstruction["profile_importance_tflops"], perm_ms))
+
     # proportionality of the time saved at the primary rate, against the 0 % run
     t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
     prop = None
@@ -242,7 +266,7 @@ def main():
             round(100 * args.primary_rate), 100 * primary["drop_rate"]),
             "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
-        "sweep": sweep, "proportionality": prop, "kernels": kernels,
+        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction,
         "roofline": roofline, "cpu_baseline": cpu, "check": check,
     }
     print(json.dumps(out))

@@ -122,6 +122,28 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, co
                            int32_t T, void* y, void* workspace, void* stream);
 
 /*
+ * Neuron importance profiling on calibration tokens (Sec. 4.2 b): for every resident expert e and
+ * ORIGINAL neuron q, the sum over the calibration tokens routed to e (Top-K, nothing dropped) of
+ *   metric 0  Swish(x W1_q)            1  |Swish(x W1_q)|
+ *   metric 2  Swish(x W1_q) (x W3_q)   3  |Swish(x W1_q) (x W3_q)|
+ *   packed      device, made by moe_partition_weights with perm == NULL (identity) for this ctx
+ *   x, logits   device [T][D] / float [T][E]: the calibration tokens
+ *   importance  device float [E_res][F], fully overwritten (0 for an expert no token routes to)
+ *   workspace   as for moe_dualsparse_forward (its contents are overwritten)
+ * bf16 layers store each term as bf16 before the fp32 row sum.  Asynchronous, no allocation.
+ */
+int moe_profile_importance(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, int32_t T,
+                           int32_t metric, float* importance, void* workspace, void* stream);
+
+/*
+ * Reconstruction order from an importance table (Sec. 4.2 b: the major sub-expert takes the most
+ * important neurons): perm[e][j] = neuron with the j-th largest importance[e][.], equal values by
+ * ascending neuron id.  importance device float [E_res][F], perm device int32 [E_res][F].  The
+ * result is what moe_partition_weights takes as perm.  NaN importances give an unspecified order.
+ */
+int moe_importance_to_perm(dsmoe_ctx* ctx, const float* importance, int32_t* perm, void* stream);
+
+/*
  * Inspection of the last forward call's plan, for tests: byte offsets into the workspace.
  * Fills out[0..DSMOE_PLAN_FIELDS-1]; returns the number of fields.
  *   0 topk_idx int32[T*K]      1 topk_w float[T*K]        2 keep_bits uint8[T*K]

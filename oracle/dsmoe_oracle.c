@@ -21,6 +21,7 @@
  *     renorm != 0 the combine weight is the normalised score, for models that normalise anyway.
  *   - load-aware thresholds enter only as a per-expert threshold table (Sec. 4.3).
  *   - shared experts are always on, weight 1, never partitioned or dropped (Sec. 5.3.1 text).
+ *   - neuron importance profiling: the four accumulated metrics of Sec. 4.2 b.
  *
  * Readings where the text leaves a choice: Top-K is taken on the logits, ordered by value
  * descending then index ascending (ties go to the lower index); a unit is kept iff n >= tau
@@ -221,4 +222,52 @@ int dsmoe_oracle_forward(const void* x, const float* logits, const void* w1, con
     free(tn);
   }
   return bad ? -1 : 0;
+}
+
+/*
+ * Neuron importance profiling on calibration tokens (Sec. 4.2 b, the four accumulated metrics):
+ * for every resident expert e and ORIGINAL neuron q, the sum over the calibration tokens that
+ * route to e (Top-K of Eq. 2, nothing dropped) of
+ *   metric 0: Swish(x . W1[:, q])                      accumulated gate value
+ *   metric 1: |Swish(x . W1[:, q])|                    accumulated absolute gate value
+ *   metric 2: Swish(x . W1[:, q]) * (x . W3[:, q])     accumulated gate-up value
+ *   metric 3: |Swish(x . W1[:, q]) * (x . W3[:, q])|   accumulated absolute gate-up value
+ * imp [hi-lo][F] double.  abs_sum (may be NULL) [hi-lo][F]: the sum of the absolute values of the
+ * same terms (the scale rounding errors of a reduced-precision implementation live on).
+ */
+int dsmoe_oracle_importance(const void* x, const float* logits, const void* w1, const void* w3, int T, int D, int F,
+                            int E, int K, int lo, int hi, int dtype, int metric, double* imp, double* abs_sum) {
+  if (T < 0 || D < 1 || F < 1 || E < 1 || K < 1 || K > E || lo < 0 || hi > E || lo > hi) return -1;
+  if (metric < 0 || metric > 3 || (dtype != 0 && dtype != 1)) return -1;
+  const size_t n = (size_t)(hi - lo) * F;
+  for (size_t i = 0; i < n; ++i) imp[i] = 0.0;
+  if (abs_sum)
+    for (size_t i = 0; i < n; ++i) abs_sum[i] = 0.0;
+  double* a = (double*)malloc(sizeof(double) * F);
+  double* b = (double*)malloc(sizeof(double) * F);
+  int32_t* ti = (int32_t*)malloc(sizeof(int32_t) * K);
+  double* ts = (double*)malloc(sizeof(double) * K);
+  double* tn = (double*)malloc(sizeof(double) * K);
+  for (int t = 0; t < T; ++t) {
+    gate_token(logits + (size_t)t * E, E, K, ti, ts, tn);
+    for (int k = 0; k < K; ++k) {
+      int e = ti[k];
+      if (e < lo || e >= hi) continue;
+      size_t r = (size_t)(e - lo);
+      xw(x, (size_t)t * D, w1, r * D * F, D, F, dtype, a);
+      if (metric >= 2) xw(x, (size_t)t * D, w3, r * D * F, D, F, dtype, b);
+      for (int q = 0; q < F; ++q) {
+        double v = swish(a[q]);
+        if (metric >= 2) v *= b[q];
+        imp[r * F + q] += (metric & 1) ? fabs(v) : v;
+        if (abs_sum) abs_sum[r * F + q] += fabs(v);
+      }
+    }
+  }
+  free(a);
+  free(b);
+  free(ti);
+  free(ts);
+  free(tn);
+  return 0;
 }

@@ -127,3 +127,35 @@ def forward(x: np.ndarray, logits: np.ndarray, w1: np.ndarray, w3: np.ndarray, w
     if rc != 0:
         raise ValueError("dsmoe_oracle_forward: bad argument")
     return y
+
+
+def importance(x: np.ndarray, logits: np.ndarray, w1: np.ndarray, w3: np.ndarray, K: int, metric: int, lo: int = 0,
+               hi: Optional[int] = None):
+    """Accumulated neuron importance [E_res][F] (float64) and the sum of the terms' absolute values."""
+    dtype = 1 if x.dtype == np.uint16 else 0
+    el = np.uint16 if dtype else np.float32
+    x = np.ascontiguousarray(x, dtype=el)
+    w1 = np.ascontiguousarray(w1, dtype=el)
+    w3 = np.ascontiguousarray(w3, dtype=el)
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, D = x.shape
+    E = logits.shape[1]
+    hi = E if hi is None else hi
+    E_res, _, F = w1.shape
+    assert E_res == hi - lo and w3.shape == w1.shape and logits.shape[0] == T
+    L = _load()
+    L.dsmoe_oracle_importance.restype = ctypes.c_int
+    imp = np.empty((E_res, F), dtype=np.float64)
+    ab = np.empty((E_res, F), dtype=np.float64)
+    rc = L.dsmoe_oracle_importance(_p(x), _p(logits), _p(w1), _p(w3), T, D, F, E, K, lo, hi, dtype, int(metric), _p(imp), _p(ab))
+    if rc != 0:
+        raise ValueError("dsmoe_oracle_importance: bad argument")
+    return imp, ab
+
+
+def perm_from_importance(imp: np.ndarray) -> np.ndarray:
+    """perm[e][j] = neuron with the j-th largest importance, ties to the lower neuron id (Sec. 4.2 b)."""
+    out = np.empty(imp.shape, dtype=np.int32)
+    for e in range(imp.shape[0]):
+        out[e] = np.lexsort((np.arange(imp.shape[1]), -imp[e])).astype(np.int32)
+    return out

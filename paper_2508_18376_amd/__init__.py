@@ -20,5 +20,7 @@ from .binding import (  # noqa: F401
     moe_partition_weights,
     moe_route_and_mask,
     moe_dualsparse_forward,
+    moe_profile_importance,
+    moe_importance_to_perm,
     lib_path,
 )

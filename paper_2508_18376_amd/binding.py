@@ -57,6 +57,10 @@ def _load() -> ctypes.CDLL:
     L.moe_route_and_mask.restype = ctypes.c_int
     L.moe_dualsparse_forward.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
     L.moe_dualsparse_forward.restype = ctypes.c_int
+    L.moe_profile_importance.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
+    L.moe_profile_importance.restype = ctypes.c_int
+    L.moe_importance_to_perm.argtypes = [vp, vp, vp, vp]
+    L.moe_importance_to_perm.restype = ctypes.c_int
     L.dsmoe_plan_layout.argtypes = [vp, i64p]
     L.dsmoe_plan_layout.restype = ctypes.c_int
     L.dsmoe_profile_begin.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -161,6 +165,16 @@ def moe_dualsparse_forward(ctx, packed, x, logits, tau, T, y, workspace, stream=
     _check(rc, ctx, "moe_dualsparse_forward")
 
 
+def moe_profile_importance(ctx, packed, x, logits, T, metric, importance, workspace, stream=None) -> None:
+    rc = _lib.moe_profile_importance(ctx, _ptr(packed), _ptr(x), _ptr(logits), int(T), int(metric), _ptr(importance),
+                                     _ptr(workspace), _stream(stream))
+    _check(rc, ctx, "moe_profile_importance")
+
+
+def moe_importance_to_perm(ctx, importance, perm, stream=None) -> None:
+    _check(_lib.moe_importance_to_perm(ctx, _ptr(importance), _ptr(perm), _stream(stream)), ctx, "moe_importance_to_perm")
+
+
 class DualSparseLayer:
     """Owns a context plus its packed-weight and workspace buffers (torch allocations)."""
 
@@ -205,6 +219,19 @@ class DualSparseLayer:
         with torch.cuda.device(self.device):
             moe_dualsparse_forward(self.ctx, self.packed, x, logits, tau, T, y, self.workspace)
         return y
+
+    def profile_importance(self, x, logits, metric):
+        """Importance [E_res][F] of the calibration tokens x (weights must be packed with perm=None)."""
+        imp = torch.empty((self.hi - self.lo, self.F), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_profile_importance(self.ctx, self.packed, x, logits, x.shape[0], metric, imp, self.workspace)
+        return imp
+
+    def importance_to_perm(self, importance):
+        perm = torch.empty((self.hi - self.lo, self.F), dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_importance_to_perm(self.ctx, importance, perm)
+        return perm
 
     def plan(self, T):
         """Copies of the last forward call's plan arrays (for tests)."""

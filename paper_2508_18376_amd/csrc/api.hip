@@ -94,6 +94,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_H = take((int64_t)(L.row_cap - L.sh_rows) * L.F * elem);
   L.o_Hs = take((int64_t)L.sh_rows * L.F_shT * elem);
   L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
+  L.o_tau0 = take((int64_t)L.E * L.P * 4);
   L.ws_bytes = o;
 
   // packed weights
@@ -246,8 +247,8 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
                              (int32_t*)(ws + L.o_bin_count), nullptr, s));
   DSMOE_STEP(2, launch_plan(L, T, ws, s));
   DSMOE_STEP(3, launch_scatter(L, T, ws, s));
-  DSMOE_STEP(4, L.mfma ? launch_gemm1_mfma(L, T, (const char*)packed, x, ws, s)
-                       : launch_gemm1_generic(L, T, (const char*)packed, x, ws, s));
+  DSMOE_STEP(4, L.mfma ? launch_gemm1_mfma(L, T, (const char*)packed, x, ws, 0, s)
+                       : launch_gemm1_generic(L, T, (const char*)packed, x, ws, 0, s));
   DSMOE_STEP(5, L.mfma ? launch_gemm2_mfma(L, T, (const char*)packed, ws, s) : launch_gemm2_generic(L, T, (const char*)packed, ws, s));
   DSMOE_STEP(6, launch_combine(L, T, ws, y, s));
   mark(kNumKernels);
@@ -320,6 +321,39 @@ int dsmoe_profile_end(dsmoe_ctx* ctx_, float* ms, int* calls) {
   free(pf.ev);
   pf = Profile();
   return rc;
+}
+
+int moe_profile_importance(dsmoe_ctx* ctx_, const void* packed, const void* x, const float* logits, int32_t T, int32_t metric,
+                           float* importance, void* workspace, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !packed || !importance || !workspace || metric < 0 || metric > 3) return DSMOE_EINVAL;
+  if (T > 0 && (!x || !logits)) return DSMOE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  if (T > L.max_tokens) return DSMOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  // every routed pair takes part: thresholds of zero keep all units
+  hipError_t err = launch_fill_i32((int32_t*)(ws + L.o_tau0), (int64_t)L.E * L.P, 0, s);
+  if (err == hipSuccess && T > 0)
+    err = launch_route(L, logits, T, (const float*)(ws + L.o_tau0), (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w),
+                       (uint8_t*)(ws + L.o_keep), (int32_t*)(ws + L.o_bin_count), nullptr, s);
+  if (err == hipSuccess) err = launch_plan(L, T, ws, s);
+  if (err == hipSuccess) err = launch_scatter(L, T, ws, s);
+  if (err == hipSuccess)
+    err = L.mfma ? launch_gemm1_mfma(L, T, (const char*)packed, x, ws, 1 + metric, s)
+                 : launch_gemm1_generic(L, T, (const char*)packed, x, ws, 1 + metric, s);
+  if (err == hipSuccess) err = launch_colsum(L, ws, importance, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_importance_to_perm(dsmoe_ctx* ctx_, const float* importance, int32_t* perm, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || !importance || !perm) return DSMOE_EINVAL;
+  hipError_t err = launch_perm_from_importance(ctx->L, importance, perm, (hipStream_t)stream);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
 }
 
 int dsmoe_plan_layout(const dsmoe_ctx* ctx_, int64_t* out) {

@@ -52,7 +52,7 @@ struct Layout {
   // workspace byte offsets
   int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
   int64_t o_tile_e, o_tile_row0, o_tile_nrows, o_tile_bits, o_act_rank, o_items1, o_items2;
-  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, ws_bytes;
+  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, ws_bytes;
   // packed weights byte offsets
   int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes;
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
@@ -89,9 +89,13 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s);
-hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+// epi: what GEMM-1 stores per (row, neuron): 0 = Swish(gate)*up (the layer), 1..4 = the profiling
+// metrics Swish(gate), |Swish(gate)|, Swish(gate)*up, |Swish(gate)*up|
+hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s);
 hipError_t launch_gemm2_generic(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
-hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s);
+hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s);
+hipError_t launch_colsum(const Layout& L, const char* ws, float* importance, hipStream_t s);
+hipError_t launch_perm_from_importance(const Layout& L, const float* importance, int32_t* perm, hipStream_t s);
 hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
 hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const void* w2, const void* sw1, const void* sw3,
                        const void* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh, hipStream_t s);
@@ -106,7 +110,19 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest,
   return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float silu_f32(float a) { return a / (1.0f + expf(-a)); }       // Swish, beta = 1
-__device__ __forceinline__ float silu_fast(float a) { return a / (1.0f + __expf(-a)); }
+__device__ __forceinline__ float silu_fast(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
+// value GEMM-1 stores for gate g and up u (see launch_gemm1_*): Eq. 4's inner term, or one of the
+// four importance metrics of Sec. 4.2 b
+template <bool FAST>
+__device__ __forceinline__ float epi_value(int epi, float g, float u) {
+  const float sg = FAST ? silu_fast(g) : silu_f32(g);
+  switch (epi) {
+    case 1: return sg;
+    case 2: return fabsf(sg);
+    case 4: return fabsf(sg * u);
+    default: return sg * u;  // 0 (layer) and 3
+  }
+}
 
 // Position of the 16-byte chunk `chunk` (0..3) of row `row` inside a [rows][32] bf16 LDS tile
 // (64-byte rows).  The chunks of a row are XOR-rotated by bits 2..3 of the row so that an MFMA

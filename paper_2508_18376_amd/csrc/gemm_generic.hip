@@ -24,7 +24,7 @@ __device__ __forceinline__ void stf<uint16_t>(uint16_t* p, size_t i, float v) { 
 constexpr int GK = 16;  // K step
 
 template <typename T>
-__global__ __launch_bounds__(256) void gemm1_generic_kernel(Layout L, const char* packed, const T* x, char* ws) {
+__global__ __launch_bounds__(256) void gemm1_generic_kernel(Layout L, const char* packed, const T* x, char* ws, int epi) {
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   if ((int)blockIdx.x >= counters[0]) return;
   const Item1 it = ((const Item1*)(ws + L.o_items1))[blockIdx.x];
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void gemm1_generic_kernel(Layout L, const char
     for (int j = 0; j < 4; ++j) {
       int c = tx * 4 + j;
       if (c >= ncols) continue;
-      float h = kept ? silu_f32(a1[i][j]) * a3[i][j] : 0.f;
+      float h = kept ? epi_value<false>(epi, a1[i][j], a3[i][j]) : 0.f;
       stf<T>(H, (size_t)(hrow0 + r) * ld + col0 + c, h);
     }
   }
@@ -156,11 +156,11 @@ __global__ __launch_bounds__(256) void gemm2_generic_kernel(Layout L, const char
   }
 }
 
-hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s) {
+hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s) {
   if (T <= 0) return hipSuccess;
   dim3 block(256), grid(items1_bound(L, T));
-  if (L.dtype == DSMOE_F32) gemm1_generic_kernel<float><<<grid, block, 0, s>>>(L, packed, (const float*)x, ws);
-  else gemm1_generic_kernel<uint16_t><<<grid, block, 0, s>>>(L, packed, (const uint16_t*)x, ws);
+  if (L.dtype == DSMOE_F32) gemm1_generic_kernel<float><<<grid, block, 0, s>>>(L, packed, (const float*)x, ws, epi);
+  else gemm1_generic_kernel<uint16_t><<<grid, block, 0, s>>>(L, packed, (const uint16_t*)x, ws, epi);
   return hipGetLastError();
 }
 

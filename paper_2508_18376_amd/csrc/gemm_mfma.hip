@@ -219,7 +219,7 @@ struct WaveTile {
 struct G1Args {
   Item1 it;
   bool sh;
-  int KS1, Fp, ld, hrow0;
+  int KS1, Fp, ld, hrow0, epi;
   i32x4 rsW, rsX;
   uint32_t xoff[4], woff, lds_w;
   const uint8_t* row_bits;
@@ -228,7 +228,7 @@ struct G1Args {
 
 // MFMA A = weight rows, B = pair rows.  Weight rows come in blocks of 32: block 2b is the gate
 // projection of neurons 32b .. 32b+31 of the tile, block 2b+1 their up projection.
-template <int I, int J, int NJ>
+template <int I, int J, int NJ, bool PROFILE>
 __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int tid) {
   // Each instantiation derives its lane-dependent offsets from its own opaque copy of the thread
   // id: shared, they would stay live across all the instantiations of the kernel and be parked in
@@ -270,7 +270,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const float gt = t.acc[i][j][vq * 4 + c], up = t.acc[i + 1][j][vq * 4 + c];
-          const float h = kept ? gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up : 0.f;  // Swish(gate) * up, Eq. 4
+          const float h = kept ? epi_value<true>(PROFILE ? g.epi : 0, gt, up) : 0.f;  // Swish(gate) * up (Eq. 4), or a profiling metric
           if (c < 2) lo[c] = (__bf16)h;
           else hi[c - 2] = (__bf16)h;
         }
@@ -296,7 +296,10 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   }
 }
 
-__global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws) {
+// PROFILE = false is the layer's kernel (epilogue fixed at compile time); PROFILE = true picks the
+// importance metric of the epilogue at run time (epi 1..4), which costs a few per cent.
+template <bool PROFILE>
+__global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws, int epi) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   const int item_id = xcd_remap(blockIdx.x);
@@ -315,6 +318,7 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   g.rsX = make_rsrc(x, (uint32_t)((int64_t)T * L.D * 2));
   g.H = g.sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
   g.hrow0 = g.sh ? g.it.row0 : g.it.row0 - L.sh_rows;
+  g.epi = epi;
 
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   // activation gather: this thread copies chunk (tid & 3) of rows i*64 + (tid >> 2)
@@ -329,17 +333,17 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
 
   if (g.it.nrows == kMfmaBM) {
-    gemm1_tile<4, 4, 4>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts, 128 x 128 each
+    gemm1_tile<4, 4, 4, PROFILE>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts, 128 x 128 each
   } else {  // 4 x 1: 64 weight rows x the ceil(nrows/32) blocks of pair rows that exist
     switch ((g.it.nrows + 31) >> 5) {
-      case 1: gemm1_tile<2, 8, 1>(g, lds, w * 64, 0, tid); break;
-      case 2: gemm1_tile<2, 8, 2>(g, lds, w * 64, 0, tid); break;
-      case 3: gemm1_tile<2, 8, 3>(g, lds, w * 64, 0, tid); break;
-      case 4: gemm1_tile<2, 8, 4>(g, lds, w * 64, 0, tid); break;
-      case 5: gemm1_tile<2, 8, 5>(g, lds, w * 64, 0, tid); break;
-      case 6: gemm1_tile<2, 8, 6>(g, lds, w * 64, 0, tid); break;
-      case 7: gemm1_tile<2, 8, 7>(g, lds, w * 64, 0, tid); break;
-      default: gemm1_tile<2, 8, 8>(g, lds, w * 64, 0, tid); break;
+      case 1: gemm1_tile<2, 8, 1, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 2: gemm1_tile<2, 8, 2, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 3: gemm1_tile<2, 8, 3, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 4: gemm1_tile<2, 8, 4, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 5: gemm1_tile<2, 8, 5, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 6: gemm1_tile<2, 8, 6, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 7: gemm1_tile<2, 8, 7, PROFILE>(g, lds, w * 64, 0, tid); break;
+      default: gemm1_tile<2, 8, 8, PROFILE>(g, lds, w * 64, 0, tid); break;
     }
   }
 }
@@ -454,7 +458,9 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
 static hipError_t set_lds_attr() {
   static bool attr_set = false;
   if (attr_set) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  hipError_t e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
@@ -463,12 +469,13 @@ static hipError_t set_lds_attr() {
 }
 
 // grids are whole chunks of 256 blocks so that the XCD remap is a bijection
-hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, hipStream_t s) {
+hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s) {
   if (T <= 0) return hipSuccess;
   hipError_t e = set_lds_attr();
   if (e != hipSuccess) return e;
   const int g1 = (items1_bound(L, T) + 255) & ~255;
-  gemm1_mfma_kernel<<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws);
+  if (epi == 0) gemm1_mfma_kernel<false><<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws, 0);
+  else gemm1_mfma_kernel<true><<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws, epi);
   return hipGetLastError();
 }
 

@@ -1,0 +1,70 @@
+// Neuron importance profiling and reconstruction order (paper Sec. 4.2 b).
+//
+// GEMM-1 is run over the calibration tokens with every routed pair kept and stores, instead of
+// Swish(gate)*up, the chosen metric per (row, neuron).  Here the rows of each expert are summed
+// per neuron (one thread per neuron, rows in order: deterministic), and an importance vector is
+// turned into the permutation "neurons by descending importance, equal values by ascending id".
+#include "common.h"
+
+namespace dsmoe {
+
+template <typename T>
+__device__ __forceinline__ float ld_h(const T* p, size_t i);
+template <>
+__device__ __forceinline__ float ld_h<float>(const float* p, size_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float ld_h<uint16_t>(const uint16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+
+// importance[e][q] = sum over the rows of expert e of H[row][q] (the packed weights must have been
+// made with the identity permutation, so column q of H is original neuron q)
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(Layout L, const char* ws, float* importance) {
+  const int e = blockIdx.y;
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= L.F) return;
+  const int32_t* exp_nrows = (const int32_t*)(ws + L.o_exp_nrows);
+  const int32_t* exp_row0 = (const int32_t*)(ws + L.o_exp_row0);
+  const T* H = (const T*)(ws + L.o_H);
+  const int n = exp_nrows[e];
+  const size_t r0 = (size_t)(exp_row0[e] - L.sh_rows);
+  float acc = 0.f;
+  for (int r = 0; r < n; ++r) acc += ld_h<T>(H, (r0 + r) * L.F + q);
+  importance[(size_t)e * L.F + q] = acc;
+}
+
+hipError_t launch_colsum(const Layout& L, const char* ws, float* importance, hipStream_t s) {
+  dim3 grid((L.F + 255) / 256, L.E_res), block(256);
+  if (L.dtype == DSMOE_F32) colsum_kernel<float><<<grid, block, 0, s>>>(L, ws, importance);
+  else colsum_kernel<uint16_t><<<grid, block, 0, s>>>(L, ws, importance);
+  return hipGetLastError();
+}
+
+// perm[e][rank(q)] = q with rank(q) = #{q' : imp[q'] > imp[q], or equal and q' < q}
+constexpr int kRankTile = 1024;
+__global__ __launch_bounds__(256) void perm_rank_kernel(int F, const float* importance, int32_t* perm) {
+  __shared__ float tile[kRankTile];
+  const int e = blockIdx.y;
+  const float* imp = importance + (size_t)e * F;
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  const float mine = q < F ? imp[q] : 0.f;
+  int rank = 0;
+  for (int base = 0; base < F; base += kRankTile) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < kRankTile; i += 256) tile[i] = base + i < F ? imp[base + i] : 0.f;
+    __syncthreads();
+    const int n = min(kRankTile, F - base);
+    for (int i = 0; i < n; ++i) {
+      const float o = tile[i];
+      rank += (o > mine || (o == mine && base + i < q)) ? 1 : 0;
+    }
+  }
+  if (q < F) perm[(size_t)e * F + rank] = q;
+}
+
+hipError_t launch_perm_from_importance(const Layout& L, const float* importance, int32_t* perm, hipStream_t s) {
+  dim3 grid((L.F + 255) / 256, L.E_res), block(256);
+  perm_rank_kernel<<<grid, block, 0, s>>>(L.F, importance, perm);
+  return hipGetLastError();
+}
+
+}  // namespace dsmoe

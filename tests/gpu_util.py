@@ -28,7 +28,7 @@ def make_gpu_layer(spec: LayerSpec, tensors, max_tokens=None, renorm=False):
     layer = DualSparseLayer(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P,
                             max_tokens=max_tokens or max(spec.T, 1), dtype=spec.dtype, n_shared=spec.n_shared,
                             d_ff_shared=spec.F_sh, expert_lo=spec.lo, expert_hi=spec.hi, renorm_combine=renorm)
-    dev = {k: to_dev(v) for k, v in tensors.items()}
+    dev = {k: to_dev(v) for k, v in tensors.items() if v is not None}
     layer.partition_weights(dev["w1"], dev["w3"], dev["w2"], perm=dev.get("perm"), sh_w1=dev.get("sh_w1"),
                             sh_w3=dev.get("sh_w3"), sh_w2=dev.get("sh_w2"))
     return layer, dev

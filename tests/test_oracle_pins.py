@@ -464,3 +464,50 @@ def test_brute_force_on_tiny_layers(oracle, shape, tau_kind):
         want = brute_layer(spec, t, tau, renorm)
         got = run(oracle, spec, t, tau, renorm=renorm)
         np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- importance profiling
+
+@pytest.mark.parametrize("metric", [0, 1, 2, 3])
+def test_importance_single_expert_is_a_column_sum(oracle, metric):
+    """E = K = 1: every token goes to the expert, so the metric is a plain column sum (Sec. 4.2 b)."""
+    spec = tiny(T=23, D=12, F=20, E=1, K=1, P=1)
+    t = make_layer(spec)
+    x = t["x"].astype(np.float64)
+    g = silu(x @ t["w1"][0].astype(np.float64))
+    u = x @ t["w3"][0].astype(np.float64)
+    want = {0: g, 1: np.abs(g), 2: g * u, 3: np.abs(g * u)}[metric].sum(axis=0)
+    imp, ab = oracle.importance(t["x"], t["logits"], t["w1"], t["w3"], 1, metric)
+    np.testing.assert_allclose(imp[0], want, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(ab[0], np.abs({0: g, 1: g, 2: g * u, 3: g * u}[metric]).sum(axis=0), rtol=1e-12)
+
+
+def test_importance_counts_only_routed_tokens_and_orders_neurons(oracle):
+    spec = tiny(T=60, D=10, F=16, E=5, K=2, P=1, seed=61)
+    t = make_layer(spec)
+    r = oracle.route(t["logits"], spec.K, 1, np.zeros((spec.E, 1), np.float32))
+    x = t["x"].astype(np.float64)
+    for metric in range(4):
+        imp, ab = oracle.importance(t["x"], t["logits"], t["w1"], t["w3"], spec.K, metric)
+        for e in range(spec.E):
+            toks = np.nonzero((r.idx == e).any(axis=1))[0]
+            g = silu(x[toks] @ t["w1"][e].astype(np.float64))
+            u = x[toks] @ t["w3"][e].astype(np.float64)
+            want = {0: g, 1: np.abs(g), 2: g * u, 3: np.abs(g * u)}[metric].sum(axis=0)
+            np.testing.assert_allclose(imp[e], want, rtol=1e-11, atol=1e-13)
+        if metric & 1:
+            np.testing.assert_allclose(imp, ab, rtol=1e-14)
+            assert np.all(imp >= 0)
+        else:
+            assert np.all(np.abs(imp) <= ab + 1e-15)
+    # resident window = rows of the full result
+    imp_all, _ = oracle.importance(t["x"], t["logits"], t["w1"], t["w3"], spec.K, 3)
+    imp_win, _ = oracle.importance(t["x"], t["logits"], t["w1"][1:4], t["w3"][1:4], spec.K, 3, lo=1, hi=4)
+    np.testing.assert_array_equal(imp_win, imp_all[1:4])
+    # the permutation lists neurons by descending importance, equal values by ascending id
+    tie = np.array([[0.5, 2.0, 0.5, 3.0, 2.0]])
+    assert list(oracle.perm_from_importance(tie)[0]) == [3, 1, 4, 0, 2]
+    perm = oracle.perm_from_importance(imp_all)
+    for e in range(spec.E):
+        assert sorted(perm[e]) == list(range(spec.F))
+        assert np.all(np.diff(imp_all[e][perm[e]]) <= 0)
