@@ -159,3 +159,60 @@ def perm_from_importance(imp: np.ndarray) -> np.ndarray:
     for e in range(imp.shape[0]):
         out[e] = np.lexsort((np.arange(imp.shape[1]), -imp[e])).astype(np.int32)
     return out
+
+
+@dataclass
+class ThresholdSelection:
+    tau: np.ndarray          # [E][P] float32
+    pair_count: np.ndarray   # [E] int64 Top-K pairs per expert, nothing dropped
+    ratio: np.ndarray        # [E/group_size] float32 actual / ideal load of each device
+    cap_bin: np.ndarray      # [E] int64 grid index b of the row-cap threshold b / n_bins (0 = cap not binding)
+    min_margin: float        # min distance of a score to the two grid values that decide cap_bin
+
+
+def select_thresholds(logits: np.ndarray, K: int, P: int, tau_max: np.ndarray, group_size: int = 1, row_cap: int = 0,
+                      n_bins: int = 4096) -> ThresholdSelection:
+    """Load-aware thresholds (Sec. 4.3) and the score-distribution map from a row budget to a
+    threshold (Sec. 5.3.3 observes that the threshold <-> drop-rate relation is not linear).
+
+    Device d holds experts [d*group_size, (d+1)*group_size).  Its load ratio is r = pairs routed
+    to its experts / (T*K*group_size/E).  r >= 1: its experts take tau_max; r < 1: tau_max * r.
+    With row_cap > 0 every expert's thresholds are then lifted, keeping their spacing, until at
+    most row_cap of its pairs reach the lowest of them; the lifted minimum is the smallest value
+    b / n_bins (b integer) that achieves this.  All threshold arithmetic is single precision, the
+    precision in which the thresholds are compared with the scores."""
+    f32 = np.float32
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    tau_max = np.asarray(tau_max, dtype=np.float32)
+    assert tau_max.shape == (P,) and E % group_size == 0
+    r = route(logits, K, P, np.zeros((E, P), np.float32))
+    n = r.n.astype(np.float32)
+    pair_count = np.array([(r.idx == e).sum() for e in range(E)], dtype=np.int64)
+    n_dev = E // group_size
+    ideal = f32(T * K * group_size) / f32(E)
+    ratio = np.empty(n_dev, dtype=np.float32)
+    tau = np.empty((E, P), dtype=np.float32)
+    cap_bin = np.zeros(E, dtype=np.int64)
+    margin = np.inf
+    for d in range(n_dev):
+        load = int(pair_count[d * group_size:(d + 1) * group_size].sum())
+        ratio[d] = f32(load) / ideal
+        scale = ratio[d] if ratio[d] < f32(1) else f32(1)
+        for e in range(d * group_size, (d + 1) * group_size):
+            tau[e] = tau_max * scale
+    if row_cap > 0:
+        for e in range(E):
+            ne = n[r.idx == e]
+            b = 0
+            while int((ne >= f32(b) / f32(n_bins)).sum()) > row_cap:  # ends at the latest at b = n_bins + 1 (> any score)
+                b += 1
+            cap_bin[e] = b
+            floor_e = f32(b) / f32(n_bins)
+            lowest = tau[e].min()
+            if floor_e > lowest:
+                tau[e] = floor_e + (tau[e] - lowest)
+            if b > 0 and ne.size:
+                for edge in (b, b - 1):
+                    margin = min(margin, float(np.abs(ne.astype(np.float64) - edge / n_bins).min()))
+    return ThresholdSelection(tau, pair_count, ratio, cap_bin, float(margin))

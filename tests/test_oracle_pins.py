@@ -511,3 +511,80 @@ def test_importance_counts_only_routed_tokens_and_orders_neurons(oracle):
     for e in range(spec.E):
         assert sorted(perm[e]) == list(range(spec.F))
         assert np.all(np.diff(imp_all[e][perm[e]]) <= 0)
+
+
+# ----------------------------------------------------------- load-aware thresholds (Sec. 4.3)
+def _one_hot_logits(assign, E):
+    """K = 1 routing by construction: token t goes to expert assign[t]."""
+    lg = np.full((len(assign), E), -4.0, dtype=np.float32)
+    lg[np.arange(len(assign)), assign] = 4.0
+    return lg
+
+
+def test_load_ratio_rule_on_a_hand_example(oracle):
+    # pairs per expert 200, 100, 50, 50: ideal share 100 -> ratios 2, 1, 0.5, 0.5
+    assign = np.repeat(np.arange(4), [200, 100, 50, 50])
+    tau_max = np.array([0.25, 0.5], dtype=np.float32)
+    sel = oracle.select_thresholds(_one_hot_logits(assign, 4), 1, 2, tau_max)
+    np.testing.assert_array_equal(sel.pair_count, [200, 100, 50, 50])
+    np.testing.assert_array_equal(sel.ratio, np.float32([2, 1, 0.5, 0.5]))
+    np.testing.assert_array_equal(sel.tau, np.float32([[0.25, 0.5], [0.25, 0.5], [0.125, 0.25], [0.125, 0.25]]))
+    # two experts per device: loads 300 and 100 against 200 -> ratios 1.5 and 0.5, shared by both experts of a device
+    sel2 = oracle.select_thresholds(_one_hot_logits(assign, 4), 1, 2, tau_max, group_size=2)
+    np.testing.assert_array_equal(sel2.ratio, np.float32([1.5, 0.5]))
+    np.testing.assert_array_equal(sel2.tau, np.float32([[0.25, 0.5], [0.25, 0.5], [0.125, 0.25], [0.125, 0.25]]))
+    # one device holding everything is balanced by definition
+    sel3 = oracle.select_thresholds(_one_hot_logits(assign, 4), 1, 2, tau_max, group_size=4)
+    np.testing.assert_array_equal(sel3.tau, np.tile(tau_max, (4, 1)))
+
+
+def test_balanced_load_takes_the_maximum_threshold_everywhere(oracle):
+    assign = np.tile(np.arange(8), 32)
+    tau_max = np.array([0.11, 0.13, 0.17], dtype=np.float32)
+    sel = oracle.select_thresholds(_one_hot_logits(assign, 8), 1, 3, tau_max)
+    np.testing.assert_array_equal(sel.tau, np.tile(tau_max, (8, 1)))
+
+
+def test_row_cap_threshold_is_the_grid_point_just_above_the_first_excluded_score(oracle):
+    """Closed form of the cap: with v the (cap+1)-th largest score of the expert, at most cap scores
+    are >= b/B exactly when b/B > v, so b = floor(v*B) + 1."""
+    rng = np.random.default_rng(17)
+    T, E, K, P, B = 600, 4, 2, 2, 4096
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    r = oracle.route(logits, K, P, np.zeros((E, P), np.float32))
+    n32 = r.n.astype(np.float32)
+    tau_max = np.array([0.02, 0.04], dtype=np.float32)
+    for cap in (1, 37, 150):
+        sel = oracle.select_thresholds(logits, K, P, tau_max, row_cap=cap, n_bins=B)
+        base = oracle.select_thresholds(logits, K, P, tau_max, n_bins=B)
+        for e in range(E):
+            ne = np.sort(n32[r.idx == e])[::-1]
+            assert ne.size > cap
+            b = int(np.floor(float(ne[cap]) * B)) + 1
+            assert sel.cap_bin[e] == b
+            lifted = np.float32(b / B)
+            assert lifted > base.tau[e, 0]
+            np.testing.assert_array_equal(sel.tau[e], np.float32([lifted, lifted + (base.tau[e, 1] - base.tau[e, 0])]))
+        # consequence, through the keep decision itself: the rows of every expert fit the cap, and the
+        # next lower grid point would not
+        rows = oracle.route(logits, K, P, sel.tau).keep.any(axis=2)
+        lower = sel.tau - np.float32(1.0 / B)
+        rows_lower = oracle.route(logits, K, P, lower).keep.any(axis=2)
+        for e in range(E):
+            assert rows[r.idx == e].sum() <= cap < rows_lower[r.idx == e].sum()
+
+
+def test_row_cap_that_does_not_bind_changes_nothing_and_cap_edge_cases(oracle):
+    rng = np.random.default_rng(18)
+    logits = rng.standard_normal((300, 4)).astype(np.float32)
+    tau_max = np.array([0.3, 0.32], dtype=np.float32)
+    base = oracle.select_thresholds(logits, 2, 2, tau_max)
+    loose = oracle.select_thresholds(logits, 2, 2, tau_max, row_cap=10_000)
+    np.testing.assert_array_equal(loose.tau, base.tau)
+    assert np.all(loose.cap_bin == 0)
+    # K = 1: every score is exactly 1; a cap below the pair count can only be met above 1
+    assign = np.repeat(np.arange(2), [30, 10])
+    sel = oracle.select_thresholds(_one_hot_logits(assign, 2), 1, 1, np.float32([0.5]), row_cap=20, n_bins=1024)
+    assert sel.cap_bin[0] == 1025 and sel.tau[0, 0] == np.float32(1025 / 1024)
+    assert sel.cap_bin[1] == 0 and sel.tau[1, 0] == np.float32(0.5 * 0.5)
+    assert oracle.route(_one_hot_logits(assign, 2), 1, 1, sel.tau).group_count.tolist() == [0, 10]
