@@ -221,6 +221,16 @@ def main():
     log("reconstruction: importance of %d tokens %.3f ms (%.0f TFLOP/s), order %.3f ms"
         % (spec.T, rec_ms, reconstruction["profile_importance_tflops"], perm_ms))
 
+    # load-aware threshold selection on the device (Sec. 4.3): the step that can feed `tau` every batch
+    tau_sel = torch.empty((spec.E, spec.P), dtype=torch.float32, device=dev)
+    pairs_sel = torch.empty((spec.E,), dtype=torch.int32, device=dev)
+    tau_max_dev = torch.from_numpy(np.ascontiguousarray(primary["tau_table"][spec.lo])).to(dev)
+    cap_rows = int(1.25 * spec.T * spec.K / spec.E)
+    sel_ms = ev_ms(lambda: ds.moe_select_thresholds(layer.ctx, logits, spec.T, tau_max_dev, 1, cap_rows, tau_sel, pairs_sel,
+                                                    layer.workspace, stream), max(10, K))
+    selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows}
+    log("threshold selection (ratio rule + row cap %d): %.4f ms" % (cap_rows, sel_ms))
+
     # proportionality of the time saved at the primary rate, against the 0 % run
     t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
     prop = None
@@ -266,7 +276,7 @@ def main():
             round(100 * args.primary_rate), 100 * primary["drop_rate"]),
             "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
-        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction,
+        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction, "threshold_selection": selection,
         "roofline": roofline, "cpu_baseline": cpu, "check": check,
     }
     print(json.dumps(out))

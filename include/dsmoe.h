@@ -144,6 +144,26 @@ int moe_profile_importance(dsmoe_ctx* ctx, const void* packed, const void* x, co
 int moe_importance_to_perm(dsmoe_ctx* ctx, const float* importance, int32_t* perm, void* stream);
 
 /*
+ * Load-aware thresholds chosen on the device, without a host round trip (Sec. 4.3; Sec. 5.3.3 on
+ * the non-linear relation between threshold and drop rate).  Routes the batch over the whole
+ * router with nothing dropped and writes the table moe_dualsparse_forward takes as tau:
+ *   1. device d holds experts [d*group_size, (d+1)*group_size) (group_size divides E); its load
+ *      ratio is r = pairs routed to its experts / (T*K*group_size/E); its experts get
+ *      tau_max[p] * min(r, 1): the predefined maximum where the load is at or above the balanced
+ *      share, proportionally less below it;
+ *   2. if row_cap > 0: for every expert whose lowest threshold would let more than row_cap of its
+ *      pairs through, all its thresholds are lifted by the same amount so that the lowest becomes
+ *      the smallest multiple of 2^-12 that at most row_cap of its pairs reach (above 1, i.e. drop
+ *      everything, if more than row_cap pairs have score 1).
+ *   logits device float [T][E]; tau_max device float [P]; tau device float [E][P] (output);
+ *   pair_count device int32 [E] (output, may be NULL): Top-K pairs per expert before any drop;
+ *   workspace as for moe_dualsparse_forward (overwritten).  Arithmetic is fp32 with one rounding
+ *   per operation.  T == 0 gives tau_max everywhere.  Asynchronous, no allocation.
+ */
+int moe_select_thresholds(dsmoe_ctx* ctx, const float* logits, int32_t T, const float* tau_max, int32_t group_size,
+                          int32_t row_cap, float* tau, int32_t* pair_count, void* workspace, void* stream);
+
+/*
  * Inspection of the last forward call's plan, for tests: byte offsets into the workspace.
  * Fills out[0..DSMOE_PLAN_FIELDS-1]; returns the number of fields.
  *   0 topk_idx int32[T*K]      1 topk_w float[T*K]        2 keep_bits uint8[T*K]

@@ -22,5 +22,6 @@ from .binding import (  # noqa: F401
     moe_dualsparse_forward,
     moe_profile_importance,
     moe_importance_to_perm,
+    moe_select_thresholds,
     lib_path,
 )

@@ -61,6 +61,8 @@ def _load() -> ctypes.CDLL:
     L.moe_profile_importance.restype = ctypes.c_int
     L.moe_importance_to_perm.argtypes = [vp, vp, vp, vp]
     L.moe_importance_to_perm.restype = ctypes.c_int
+    L.moe_select_thresholds.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
+    L.moe_select_thresholds.restype = ctypes.c_int
     L.dsmoe_plan_layout.argtypes = [vp, i64p]
     L.dsmoe_plan_layout.restype = ctypes.c_int
     L.dsmoe_profile_begin.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -175,6 +177,12 @@ def moe_importance_to_perm(ctx, importance, perm, stream=None) -> None:
     _check(_lib.moe_importance_to_perm(ctx, _ptr(importance), _ptr(perm), _stream(stream)), ctx, "moe_importance_to_perm")
 
 
+def moe_select_thresholds(ctx, logits, T, tau_max, group_size, row_cap, tau, pair_count, workspace, stream=None) -> None:
+    rc = _lib.moe_select_thresholds(ctx, _ptr(logits), int(T), _ptr(tau_max), int(group_size), int(row_cap), _ptr(tau),
+                                    _ptr(pair_count), _ptr(workspace), _stream(stream))
+    _check(rc, ctx, "moe_select_thresholds")
+
+
 class DualSparseLayer:
     """Owns a context plus its packed-weight and workspace buffers (torch allocations)."""
 
@@ -232,6 +240,14 @@ class DualSparseLayer:
         with torch.cuda.device(self.device):
             moe_importance_to_perm(self.ctx, importance, perm)
         return perm
+
+    def select_thresholds(self, logits, tau_max, group_size=1, row_cap=0):
+        """Load-aware tau [E][P] (and the pair count of every expert) for this batch, on the device."""
+        tau = torch.empty((self.E, self.P), dtype=torch.float32, device=self.device)
+        pairs = torch.empty((self.E,), dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_select_thresholds(self.ctx, logits, logits.shape[0], tau_max, group_size, row_cap, tau, pairs, self.workspace)
+        return tau, pairs
 
     def plan(self, T):
         """Copies of the last forward call's plan arrays (for tests)."""

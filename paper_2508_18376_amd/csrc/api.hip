@@ -95,6 +95,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_Hs = take((int64_t)L.sh_rows * L.F_shT * elem);
   L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
+  L.o_sel = take((int64_t)L.E * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both
   L.ws_bytes = o;
 
   // packed weights
@@ -352,6 +353,27 @@ int moe_importance_to_perm(dsmoe_ctx* ctx_, const float* importance, int32_t* pe
   Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
   if (!ctx || !importance || !perm) return DSMOE_EINVAL;
   hipError_t err = launch_perm_from_importance(ctx->L, importance, perm, (hipStream_t)stream);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_select_thresholds(dsmoe_ctx* ctx_, const float* logits, int32_t T, const float* tau_max, int32_t group_size,
+                          int32_t row_cap, float* tau, int32_t* pair_count, void* workspace, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !tau_max || !tau || !workspace || row_cap < 0) return DSMOE_EINVAL;
+  if (T > 0 && !logits) return DSMOE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  if (T > L.max_tokens || group_size < 1 || L.E % group_size != 0) return DSMOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  // zero thresholds for the routing pass and a cleared score histogram (adjacent in the workspace)
+  const int64_t clear = (L.o_sel - L.o_tau0) / 4 + (int64_t)L.E * (kSelBins + 2);
+  hipError_t err = launch_fill_i32((int32_t*)(ws + L.o_tau0), clear, 0, s);
+  if (err == hipSuccess && T > 0)
+    err = launch_route(L, logits, T, (const float*)(ws + L.o_tau0), (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w),
+                       (uint8_t*)(ws + L.o_keep), nullptr, nullptr, s, true);
+  if (err == hipSuccess) err = launch_select_thresholds(L, T, tau_max, group_size, row_cap, ws, tau, pair_count, s);
   if (err != hipSuccess) return hip_fail(ctx, err);
   return DSMOE_OK;
 }

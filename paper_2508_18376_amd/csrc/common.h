@@ -11,6 +11,7 @@ constexpr int kMaxTopK = 16;
 constexpr int kMaxExperts = 512;
 constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
+constexpr int kSelBins = 4096;  // grid of the row-budget thresholds: multiples of 2^-12 (a power of two keeps n * kSelBins exact)
 constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels (one histogram row each)
 
 // MFMA path tile shape: 256 rows (token-expert pairs) x 128 neurons (gate+up = 256 weight rows)
@@ -52,7 +53,7 @@ struct Layout {
   // workspace byte offsets
   int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
   int64_t o_tile_e, o_tile_row0, o_tile_nrows, o_tile_bits, o_act_rank, o_items1, o_items2;
-  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, ws_bytes;
+  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, ws_bytes;
   // packed weights byte offsets
   int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes;
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
@@ -85,7 +86,7 @@ inline int items2_bound(const Layout& L, int T) { return (routed_tiles_bound(L, 
 // launchers (each returns hipError_t of the launch)
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);
 hipError_t launch_route(const Layout& L, const float* logits, int T, const float* tau, int32_t* idx, float* w,
-                        uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s);
+                        uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s, bool whole_router_scores = false);
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s);
@@ -94,6 +95,8 @@ hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t
 hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s);
 hipError_t launch_gemm2_generic(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
 hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s);
+hipError_t launch_select_thresholds(const Layout& L, int T, const float* tau_max, int group_size, int row_cap, char* ws,
+                                    float* tau, int32_t* pair_count, hipStream_t s);
 hipError_t launch_colsum(const Layout& L, const char* ws, float* importance, hipStream_t s);
 hipError_t launch_perm_from_importance(const Layout& L, const float* importance, int32_t* perm, hipStream_t s);
 hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);

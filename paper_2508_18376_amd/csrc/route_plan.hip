@@ -223,7 +223,7 @@ __global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
 }
 
 hipError_t launch_route(const Layout& L, const float* logits, int T, const float* tau, int32_t* idx, float* w,
-                        uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s) {
+                        uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s, bool whole_router_scores) {
   if (T <= 0) return hipSuccess;
   RouteArgs a;
   a.logits = logits;
@@ -237,9 +237,10 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
   a.E = L.E;
   a.K = L.K;
   a.P = L.P;
-  a.lo = L.lo;
-  a.hi = L.hi;
-  a.renorm = L.renorm;
+  // whole_router_scores: every expert counts as resident and w receives the normalised score
+  a.lo = whole_router_scores ? 0 : L.lo;
+  a.hi = whole_router_scores ? L.E : L.hi;
+  a.renorm = whole_router_scores ? 1 : L.renorm;
   a.nsub = L.nsub;
   a.nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   a.nhist = (bin_count ? L.nbins : 0) + (group_count ? L.E * L.P : 0);
