@@ -216,3 +216,51 @@ def select_thresholds(logits: np.ndarray, K: int, P: int, tau_max: np.ndarray, g
                 for edge in (b, b - 1):
                     margin = min(margin, float(np.abs(ne.astype(np.float64) - edge / n_bins).min()))
     return ThresholdSelection(tau, pair_count, ratio, cap_bin, float(margin))
+
+
+def _widen(a: np.ndarray) -> np.ndarray:
+    """float64 view of an input tensor: float32 as is, uint16 as bfloat16 bit patterns (exact)."""
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def _narrow_like(v: np.ndarray, like: np.ndarray) -> np.ndarray:
+    """Round float64 values to the storage type of `like` (float32, or bfloat16 bits, nearest-even)."""
+    f = v.astype(np.float32)
+    if like.dtype != np.uint16:
+        return f
+    b = f.view(np.uint32)
+    return ((b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+
+
+def router_logits(x: np.ndarray, wg: np.ndarray) -> np.ndarray:
+    """Gating logits l = x W_g (Sec. 3.1, first equation; W_g is [d_model][E]), float64 [T][E]."""
+    return np.matmul(_widen(x), _widen(wg))
+
+
+def complete_transform(wg: np.ndarray, w1: np.ndarray, w3: np.ndarray, w2: np.ndarray, P: int,
+                       perm: Optional[np.ndarray] = None, scale_w2: bool = True):
+    """Complete transformation of a layer into E*P finer-grained experts (Sec. 3.1, steps 1-3).
+
+    Router column e is repeated P times (new experts e*P .. e*P+P-1); the neurons of expert e, in
+    the order perm[e] (Sec. 4.2 b; identity if None), are split evenly so that new expert e*P+p
+    owns positions [p*F/P, (p+1)*F/P); its down projection is multiplied by P (rounded once to the
+    storage type).  Returns (wg', w1', w3', w2') with shapes [D][E*P], [E*P][D][F/P] (twice),
+    [E*P][F/P][D]; the transformed layer selects Top-(K*P)."""
+    E, D, F = w1.shape
+    assert F % P == 0 and wg.shape == (D, E)
+    Fp = F // P
+    wg_t = np.repeat(wg, P, axis=1)
+    w1_t = np.empty((E * P, D, Fp), dtype=w1.dtype)
+    w3_t = np.empty((E * P, D, Fp), dtype=w3.dtype)
+    w2_t = np.empty((E * P, Fp, D), dtype=w2.dtype)
+    for e in range(E):
+        order = np.arange(F) if perm is None else perm[e]
+        for p in range(P):
+            own = order[p * Fp:(p + 1) * Fp]
+            w1_t[e * P + p] = w1[e][:, own]
+            w3_t[e * P + p] = w3[e][:, own]
+            rows = w2[e][own, :]
+            w2_t[e * P + p] = _narrow_like(_widen(rows) * P, w2) if scale_w2 else rows
+    return wg_t, w1_t, w3_t, w2_t

@@ -10,6 +10,7 @@ from .layers import (  # noqa: F401
     make_layer,
     make_logits,
     make_perm,
+    make_router,
     f32_to_bf16_bits,
     bf16_bits_to_f32,
     spread_thresholds,

@@ -16,7 +16,7 @@ from typing import Dict, Optional, Tuple
 
 import numpy as np
 
-_KIND = {"x": 1, "logits": 2, "w1": 3, "w3": 4, "w2": 5, "sh_w1": 6, "sh_w3": 7, "sh_w2": 8, "perm": 9}
+_KIND = {"x": 1, "logits": 2, "w1": 3, "w3": 4, "w2": 5, "sh_w1": 6, "sh_w3": 7, "sh_w2": 8, "perm": 9, "wg": 10}
 
 
 @dataclass(frozen=True)
@@ -107,6 +107,12 @@ def make_logits(spec: LayerSpec) -> np.ndarray:
     if spec.zipf_s > 0:
         l = (l + zipf_logit_bias(spec)[None, :]).astype(np.float32)
     return l
+
+
+def make_router(spec: LayerSpec) -> np.ndarray:
+    """Gating weights W_g [D][E] in the layer's dtype ~ N(0, 1 / (x_std sqrt(D))), so that the logits
+    x W_g are ~ N(0, 1) like make_logits' (no popularity bias)."""
+    return _normal(spec.seed, "wg", 0, (spec.D, spec.E), 1.0 / (spec.x_std * np.sqrt(spec.D)), spec.dtype)
 
 
 def make_perm(spec: LayerSpec) -> np.ndarray:

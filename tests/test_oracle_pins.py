@@ -588,3 +588,74 @@ def test_row_cap_that_does_not_bind_changes_nothing_and_cap_edge_cases(oracle):
     assert sel.cap_bin[0] == 1025 and sel.tau[0, 0] == np.float32(1025 / 1024)
     assert sel.cap_bin[1] == 0 and sel.tau[1, 0] == np.float32(0.5 * 0.5)
     assert oracle.route(_one_hot_logits(assign, 2), 1, 1, sel.tau).group_count.tolist() == [0, 10]
+
+
+# ------------------------------------------- router GEMM and complete transformation (Sec. 3.1)
+def test_router_logits_on_unit_vectors_and_bf16_widening(oracle):
+    from synth import f32_to_bf16_bits
+    wg = np.arange(12, dtype=np.float32).reshape(4, 3) - 5.0         # W_g [D=4][E=3]
+    x = np.eye(4, dtype=np.float32)[[2, 0, 3]]                       # tokens e_2, e_0, e_3 pick rows of W_g
+    np.testing.assert_array_equal(oracle.router_logits(x, wg), wg[[2, 0, 3]].astype(np.float64))
+    x2 = np.float32([[1, 2, 3, 4], [0.5, -1, 0, 2]])
+    want = [[sum(float(x2[t, d]) * float(wg[d, e]) for d in range(4)) for e in range(3)] for t in range(2)]
+    np.testing.assert_array_equal(oracle.router_logits(x2, wg), np.float64(want))
+    # bf16 storage: values are the bit patterns widened exactly
+    np.testing.assert_array_equal(oracle.router_logits(f32_to_bf16_bits(x2), f32_to_bf16_bits(wg)), np.float64(want))
+
+
+@pytest.mark.parametrize("P,dtype", [(2, "f32"), (4, "f32"), (2, "bf16"), (3, "f32")])
+def test_complete_transform_function_preserves_the_layer(oracle, P, dtype):
+    """The transformed layer (E*P experts, Top-(K*P), router columns repeated, W2 * P) computes the
+    original layer's output (Sec. 3.1, last equation); without the W2 scaling it computes y / P."""
+    from synth import make_router
+    spec = tiny(T=24, D=16, F=24, E=4, K=2, P=1, dtype=dtype, seed=77, perm_kind="random", x_std=1.0, w_std=0.2)
+    t = make_layer(spec)
+    wg = make_router(spec)
+    logits = oracle.router_logits(t["x"], wg).astype(np.float32)
+    tau0 = np.zeros((spec.E, 1), np.float32)
+    y = oracle.forward(t["x"], logits, t["w1"], t["w3"], t["w2"], tau0, spec.K, 1)
+    wg_t, w1_t, w3_t, w2_t = oracle.complete_transform(wg, t["w1"], t["w3"], t["w2"], P, perm=t["perm"])
+    assert wg_t.shape == (spec.D, spec.E * P) and w1_t.shape == (spec.E * P, spec.D, spec.F // P)
+    logits_t = oracle.router_logits(t["x"], wg_t).astype(np.float32)
+    np.testing.assert_array_equal(logits_t, np.repeat(logits, P, axis=1))
+    tau0_t = np.zeros((spec.E * P, 1), np.float32)
+    y_t = oracle.forward(t["x"], logits_t, w1_t, w3_t, w2_t, tau0_t, spec.K * P, 1)
+    if P in (2, 4):  # exact scaling
+        np.testing.assert_allclose(y_t, y, rtol=1e-11, atol=1e-13)
+    else:            # W2 * 3 is rounded to the storage type: 2^-24 relative per weight
+        np.testing.assert_allclose(y_t, y, rtol=0, atol=2e-7 * np.abs(y).max())
+    _, _, _, w2_plain = oracle.complete_transform(wg, t["w1"], t["w3"], t["w2"], P, perm=t["perm"], scale_w2=False)
+    y_p = oracle.forward(t["x"], logits_t, w1_t, w3_t, w2_plain, tau0_t, spec.K * P, 1)
+    np.testing.assert_allclose(y_p, y / P, rtol=1e-11, atol=1e-13)
+
+
+def test_complete_transform_places_the_permuted_neurons(oracle):
+    """New expert e*P+p holds original neurons perm[e][p*F/P ..], in that order, in all three matrices."""
+    rng = np.random.default_rng(5)
+    E, D, F, P = 2, 3, 6, 3
+    w1 = rng.standard_normal((E, D, F)).astype(np.float32)
+    w3 = rng.standard_normal((E, D, F)).astype(np.float32)
+    w2 = rng.standard_normal((E, F, D)).astype(np.float32)
+    wg = rng.standard_normal((D, E)).astype(np.float32)
+    perm = np.int32([[5, 0, 3, 1, 4, 2], [2, 3, 4, 5, 0, 1]])
+    wg_t, w1_t, w3_t, w2_t = oracle.complete_transform(wg, w1, w3, w2, P, perm=perm)
+    np.testing.assert_array_equal(wg_t[:, [0, 1, 2]], np.repeat(wg[:, :1], 3, axis=1))
+    assert w1_t[1, 2, 0] == w1[0, 2, 3] and w1_t[1, 2, 1] == w1[0, 2, 1]      # expert 0, part 1: neurons 3, 1
+    assert w3_t[5, 0, 1] == w3[1, 0, 1]                                        # expert 1, part 2: neurons 0, 1
+    assert w2_t[2, 0, 1] == np.float32(3) * w2[0, 4, 1]                        # expert 0, part 2: neurons 4, 2; times P
+    assert w2_t[3, 1, 2] == np.float32(3) * w2[1, 3, 2]
+
+
+def test_thresholds_of_the_transformed_layer_are_the_originals_over_P(oracle):
+    """In the transformed layer every normalised score is n / P (Sec. 3.1: s_{e,p} = s_e / P), so a
+    single threshold tau on the original layer is tau / P there (Table 1 uses such values)."""
+    from synth import make_router
+    spec = tiny(T=200, D=16, F=8, E=8, K=2, P=1, seed=78, x_std=1.0)
+    t = make_layer(spec, weights=False)
+    logits = oracle.router_logits(t["x"], make_router(spec)).astype(np.float32)
+    P = 2
+    r = oracle.route(logits, spec.K, 1, np.full((spec.E, 1), 0.3, np.float32))
+    rt = oracle.route(np.repeat(logits, P, axis=1), spec.K * P, 1, np.full((spec.E * P, 1), 0.3 / P, np.float32))
+    assert min(r.min_margin, rt.min_margin) > 1e-9
+    np.testing.assert_array_equal(rt.keep[:, :, 0], np.repeat(r.keep[:, :, 0], P, axis=1))
+    np.testing.assert_allclose(rt.n, np.repeat(r.n, P, axis=1) / P, rtol=1e-12)
