@@ -231,6 +231,31 @@ def main():
     selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows}
     log("threshold selection (ratio rule + row cap %d): %.4f ms" % (cap_rows, sel_ms))
 
+    # gating product x W_g in front of the path (Sec. 3.1, first equation) and the complete transformation
+    from synth import make_router
+    wg_host = make_router(spec)
+    router_packed = torch.empty(max(ds.dsmoe_router_packed_bytes(layer.ctx), 16), dtype=torch.uint8, device=dev)
+    ds.moe_pack_router(layer.ctx, up(wg_host), router_packed, stream)
+    lg_out = torch.empty((spec.T, spec.E), dtype=torch.float32, device=dev)
+    router_ms = ev_ms(lambda: ds.moe_router_logits(layer.ctx, router_packed, x, spec.T, lg_out, stream), max(10, K))
+    routed_ms = ev_ms(lambda: ds.moe_dualsparse_forward_routed(layer.ctx, layer.packed, router_packed, x, primary["tau_dev"],
+                                                               spec.T, y, None, layer.workspace, stream), max(5, K // 2))
+    router_bytes = spec.T * spec.D * 2 + spec.T * spec.E * 4
+    router = {"router_logits_ms": router_ms, "GBps": router_bytes / (router_ms * 1e-3) / 1e9,
+              "forward_routed_ms": routed_ms}
+    log("router x W_g: %.4f ms (%.0f GB/s of x); whole layer with its own router %.3f ms" % (router_ms, router["GBps"], routed_ms))
+    del lg_out
+    w_dev = {k: up(host[k]) for k in ("w1", "w3", "w2")}
+    w_out = {k: torch.empty_like(v) for k, v in w_dev.items()}
+    wg_dev, wg_out = up(wg_host), torch.empty((spec.D, spec.E * spec.P), dtype=torch.bfloat16, device=dev)
+    perm_dev = up(host["perm"])
+    tr_ms = ev_ms(lambda: ds.moe_transform_complete(layer.ctx, wg_dev, w_dev["w1"], w_dev["w3"], w_dev["w2"], perm_dev, wg_out,
+                                                    w_out["w1"], w_out["w3"], w_out["w2"], layer.workspace, stream), 2)
+    w_bytes = sum(v.numel() * 2 for v in w_dev.values())
+    transform = {"transform_complete_ms": tr_ms, "GBps": 2 * w_bytes / (tr_ms * 1e-3) / 1e9}
+    log("complete transformation of %.2f GB of weights: %.2f ms (%.0f GB/s read + write)" % (w_bytes / 1e9, tr_ms, transform["GBps"]))
+    del w_dev, w_out
+
     # proportionality of the time saved at the primary rate, against the 0 % run
     t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
     prop = None
@@ -276,7 +301,7 @@ def main():
             round(100 * args.primary_rate), 100 * primary["drop_rate"]),
             "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
-        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction, "threshold_selection": selection,
+        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction, "threshold_selection": selection, "router": router, "complete_transformation": transform,
         "roofline": roofline, "cpu_baseline": cpu, "check": check,
     }
     print(json.dumps(out))

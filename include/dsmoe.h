@@ -122,6 +122,43 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, co
                            int32_t T, void* y, void* workspace, void* stream);
 
 /*
+ * Gating logits l = x W_g (Sec. 3.1, first equation; the input of Eq. 1).
+ *   moe_pack_router: wg device [D][E] (cfg.dtype), row-major as in the paper; router_packed device,
+ *     dsmoe_router_packed_bytes(ctx) bytes, 16-byte aligned: W_g in the kernel's operand order
+ *     (once per layer).  Asynchronous.
+ *   moe_router_logits: x device [T][D] (cfg.dtype, 16-byte aligned); logits device float [T][E],
+ *     fully overwritten.  Products are exact, accumulation is fp32 (order differs from a sequential
+ *     sum).  Asynchronous, no allocation.
+ *   moe_dualsparse_forward_routed: moe_router_logits followed by moe_dualsparse_forward on those
+ *     logits; logits_out device float [T][E] receives them, or NULL to keep them in the workspace.
+ */
+size_t dsmoe_router_packed_bytes(const dsmoe_ctx* ctx);
+int moe_pack_router(dsmoe_ctx* ctx, const void* wg, void* router_packed, void* stream);
+int moe_router_logits(dsmoe_ctx* ctx, const void* router_packed, const void* x, int32_t T, float* logits, void* stream);
+int moe_dualsparse_forward_routed(dsmoe_ctx* ctx, const void* packed, const void* router_packed, const void* x,
+                                  const float* tau, int32_t T, void* y, float* logits_out, void* workspace, void* stream);
+
+/*
+ * Complete transformation (Sec. 3.1, steps 1-3): rewrites the layer described by ctx (E experts of
+ * F neurons, P parts) as a plain layer of E*P experts of F/P neurons that any MoE implementation,
+ * this library included (n_experts = E*P, top_k = K*P, n_part = 1), runs with Top-(K*P) and that
+ * computes the same output.
+ *   wg   device [D][E] or NULL (then wg_out must be NULL too)   -> wg_out device [D][E*P]: column e
+ *        repeated P times (new experts e*P .. e*P+P-1)
+ *   w1, w3 device [E_res][D][F] -> w1_out, w3_out device [E_res*P][D][F/P]
+ *   w2   device [E_res][F][D]   -> w2_out device [E_res*P][F/P][D], multiplied by P (one rounding to
+ *        cfg.dtype; exact for P = 2, 4, 8)
+ *   perm device int32 [E_res][F] or NULL, as for moe_partition_weights: new expert e*P+p gets the
+ *        original neurons perm[e][p*F/P .. (p+1)*F/P - 1] in that order (Sec. 4.2 b)
+ *   workspace: needed only with perm (the permutation check); as for moe_dualsparse_forward.
+ * Outputs must not overlap inputs.  With perm the call synchronises the stream once and returns
+ * DSMOE_EPERM for a non-permutation (outputs then untouched); otherwise asynchronous.
+ */
+int moe_transform_complete(dsmoe_ctx* ctx, const void* wg, const void* w1, const void* w3, const void* w2,
+                           const int32_t* perm, void* wg_out, void* w1_out, void* w3_out, void* w2_out, void* workspace,
+                           void* stream);
+
+/*
  * Neuron importance profiling on calibration tokens (Sec. 4.2 b): for every resident expert e and
  * ORIGINAL neuron q, the sum over the calibration tokens routed to e (Top-K, nothing dropped) of
  *   metric 0  Swish(x W1_q)            1  |Swish(x W1_q)|
@@ -178,8 +215,9 @@ int dsmoe_plan_layout(const dsmoe_ctx* ctx, int64_t* out);
 
 /*
  * Per-kernel timing of the next moe_dualsparse_forward calls on this context, for benchmarks.
- * The steps of the layer (Eq. 1-4 with the drops of Sec. 4) run as seven kernels: clear counters,
- * route+mask, plan, scatter, GEMM-1, GEMM-2, combine.  begin creates HIP events (host objects, no
+ * The steps of the layer (Eq. 1-4 with the drops of Sec. 4) run as up to seven kernels: router
+ * (only in moe_dualsparse_forward_routed; otherwise its slot reads 0), route+mask, plan, scatter,
+ * GEMM-1, GEMM-2, combine.  begin creates HIP events (host objects, no
  * device memory); while profiling, forward records them on its stream between the kernels
  * (level 2) or only around GEMM-1 (level 1) and stays asynchronous; calls beyond max_calls are not
  * recorded.  end waits for the recorded events, writes the mean duration in milliseconds of each

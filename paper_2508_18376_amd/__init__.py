@@ -23,5 +23,10 @@ from .binding import (  # noqa: F401
     moe_profile_importance,
     moe_importance_to_perm,
     moe_select_thresholds,
+    moe_pack_router,
+    moe_router_logits,
+    moe_dualsparse_forward_routed,
+    moe_transform_complete,
+    dsmoe_router_packed_bytes,
     lib_path,
 )

@@ -61,6 +61,16 @@ def _load() -> ctypes.CDLL:
     L.moe_profile_importance.restype = ctypes.c_int
     L.moe_importance_to_perm.argtypes = [vp, vp, vp, vp]
     L.moe_importance_to_perm.restype = ctypes.c_int
+    L.dsmoe_router_packed_bytes.argtypes = [vp]
+    L.dsmoe_router_packed_bytes.restype = ctypes.c_size_t
+    L.moe_pack_router.argtypes = [vp, vp, vp, vp]
+    L.moe_pack_router.restype = ctypes.c_int
+    L.moe_router_logits.argtypes = [vp, vp, vp, i32, vp, vp]
+    L.moe_router_logits.restype = ctypes.c_int
+    L.moe_dualsparse_forward_routed.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    L.moe_dualsparse_forward_routed.restype = ctypes.c_int
+    L.moe_transform_complete.argtypes = [vp] * 12
+    L.moe_transform_complete.restype = ctypes.c_int
     L.moe_select_thresholds.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
     L.moe_select_thresholds.restype = ctypes.c_int
     L.dsmoe_plan_layout.argtypes = [vp, i64p]
@@ -126,7 +136,7 @@ def dsmoe_plan_layout(ctx):
     return [int(v) for v in out]
 
 
-KERNEL_NAMES = ("fill", "route_mask", "plan", "scatter", "gemm1", "gemm2", "combine")
+KERNEL_NAMES = ("router", "route_mask", "plan", "scatter", "gemm1", "gemm2", "combine")
 
 
 def dsmoe_profile_begin(ctx, level: int, max_calls: int) -> None:
@@ -175,6 +185,31 @@ def moe_profile_importance(ctx, packed, x, logits, T, metric, importance, worksp
 
 def moe_importance_to_perm(ctx, importance, perm, stream=None) -> None:
     _check(_lib.moe_importance_to_perm(ctx, _ptr(importance), _ptr(perm), _stream(stream)), ctx, "moe_importance_to_perm")
+
+
+def dsmoe_router_packed_bytes(ctx) -> int:
+    return int(_lib.dsmoe_router_packed_bytes(ctx))
+
+
+def moe_pack_router(ctx, wg, router_packed, stream=None) -> None:
+    _check(_lib.moe_pack_router(ctx, _ptr(wg), _ptr(router_packed), _stream(stream)), ctx, "moe_pack_router")
+
+
+def moe_router_logits(ctx, router_packed, x, T, logits, stream=None) -> None:
+    _check(_lib.moe_router_logits(ctx, _ptr(router_packed), _ptr(x), int(T), _ptr(logits), _stream(stream)), ctx,
+           "moe_router_logits")
+
+
+def moe_dualsparse_forward_routed(ctx, packed, router_packed, x, tau, T, y, logits_out, workspace, stream=None) -> None:
+    rc = _lib.moe_dualsparse_forward_routed(ctx, _ptr(packed), _ptr(router_packed), _ptr(x), _ptr(tau), int(T), _ptr(y),
+                                            _ptr(logits_out), _ptr(workspace), _stream(stream))
+    _check(rc, ctx, "moe_dualsparse_forward_routed")
+
+
+def moe_transform_complete(ctx, wg, w1, w3, w2, perm, wg_out, w1_out, w3_out, w2_out, workspace, stream=None) -> None:
+    rc = _lib.moe_transform_complete(ctx, _ptr(wg), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(perm), _ptr(wg_out), _ptr(w1_out),
+                                     _ptr(w3_out), _ptr(w2_out), _ptr(workspace), _stream(stream))
+    _check(rc, ctx, "moe_transform_complete")
 
 
 def moe_select_thresholds(ctx, logits, T, tau_max, group_size, row_cap, tau, pair_count, workspace, stream=None) -> None:
@@ -240,6 +275,37 @@ class DualSparseLayer:
         with torch.cuda.device(self.device):
             moe_importance_to_perm(self.ctx, importance, perm)
         return perm
+
+    def pack_router(self, wg):
+        """Keeps W_g [D][E] in the kernel's operand order for router_logits / forward_routed."""
+        self.router_packed = torch.empty(max(dsmoe_router_packed_bytes(self.ctx), 16), dtype=torch.uint8, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_pack_router(self.ctx, wg, self.router_packed)
+
+    def router_logits(self, x):
+        logits = torch.empty((x.shape[0], self.E), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_router_logits(self.ctx, self.router_packed, x, x.shape[0], logits)
+        return logits
+
+    def forward_routed(self, x, tau, want_logits=False):
+        T = x.shape[0]
+        y = torch.empty((T, self.D), dtype=self.torch_dtype, device=self.device)
+        logits = torch.empty((T, self.E), dtype=torch.float32, device=self.device) if want_logits else None
+        with torch.cuda.device(self.device):
+            moe_dualsparse_forward_routed(self.ctx, self.packed, self.router_packed, x, tau, T, y, logits, self.workspace)
+        return (y, logits) if want_logits else y
+
+    def transform_complete(self, wg, w1, w3, w2, perm=None):
+        """(wg', w1', w3', w2') of the equivalent layer with E*P experts (Sec. 3.1)."""
+        E_res, P, Fp = self.hi - self.lo, self.P, self.F // self.P
+        wg_o = torch.empty((self.D, self.E * P), dtype=wg.dtype, device=self.device) if wg is not None else None
+        w1_o = torch.empty((E_res * P, self.D, Fp), dtype=w1.dtype, device=self.device)
+        w3_o = torch.empty((E_res * P, self.D, Fp), dtype=w3.dtype, device=self.device)
+        w2_o = torch.empty((E_res * P, Fp, self.D), dtype=w2.dtype, device=self.device)
+        with torch.cuda.device(self.device):
+            moe_transform_complete(self.ctx, wg, w1, w3, w2, perm, wg_o, w1_o, w3_o, w2_o, self.workspace)
+        return wg_o, w1_o, w3_o, w2_o
 
     def select_thresholds(self, logits, tau_max, group_size=1, row_cap=0):
         """Load-aware tau [E][P] (and the pair count of every expert) for this batch, on the device."""

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsmoe.so")
-SOURCES = ["api.hip", "route_plan.hip", "pack.hip", "gemm_generic.hip", "gemm_mfma.hip", "importance.hip", "thresholds.hip"]
+SOURCES = ["api.hip", "route_plan.hip", "pack.hip", "gemm_generic.hip", "gemm_mfma.hip", "importance.hip", "thresholds.hip", "router.hip", "transform.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -96,6 +96,8 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
   L.o_sel = take((int64_t)L.E * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both
+  L.o_logits = take((int64_t)Tm * L.E * 4);
+  L.o_perm_check = take(((int64_t)L.E_res * L.F + 1) * 4);
   L.ws_bytes = o;
 
   // packed weights
@@ -125,6 +127,8 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   const int64_t need_check = ((int64_t)L.E_res * L.F + 1) * 4;
   if (q < need_check) q = align_up(need_check, 256);
   L.packed_bytes = q;
+  L.router_mfma = (c.dtype == DSMOE_BF16 && L.D % 64 == 0 && !(force && force[0] == '1')) ? 1 : 0;
+  L.router_bytes = L.router_mfma ? (int64_t)L.D * ((L.E + 31) / 32 * 32) * 2 : (int64_t)L.D * L.E * 4;
   return true;
 }
 
@@ -159,6 +163,7 @@ int dsmoe_destroy(dsmoe_ctx* ctx) {
 }
 
 size_t dsmoe_packed_bytes(const dsmoe_ctx* ctx) { return ctx ? (size_t) reinterpret_cast<const Ctx*>(ctx)->L.packed_bytes : 0; }
+size_t dsmoe_router_packed_bytes(const dsmoe_ctx* ctx) { return ctx ? (size_t) reinterpret_cast<const Ctx*>(ctx)->L.router_bytes : 0; }
 size_t dsmoe_workspace_bytes(const dsmoe_ctx* ctx) { return ctx ? (size_t) reinterpret_cast<const Ctx*>(ctx)->L.ws_bytes : 0; }
 int dsmoe_last_hip_error(const dsmoe_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->last_hip : 0; }
 int dsmoe_uses_mfma(const dsmoe_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->L.mfma : 0; }
@@ -215,14 +220,12 @@ int moe_route_and_mask(dsmoe_ctx* ctx_, const float* logits, int32_t T, const fl
   return DSMOE_OK;
 }
 
-int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, const float* logits, const float* tau,
-                           int32_t T, void* y, void* workspace, void* stream) {
-  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
-  if (!ctx || T < 0 || !packed || !tau || !workspace) return DSMOE_EINVAL;
-  if (T > 0 && (!x || !logits || !y)) return DSMOE_EINVAL;
-  if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0) return DSMOE_EINVAL;
+// The layer's kernel sequence.  router_packed != nullptr: the logits are computed first (into
+// logits_buf) from x and the packed gating weights; otherwise logits_buf holds the caller's logits.
+static int forward_impl(Ctx* ctx, const void* packed, const char* router_packed, const void* x, const float* logits_buf,
+                        const float* tau, int32_t T, void* y, void* workspace, void* stream) {
   const Layout& L = ctx->L;
-  if (T > L.max_tokens) return DSMOE_EINVAL;
+  const float* logits = logits_buf;
   if (T == 0) return DSMOE_OK;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
@@ -243,7 +246,8 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
     mark(b);                \
     if (err == hipSuccess) err = (call); \
   } while (0)
-  mark(0);  // (slot 0 was a clearing kernel; the route kernel now writes whole histogram rows)
+  mark(0);
+  if (router_packed && err == hipSuccess) err = launch_router(L, T, router_packed, x, const_cast<float*>(logits_buf), s);
   DSMOE_STEP(1, launch_route(L, logits, T, tau, (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w), (uint8_t*)(ws + L.o_keep),
                              (int32_t*)(ws + L.o_bin_count), nullptr, s));
   DSMOE_STEP(2, launch_plan(L, T, ws, s));
@@ -256,6 +260,71 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
 #undef DSMOE_STEP
   if (err != hipSuccess) return hip_fail(ctx, err);
   if (rec) pf.calls += 1;
+  return DSMOE_OK;
+}
+
+int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, const float* logits, const float* tau,
+                           int32_t T, void* y, void* workspace, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !packed || !tau || !workspace) return DSMOE_EINVAL;
+  if (T > 0 && (!x || !logits || !y)) return DSMOE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0) return DSMOE_EINVAL;
+  if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
+  return forward_impl(ctx, packed, nullptr, x, logits, tau, T, y, workspace, stream);
+}
+
+int moe_pack_router(dsmoe_ctx* ctx_, const void* wg, void* router_packed, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || !wg || !router_packed || ((uintptr_t)router_packed & 15) != 0) return DSMOE_EINVAL;
+  hipError_t err = launch_router_pack(ctx->L, wg, (char*)router_packed, (hipStream_t)stream);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_router_logits(dsmoe_ctx* ctx_, const void* router_packed, const void* x, int32_t T, float* logits, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !router_packed || ((uintptr_t)router_packed & 15) != 0) return DSMOE_EINVAL;
+  if (T > 0 && (!x || !logits || ((uintptr_t)x & 15) != 0)) return DSMOE_EINVAL;
+  if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
+  hipError_t err = launch_router(ctx->L, T, (const char*)router_packed, x, logits, (hipStream_t)stream);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_dualsparse_forward_routed(dsmoe_ctx* ctx_, const void* packed, const void* router_packed, const void* x,
+                                  const float* tau, int32_t T, void* y, float* logits_out, void* workspace, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !packed || !router_packed || !tau || !workspace) return DSMOE_EINVAL;
+  if (T > 0 && (!x || !y || ((uintptr_t)x & 15) != 0)) return DSMOE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0 || ((uintptr_t)router_packed & 15) != 0) return DSMOE_EINVAL;
+  if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
+  float* lbuf = logits_out ? logits_out : (float*)((char*)workspace + ctx->L.o_logits);
+  return forward_impl(ctx, packed, (const char*)router_packed, x, lbuf, tau, T, y, workspace, stream);
+}
+
+int moe_transform_complete(dsmoe_ctx* ctx_, const void* wg, const void* w1, const void* w3, const void* w2,
+                           const int32_t* perm, void* wg_out, void* w1_out, void* w3_out, void* w2_out, void* workspace,
+                           void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || !w1 || !w3 || !w2 || !w1_out || !w3_out || !w2_out) return DSMOE_EINVAL;
+  if ((wg == nullptr) != (wg_out == nullptr)) return DSMOE_EINVAL;
+  if (perm && (!workspace || ((uintptr_t)workspace & 255) != 0)) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t err;
+  if (perm) {
+    int32_t* scratch = (int32_t*)((char*)workspace + L.o_perm_check);
+    err = launch_perm_check(L, perm, scratch, s);
+    if (err != hipSuccess) return hip_fail(ctx, err);
+    int32_t bad = 0;
+    err = hipMemcpyAsync(&bad, scratch + (size_t)L.E_res * L.F, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+    if (err != hipSuccess) return hip_fail(ctx, err);
+    err = hipStreamSynchronize(s);
+    if (err != hipSuccess) return hip_fail(ctx, err);
+    if (bad != 0) return DSMOE_EPERM;
+  }
+  err = launch_transform_complete(L, wg, w1, w3, w2, perm, wg_out, w1_out, w3_out, w2_out, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
   return DSMOE_OK;
 }
 

@@ -40,7 +40,7 @@ struct Layout {
   int32_t D, F, E, K, P, Fp;
   int32_t lo, hi, E_res;      // resident window
   int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
-  int32_t renorm, dtype, mfma;
+  int32_t renorm, dtype, mfma, router_mfma;
   int32_t max_tokens;
   // plan geometry
   int32_t BM;                 // row tile height
@@ -53,9 +53,9 @@ struct Layout {
   // workspace byte offsets
   int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
   int64_t o_tile_e, o_tile_row0, o_tile_nrows, o_tile_bits, o_act_rank, o_items1, o_items2;
-  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, ws_bytes;
+  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, o_logits, o_perm_check, ws_bytes;
   // packed weights byte offsets
-  int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes;
+  int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes, router_bytes;
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
 };
 
@@ -97,6 +97,11 @@ hipError_t launch_gemm2_generic(const Layout& L, int T, const char* packed, char
 hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s);
 hipError_t launch_select_thresholds(const Layout& L, int T, const float* tau_max, int group_size, int row_cap, char* ws,
                                     float* tau, int32_t* pair_count, hipStream_t s);
+hipError_t launch_router_pack(const Layout& L, const void* wg, char* out, hipStream_t s);
+hipError_t launch_router(const Layout& L, int T, const char* router_packed, const void* x, float* logits, hipStream_t s);
+hipError_t launch_transform_complete(const Layout& L, const void* wg, const void* w1, const void* w3, const void* w2,
+                                     const int32_t* perm, void* wg_out, void* w1_out, void* w3_out, void* w2_out,
+                                     hipStream_t s);
 hipError_t launch_colsum(const Layout& L, const char* ws, float* importance, hipStream_t s);
 hipError_t launch_perm_from_importance(const Layout& L, const float* importance, int32_t* perm, hipStream_t s);
 hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
