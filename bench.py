@@ -256,6 +256,37 @@ def main():
     log("complete transformation of %.2f GB of weights: %.2f ms (%.0f GB/s read + write)" % (w_bytes / 1e9, tr_ms, transform["GBps"]))
     del w_dev, w_out
 
+    # decode-sized batches of the same layer (weight streaming regime): the first T tokens of the batch
+    decode = []
+    w_unit_bytes = 3 * spec.D * Fp * 2
+    for Td in (16, 64, 256):
+        if Td > spec.T:
+            continue
+        xd, ld = x[:Td].contiguous(), logits[:Td].contiguous()
+        res_d = resident[:Td]
+        tab = np.tile(tau_for_drop_rate(n_all[:Td][res_d], spec.P, args.primary_rate)[None, :], (spec.E, 1)).astype(np.float32)
+        tau_d = torch.from_numpy(tab).to(dev)
+        ds.moe_route_and_mask(rctx, ld, Td, tau_d, r_idx, r_w, r_keep, r_gc)
+        torch.cuda.synchronize()
+        gc = r_gc.cpu().numpy()
+        active = int((gc > 0).sum())
+        wbytes = active * w_unit_bytes + 3 * spec.D * spec.F_sh * spec.n_shared * 2
+        yd = torch.empty((Td, spec.D), dtype=torch.bfloat16, device=dev)
+        fn = lambda: ds.moe_dualsparse_forward(layer.ctx, layer.packed, xd, ld, tau_d, Td, yd, layer.workspace, stream)
+        for _ in range(W):
+            fn()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(K):
+            fn()
+        torch.cuda.synchronize()
+        ms_d = (time.perf_counter() - t_start) / K * 1e3
+        decode.append({"tokens": Td, "ms_per_step": ms_d, "tokens_per_s": Td / (ms_d * 1e-3), "active_sub_experts": active,
+                       "kept_units": int(gc.sum()), "weight_bytes": wbytes, "GBps": wbytes / (ms_d * 1e-3) / 1e9,
+                       "frac_hbm_peak": wbytes / (ms_d * 1e-3) / 1e9 / 8000.0})
+        log("decode T=%d: %.3f ms/step, weights of %d active sub-experts %.2f GB -> %.0f GB/s (%.0f %% of 8 TB/s)"
+            % (Td, ms_d, active, wbytes / 1e9, decode[-1]["GBps"], 100 * decode[-1]["frac_hbm_peak"]))
+
     # proportionality of the time saved at the primary rate, against the 0 % run
     t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
     prop = None
@@ -301,7 +332,7 @@ def main():
             round(100 * args.primary_rate), 100 * primary["drop_rate"]),
             "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
-        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction, "threshold_selection": selection, "router": router, "complete_transformation": transform,
+        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction, "threshold_selection": selection, "decode": decode, "router": router, "complete_transformation": transform,
         "roofline": roofline, "cpu_baseline": cpu, "check": check,
     }
     print(json.dumps(out))

@@ -11,6 +11,8 @@ constexpr int kMaxTopK = 16;
 constexpr int kMaxExperts = 512;
 constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
+constexpr int kSplitItems = 256;  // GEMM-2 splits K while that keeps its items within one per compute unit (measured best)
+constexpr int kMaxSplit = 8;   // most K ranges GEMM-2 is split into when there are few row tiles
 constexpr int kSelBins = 4096;  // grid of the row-budget thresholds: multiples of 2^-12 (a power of two keeps n * kSelBins exact)
 constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels (one histogram row each)
 
@@ -31,7 +33,9 @@ struct Item1 {  // one tile of GEMM-1: rows [row0, row0+nrows) x neurons tile jt
   int32_t row0, nrows, e, p, jt, pad0, pad1, pad2;
 };
 struct Item2 {  // one tile of GEMM-2: rows x output column tile jd, summed over partitions in kmask
-  int32_t row0, nrows, e, jd, kmask, pad0, pad1, pad2;
+  int32_t row0, nrows, e, jd, kmask;
+  int32_t ks_lo, ks_n;  // K stages [ks_lo, ks_lo + ks_n) of every kept partition (the whole partition unless K is split)
+  int32_t split;        // index of the partial-output slab this item writes (0 unless K is split)
 };
 
 // Everything the device code needs to know about the layer and the workspace.
@@ -41,6 +45,7 @@ struct Layout {
   int32_t lo, hi, E_res;      // resident window
   int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
   int32_t renorm, dtype, mfma, router_mfma;
+  int32_t split_items;  // GEMM-2 splits K while tiles * column tiles * splits <= split_items (0: never)
   int32_t max_tokens;
   // plan geometry
   int32_t BM;                 // row tile height
@@ -81,7 +86,10 @@ inline int shared_tiles(const Layout& L, int T) { return L.n_shared > 0 ? (T + L
 inline int items1_bound(const Layout& L, int T) {
   return routed_tiles_bound(L, T) * L.P * L.NT1 + shared_tiles(L, T) * L.NT1_sh;
 }
-inline int items2_bound(const Layout& L, int T) { return (routed_tiles_bound(L, T) + shared_tiles(L, T)) * L.ND2; }
+inline int items2_bound(const Layout& L, int T) {
+  const int whole = (routed_tiles_bound(L, T) + shared_tiles(L, T)) * L.ND2;
+  return whole > L.split_items ? whole : L.split_items;  // K is split only while the items stay within split_items
+}
 
 // launchers (each returns hipError_t of the launch)
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t s);

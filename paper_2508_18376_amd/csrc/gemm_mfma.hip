@@ -370,8 +370,8 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   while (p_cur < g.np && !((g.it.kmask >> p_cur) & 1)) ++p_cur;
   uint32_t slot = 0, sW = 0, sH = 0;
   auto begin = [&](int st) {
-    const int kt = p_cur * g.KSp + k_in;
-    if (++k_in == g.KSp) {
+    const int kt = p_cur * g.KSp + g.it.ks_lo + k_in;
+    if (++k_in == g.it.ks_n) {
       k_in = 0;
       ++p_cur;
       while (p_cur < g.np && !((g.it.kmask >> p_cur) & 1)) ++p_cur;
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   const char* hbase = (const char*)(H + (size_t)hrow0 * ld);
   g.rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
   g.rsH = make_rsrc(hbase, (uint32_t)((int64_t)g.it.nrows * ld * 2));
-  g.Yp = (float*)(ws + L.o_Yp);
+  g.Yp = (float*)(ws + L.o_Yp) + (size_t)g.it.split * counters[2] * kMfmaBM * L.D;  // this split's slab of partial outputs
 
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   g.woff = (uint32_t)tid * 16;
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
   g.nstages = 0;
-  for (int p = 0; p < g.np; ++p) g.nstages += ((g.it.kmask >> p) & 1) ? g.KSp : 0;
+  for (int p = 0; p < g.np; ++p) g.nstages += ((g.it.kmask >> p) & 1) ? g.it.ks_n : 0;
 
   if (g.it.nrows == kMfmaBM) {
     gemm2_tile<4, 4, 4>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts

@@ -398,18 +398,32 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     }
     return bits;
   };
-  // 5. GEMM-2 items: every tile x every output column tile, column tiles innermost
-  for (int it = tid; it < total_tiles * L.ND2; it += kPlanThreads) {
-    const int g = it / L.ND2, jd = it % L.ND2;
+  // 5. GEMM-2 items: every tile x every output column tile, column tiles innermost.  With few row
+  //    tiles (decode-sized batches) that is fewer items than compute units, and each item streams a
+  //    whole column tile of W2 by itself: K is then split into nsplit ranges, each an item of its
+  //    own that writes a partial-output slab; the combine kernel adds the slabs in a fixed order.
+  int nsplit = 1;
+  {
+    int ksp = L.Fp / kBK;
+    if (has_sh) ksp = min(ksp, L.F_shT / kBK);
+    const int whole = total_tiles * L.ND2;
+    while (nsplit < kMaxSplit && whole * nsplit * 2 <= L.split_items && nsplit * 2 <= ksp) nsplit *= 2;
+  }
+  for (int it = tid; it < total_tiles * L.ND2 * nsplit; it += kPlanThreads) {
+    const int sp = it % nsplit, gj = it / nsplit;
+    const int g = gj / L.ND2, jd = gj % L.ND2;
     const int e = tile_expert(g);
     const int i = g - ts[e];
+    const int ksp = (e < E_res ? L.Fp : L.F_shT) / kBK;
     Item2 v;
     v.row0 = rs[e] + i * BM;
     v.nrows = min(ne[e] - i * BM, BM);
     v.e = e;
     v.jd = jd;
     v.kmask = tile_bits_of(e, i);
-    v.pad0 = v.pad1 = v.pad2 = 0;
+    v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
+    v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
+    v.split = sp;
     items2[it] = v;
   }
   // 6. per (expert, partition): rank of each active tile
@@ -452,9 +466,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   }
   if (tid == 0) {
     counters[0] = total1;
-    counters[1] = total_tiles * L.ND2;
+    counters[1] = total_tiles * L.ND2 * nsplit;
     counters[2] = total_tiles;
-    counters[3] = 0;
+    counters[3] = nsplit;
   }
 }
 
@@ -549,6 +563,31 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
     v[k] = row[k] >= 0 ? *(const float4*)(Yp + (size_t)row[k] * L.D + d) : make_float4(0.f, 0.f, 0.f, 0.f);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   if (L.n_shared > 0) acc = *(const float4*)(Yp + (size_t)t * L.D + d);  // shared rows sit first in the row space
+  const int32_t* counters = (const int32_t*)(ws + L.o_counters);
+  const int nsplit = counters[3];
+  if (nsplit > 1) {  // GEMM-2 split K: add the partial-output slabs in slab order
+    const size_t slab = (size_t)counters[2] * L.BM * L.D;
+    for (int sp = 1; sp < nsplit; ++sp) {
+      const float* Ys = Yp + sp * slab;
+#pragma unroll
+      for (int k = 0; k < KB; ++k) {
+        if (row[k] >= 0) {
+          const float4 u = *(const float4*)(Ys + (size_t)row[k] * L.D + d);
+          v[k].x += u.x;
+          v[k].y += u.y;
+          v[k].z += u.z;
+          v[k].w += u.w;
+        }
+      }
+      if (L.n_shared > 0) {
+        const float4 u = *(const float4*)(Ys + (size_t)t * L.D + d);
+        acc.x += u.x;
+        acc.y += u.y;
+        acc.z += u.z;
+        acc.w += u.w;
+      }
+    }
+  }
 #pragma unroll
   for (int k = 0; k < KB; ++k) {
     if (row[k] >= 0) {

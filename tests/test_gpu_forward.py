@@ -217,3 +217,27 @@ def test_forward_is_repeatable_and_workspace_reusable(oracle):
     y_ref = oracle_forward(oracle, spec.with_(T=257), sub, tau_b)
     assert_output_close(to_host64(yb, "bf16"), y_ref, "bf16")
     layer.close()
+
+
+# ------------------------------------------------------------------ decode-sized batches: split K
+SPLIT_CASES = [
+    # name, spec, tau, expected number of K ranges GEMM-2 is split into
+    ("decode_16_tokens", spec_of(T=16, D=512, F=1024, E=8, K=2, P=4, seed=40), "rate0.25", 8),
+    ("uneven_ranges", spec_of(T=40, D=256, F=448, E=4, K=2, P=2, seed=41), "rate0.25", 4),          # 7 stages per part
+    ("shared_limits_the_split", spec_of(T=24, D=128, F=512, E=4, K=2, P=2, n_shared=1, F_sh=64, seed=42), "rate0.25", 2),
+    ("one_token_split", spec_of(T=1, D=256, F=2048, E=8, K=2, P=2, seed=43), 0.0, 8),
+    ("too_many_tiles_to_split", spec_of(T=1200, D=768, F=128, E=64, K=8, P=2, seed=44), "rate0.25", 1),
+]
+
+
+@pytest.mark.parametrize("name,spec,tau_kind,nsplit", SPLIT_CASES, ids=[c[0] for c in SPLIT_CASES])
+def test_gemm2_split_k_on_few_row_tiles(oracle, name, spec, tau_kind, nsplit):
+    """With few row tiles the second GEMM splits its contraction into ranges that write partial
+    outputs, added in a fixed order by the combine kernel: same result as the oracle, and the
+    split only happens while the items stay within one per compute unit."""
+    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
+    counters = plan["counters"].cpu().numpy()
+    assert counters[3] == nsplit, counters
+    tiles_x_cols = counters[2] * ((spec.D + 255) // 256)
+    assert counters[1] == tiles_x_cols * nsplit
+    assert nsplit == 1 or counters[1] <= 256
