@@ -207,7 +207,7 @@ int moe_select_thresholds(dsmoe_ctx* ctx, const float* logits, int32_t T, const 
  *   3 pair_row int32[T*K] (-1 = no kept unit)              4 row_token int32[rows]
  *   5 row_bits uint8[rows]     6 expert_nrows int32[E_res] 7 expert_row0 int32[E_res]
  *   8 row capacity (a count, not an offset)                9 row tile height (a count)
- *  10 rows reserved at the start of the row space for the shared experts (a count)
+ *  10 rows at the start of the row space that the last call gave to the shared experts (a count)
  *  11 counters int32[4]: items of GEMM-1, items of GEMM-2, row tiles, K ranges GEMM-2 is split into
  */
 #define DSMOE_PLAN_FIELDS 12

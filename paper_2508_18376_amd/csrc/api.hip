@@ -152,6 +152,7 @@ int dsmoe_create(const dsmoe_config* cfg, dsmoe_ctx** out) {
   if (!c) return DSMOE_EINVAL;
   c->cfg = *cfg;
   c->last_hip = 0;
+  c->last_sh_rows = 0;
   if (!build_layout(*cfg, c->L)) {
     delete c;
     return DSMOE_EINVAL;
@@ -228,7 +229,12 @@ int moe_route_and_mask(dsmoe_ctx* ctx_, const float* logits, int32_t T, const fl
 // logits_buf) from x and the packed gating weights; otherwise logits_buf holds the caller's logits.
 static int forward_impl(Ctx* ctx, const void* packed, const char* router_packed, const void* x, const float* logits_buf,
                         const float* tau, int32_t T, void* y, void* workspace, void* stream) {
-  const Layout& L = ctx->L;
+  // The shared experts' rows come first in the row space and the routed rows start at the next
+  // tile boundary after the T rows of THIS call (the plan kernel places them there), so the layout
+  // every kernel of the call sees carries that boundary, not the one max_tokens would give.
+  Layout L = ctx->L;
+  L.sh_rows = L.n_shared > 0 ? (int)align_up(T, L.BM) : 0;
+  ctx->last_sh_rows = L.sh_rows;
   const float* logits = logits_buf;
   if (T == 0) return DSMOE_OK;
   hipStream_t s = (hipStream_t)stream;
@@ -403,8 +409,10 @@ int moe_profile_importance(dsmoe_ctx* ctx_, const void* packed, const void* x, c
   if (!ctx || T < 0 || !packed || !importance || !workspace || metric < 0 || metric > 3) return DSMOE_EINVAL;
   if (T > 0 && (!x || !logits)) return DSMOE_EINVAL;
   if (((uintptr_t)workspace & 255) != 0) return DSMOE_EINVAL;
-  const Layout& L = ctx->L;
-  if (T > L.max_tokens) return DSMOE_EINVAL;
+  if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
+  Layout L = ctx->L;  // per-call boundary of the shared rows, as in the forward call
+  L.sh_rows = L.n_shared > 0 ? (int)align_up(T, L.BM) : 0;
+  ctx->last_sh_rows = L.sh_rows;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
   // every routed pair takes part: thresholds of zero keep all units
@@ -465,7 +473,7 @@ int dsmoe_plan_layout(const dsmoe_ctx* ctx_, int64_t* out) {
   out[7] = L.o_exp_row0;
   out[8] = L.row_cap;
   out[9] = L.BM;
-  out[10] = L.sh_rows;
+  out[10] = ctx->last_sh_rows;
   out[11] = L.o_counters;
   return DSMOE_PLAN_FIELDS;
 }

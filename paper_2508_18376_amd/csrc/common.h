@@ -52,7 +52,8 @@ struct Layout {
   int32_t NT1, NT1_sh;        // neuron tiles per partition (routed / shared)
   int32_t ND2;                // output column tiles of GEMM-2
   int32_t nsub, nbins;        // sort bins: E_res * nsub
-  int32_t sh_rows;            // rows reserved for the shared region (multiple of BM), first in the row space
+  int32_t sh_rows;            // rows of the shared region (multiple of BM), first in the row space: the context holds the
+                              // capacity for max_tokens, the copy a call hands to its kernels the boundary for its T
   int32_t row_cap;            // total row capacity
   int32_t max_tiles, max_items1, max_items2;
   // workspace byte offsets
@@ -77,6 +78,7 @@ struct Ctx {
   dsmoe_config cfg;
   Layout L;
   int last_hip;
+  int last_sh_rows;  // rows the last call reserved for the shared experts (for dsmoe_plan_layout)
   Profile prof;
 };
 

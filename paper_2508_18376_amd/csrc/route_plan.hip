@@ -398,7 +398,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     }
     return bits;
   };
-  // 5. GEMM-2 items: every tile x every output column tile, column tiles innermost.  With few row
+  // 5. GEMM-2 items: every tile x every output column tile.  With few row
   //    tiles (decode-sized batches) that is fewer items than compute units, and each item streams a
   //    whole column tile of W2 by itself: K is then split into nsplit ranges, each an item of its
   //    own that writes a partial-output slab; the combine kernel adds the slabs in a fixed order.
@@ -424,7 +424,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
     v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
     v.split = sp;
-    items2[it] = v;
+    // order (expert, column tile, row tile, split): the row tiles that share one column tile of W2
+    // are adjacent, so they run at the same time on one XCD and the weights are fetched once
+    const int nt_e = (ne[e] + BM - 1) / BM;
+    items2[((size_t)ts[e] * L.ND2 + (size_t)jd * nt_e + i) * nsplit + sp] = v;
   }
   // 6. per (expert, partition): rank of each active tile
   for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {

@@ -241,3 +241,28 @@ def test_gemm2_split_k_on_few_row_tiles(oracle, name, spec, tau_kind, nsplit):
     tiles_x_cols = counters[2] * ((spec.D + 255) // 256)
     assert counters[1] == tiles_x_cols * nsplit
     assert nsplit == 1 or counters[1] <= 256
+
+
+@pytest.mark.parametrize("dtype,T", [("bf16", 16), ("bf16", 300), ("f32", 40)])
+def test_shared_experts_with_a_batch_smaller_than_max_tokens(oracle, dtype, T):
+    """The routed rows start right after the shared experts' rows of THIS batch: a context sized
+    for more tokens than a call carries must give the same result as one sized exactly."""
+    import torch
+    if dtype == "bf16":
+        spec = spec_of(T=T, D=128, F=256, E=8, K=2, P=2, n_shared=2, F_sh=96, seed=46)
+    else:
+        spec = spec_of(dtype="f32", T=T, D=40, F=48, E=6, K=2, P=2, n_shared=1, F_sh=24, x_std=0.5, w_std=0.1, seed=47)
+    t = make_layer(spec)
+    tau = resolve_tau(oracle, spec, t, "rate0.25")
+    y_ref = oracle_forward(oracle, spec, t, tau)
+    layer, dev = make_gpu_layer(spec, t, max_tokens=1024)
+    y = layer.forward(dev["x"], dev["logits"], to_dev(tau))
+    torch.cuda.synchronize()
+    assert_output_close(to_host64(y, spec.dtype), y_ref, spec.dtype)
+    plan = layer.plan(spec.T)
+    assert plan["shared_rows"] == (T + plan["tile_rows"] - 1) // plan["tile_rows"] * plan["tile_rows"]
+    # importance profiling shares the row layout
+    imp = layer.profile_importance(dev["x"], dev["logits"], 1)
+    torch.cuda.synchronize()
+    assert torch.isfinite(imp).all()
+    layer.close()
