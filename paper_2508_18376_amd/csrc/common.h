@@ -45,6 +45,7 @@ struct Layout {
   int32_t lo, hi, E_res;      // resident window
   int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
   int32_t renorm, dtype, mfma, router_mfma;
+  int32_t g2_rows_inner;  // GEMM-2 item order: 1 = (expert, column tile, row tile), 0 = (expert, row tile, column tile)
   int32_t split_items;  // GEMM-2 splits K while tiles * column tiles * splits <= split_items (0: never)
   int32_t max_tokens;
   // plan geometry

@@ -427,7 +427,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     // order (expert, column tile, row tile, split): the row tiles that share one column tile of W2
     // are adjacent, so they run at the same time on one XCD and the weights are fetched once
     const int nt_e = (ne[e] + BM - 1) / BM;
-    items2[((size_t)ts[e] * L.ND2 + (size_t)jd * nt_e + i) * nsplit + sp] = v;
+    const size_t slot = L.g2_rows_inner ? (size_t)ts[e] * L.ND2 + (size_t)jd * nt_e + i : (size_t)gj;
+    items2[slot * nsplit + sp] = v;
   }
   // 6. per (expert, partition): rank of each active tile
   for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
