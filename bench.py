@@ -8,7 +8,7 @@ drop; the same line carries the 0 / 25 / 50 % sweep (tokens/s, algorithmic TFLOP
 bf16 MFMA peak), the roofline of the dominant kernel and the fp64 CPU oracle timed on a token
 sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--sample S] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--sample S] [--no-cpu] [--core-only]
 """
 import argparse
 import json
@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--sample", type=int, default=0, help="tokens for the CPU oracle leg (0 = per workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--core-only", action="store_true",
+                    help="only the layer's forward pass (no reconstruction / threshold selection / decode / router / "
+                         "transformation timings): what the rocprofv3 summaries are taken from")
     ap.add_argument("--rates", default="0,0.25,0.5")
     ap.add_argument("--primary-rate", type=float, default=0.25)
     args = ap.parse_args()
@@ -197,95 +200,98 @@ def main():
                 "unit": "TFLOP/s", "frac": g1_ach / BF16_PEAK_TFLOPS, "traffic": read_traffic(spec.name),
                 "avg_launch_ms": primary["gemm1_ms"], "flops_per_launch": g1_flops}
 
-    # reconstruction step that precedes the path (Sec. 4.2 b): importance of this batch used as the
-    # calibration set (every routed pair, no drops) and the order made from it; timed on its own
-    def ev_ms(fn, n):
-        fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
-
-    imp = torch.empty((spec.E_res, spec.F), dtype=torch.float32, device=dev)
-    perm_out = torch.empty((spec.E_res, spec.F), dtype=torch.int32, device=dev)
-    n_rec = max(2, K // 5)
-    rec_ms = ev_ms(lambda: ds.moe_profile_importance(layer.ctx, layer.packed, x, logits, spec.T, 3, imp, layer.workspace,
-                                                     stream), n_rec)
-    perm_ms = ev_ms(lambda: ds.moe_importance_to_perm(layer.ctx, imp, perm_out, stream), n_rec)
-    rec_flops = 4.0 * spec.D * spec.F * int(resident.sum())
-    reconstruction = {"profile_importance_ms": rec_ms, "profile_importance_tflops": rec_flops / (rec_ms * 1e-3) / 1e12,
-                      "importance_to_perm_ms": perm_ms, "calibration_tokens": spec.T, "metric": 3}
-    log("reconstruction: importance of %d tokens %.3f ms (%.0f TFLOP/s), order %.3f ms"
-        % (spec.T, rec_ms, reconstruction["profile_importance_tflops"], perm_ms))
-
-    # load-aware threshold selection on the device (Sec. 4.3): the step that can feed `tau` every batch
-    tau_sel = torch.empty((spec.E, spec.P), dtype=torch.float32, device=dev)
-    pairs_sel = torch.empty((spec.E,), dtype=torch.int32, device=dev)
-    tau_max_dev = torch.from_numpy(np.ascontiguousarray(primary["tau_table"][spec.lo])).to(dev)
-    cap_rows = int(1.25 * spec.T * spec.K / spec.E)
-    sel_ms = ev_ms(lambda: ds.moe_select_thresholds(layer.ctx, logits, spec.T, tau_max_dev, 1, cap_rows, tau_sel, pairs_sel,
-                                                    layer.workspace, stream), max(10, K))
-    selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows}
-    log("threshold selection (ratio rule + row cap %d): %.4f ms" % (cap_rows, sel_ms))
-
-    # gating product x W_g in front of the path (Sec. 3.1, first equation) and the complete transformation
-    from synth import make_router
-    wg_host = make_router(spec)
-    router_packed = torch.empty(max(ds.dsmoe_router_packed_bytes(layer.ctx), 16), dtype=torch.uint8, device=dev)
-    ds.moe_pack_router(layer.ctx, up(wg_host), router_packed, stream)
-    lg_out = torch.empty((spec.T, spec.E), dtype=torch.float32, device=dev)
-    router_ms = ev_ms(lambda: ds.moe_router_logits(layer.ctx, router_packed, x, spec.T, lg_out, stream), max(10, K))
-    routed_ms = ev_ms(lambda: ds.moe_dualsparse_forward_routed(layer.ctx, layer.packed, router_packed, x, primary["tau_dev"],
-                                                               spec.T, y, None, layer.workspace, stream), max(5, K // 2))
-    router_bytes = spec.T * spec.D * 2 + spec.T * spec.E * 4
-    router = {"router_logits_ms": router_ms, "GBps": router_bytes / (router_ms * 1e-3) / 1e9,
-              "forward_routed_ms": routed_ms}
-    log("router x W_g: %.4f ms (%.0f GB/s of x); whole layer with its own router %.3f ms" % (router_ms, router["GBps"], routed_ms))
-    del lg_out
-    w_dev = {k: up(host[k]) for k in ("w1", "w3", "w2")}
-    w_out = {k: torch.empty_like(v) for k, v in w_dev.items()}
-    wg_dev, wg_out = up(wg_host), torch.empty((spec.D, spec.E * spec.P), dtype=torch.bfloat16, device=dev)
-    perm_dev = up(host["perm"])
-    tr_ms = ev_ms(lambda: ds.moe_transform_complete(layer.ctx, wg_dev, w_dev["w1"], w_dev["w3"], w_dev["w2"], perm_dev, wg_out,
-                                                    w_out["w1"], w_out["w3"], w_out["w2"], layer.workspace, stream), 2)
-    w_bytes = sum(v.numel() * 2 for v in w_dev.values())
-    transform = {"transform_complete_ms": tr_ms, "GBps": 2 * w_bytes / (tr_ms * 1e-3) / 1e9}
-    log("complete transformation of %.2f GB of weights: %.2f ms (%.0f GB/s read + write)" % (w_bytes / 1e9, tr_ms, transform["GBps"]))
-    del w_dev, w_out
-
-    # decode-sized batches of the same layer (weight streaming regime): the first T tokens of the batch
+    reconstruction = selection = router = transform = None
     decode = []
-    w_unit_bytes = 3 * spec.D * Fp * 2
-    for Td in (16, 64, 256):
-        if Td > spec.T:
-            continue
-        xd, ld = x[:Td].contiguous(), logits[:Td].contiguous()
-        res_d = resident[:Td]
-        tab = np.tile(tau_for_drop_rate(n_all[:Td][res_d], spec.P, args.primary_rate)[None, :], (spec.E, 1)).astype(np.float32)
-        tau_d = torch.from_numpy(tab).to(dev)
-        ds.moe_route_and_mask(rctx, ld, Td, tau_d, r_idx, r_w, r_keep, r_gc)
-        torch.cuda.synchronize()
-        gc = r_gc.cpu().numpy()
-        active = int((gc > 0).sum())
-        wbytes = active * w_unit_bytes + 3 * spec.D * spec.F_sh * spec.n_shared * 2
-        yd = torch.empty((Td, spec.D), dtype=torch.bfloat16, device=dev)
-        fn = lambda: ds.moe_dualsparse_forward(layer.ctx, layer.packed, xd, ld, tau_d, Td, yd, layer.workspace, stream)
-        for _ in range(W):
+    if not args.core_only:
+        # reconstruction step that precedes the path (Sec. 4.2 b): importance of this batch used as the
+        # calibration set (every routed pair, no drops) and the order made from it; timed on its own
+        def ev_ms(fn, n):
             fn()
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(K):
-            fn()
-        torch.cuda.synchronize()
-        ms_d = (time.perf_counter() - t_start) / K * 1e3
-        decode.append({"tokens": Td, "ms_per_step": ms_d, "tokens_per_s": Td / (ms_d * 1e-3), "active_sub_experts": active,
-                       "kept_units": int(gc.sum()), "weight_bytes": wbytes, "GBps": wbytes / (ms_d * 1e-3) / 1e9,
-                       "frac_hbm_peak": wbytes / (ms_d * 1e-3) / 1e9 / 8000.0})
-        log("decode T=%d: %.3f ms/step, weights of %d active sub-experts %.2f GB -> %.0f GB/s (%.0f %% of 8 TB/s)"
-            % (Td, ms_d, active, wbytes / 1e9, decode[-1]["GBps"], 100 * decode[-1]["frac_hbm_peak"]))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        imp = torch.empty((spec.E_res, spec.F), dtype=torch.float32, device=dev)
+        perm_out = torch.empty((spec.E_res, spec.F), dtype=torch.int32, device=dev)
+        n_rec = max(2, K // 5)
+        rec_ms = ev_ms(lambda: ds.moe_profile_importance(layer.ctx, layer.packed, x, logits, spec.T, 3, imp, layer.workspace,
+                                                         stream), n_rec)
+        perm_ms = ev_ms(lambda: ds.moe_importance_to_perm(layer.ctx, imp, perm_out, stream), n_rec)
+        rec_flops = 4.0 * spec.D * spec.F * int(resident.sum())
+        reconstruction = {"profile_importance_ms": rec_ms, "profile_importance_tflops": rec_flops / (rec_ms * 1e-3) / 1e12,
+                          "importance_to_perm_ms": perm_ms, "calibration_tokens": spec.T, "metric": 3}
+        log("reconstruction: importance of %d tokens %.3f ms (%.0f TFLOP/s), order %.3f ms"
+            % (spec.T, rec_ms, reconstruction["profile_importance_tflops"], perm_ms))
+
+        # load-aware threshold selection on the device (Sec. 4.3): the step that can feed `tau` every batch
+        tau_sel = torch.empty((spec.E, spec.P), dtype=torch.float32, device=dev)
+        pairs_sel = torch.empty((spec.E,), dtype=torch.int32, device=dev)
+        tau_max_dev = torch.from_numpy(np.ascontiguousarray(primary["tau_table"][spec.lo])).to(dev)
+        cap_rows = int(1.25 * spec.T * spec.K / spec.E)
+        sel_ms = ev_ms(lambda: ds.moe_select_thresholds(layer.ctx, logits, spec.T, tau_max_dev, 1, cap_rows, tau_sel, pairs_sel,
+                                                        layer.workspace, stream), max(10, K))
+        selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows}
+        log("threshold selection (ratio rule + row cap %d): %.4f ms" % (cap_rows, sel_ms))
+
+        # gating product x W_g in front of the path (Sec. 3.1, first equation) and the complete transformation
+        from synth import make_router
+        wg_host = make_router(spec)
+        router_packed = torch.empty(max(ds.dsmoe_router_packed_bytes(layer.ctx), 16), dtype=torch.uint8, device=dev)
+        ds.moe_pack_router(layer.ctx, up(wg_host), router_packed, stream)
+        lg_out = torch.empty((spec.T, spec.E), dtype=torch.float32, device=dev)
+        router_ms = ev_ms(lambda: ds.moe_router_logits(layer.ctx, router_packed, x, spec.T, lg_out, stream), max(10, K))
+        routed_ms = ev_ms(lambda: ds.moe_dualsparse_forward_routed(layer.ctx, layer.packed, router_packed, x, primary["tau_dev"],
+                                                                   spec.T, y, None, layer.workspace, stream), max(5, K // 2))
+        router_bytes = spec.T * spec.D * 2 + spec.T * spec.E * 4
+        router = {"router_logits_ms": router_ms, "GBps": router_bytes / (router_ms * 1e-3) / 1e9,
+                  "forward_routed_ms": routed_ms}
+        log("router x W_g: %.4f ms (%.0f GB/s of x); whole layer with its own router %.3f ms" % (router_ms, router["GBps"], routed_ms))
+        del lg_out
+        w_dev = {k: up(host[k]) for k in ("w1", "w3", "w2")}
+        w_out = {k: torch.empty_like(v) for k, v in w_dev.items()}
+        wg_dev, wg_out = up(wg_host), torch.empty((spec.D, spec.E * spec.P), dtype=torch.bfloat16, device=dev)
+        perm_dev = up(host["perm"])
+        tr_ms = ev_ms(lambda: ds.moe_transform_complete(layer.ctx, wg_dev, w_dev["w1"], w_dev["w3"], w_dev["w2"], perm_dev, wg_out,
+                                                        w_out["w1"], w_out["w3"], w_out["w2"], layer.workspace, stream), 2)
+        w_bytes = sum(v.numel() * 2 for v in w_dev.values())
+        transform = {"transform_complete_ms": tr_ms, "GBps": 2 * w_bytes / (tr_ms * 1e-3) / 1e9}
+        log("complete transformation of %.2f GB of weights: %.2f ms (%.0f GB/s read + write)" % (w_bytes / 1e9, tr_ms, transform["GBps"]))
+        del w_dev, w_out
+
+        # decode-sized batches of the same layer (weight streaming regime): the first T tokens of the batch
+        decode = []
+        w_unit_bytes = 3 * spec.D * Fp * 2
+        for Td in (16, 64, 256):
+            if Td > spec.T:
+                continue
+            xd, ld = x[:Td].contiguous(), logits[:Td].contiguous()
+            res_d = resident[:Td]
+            tab = np.tile(tau_for_drop_rate(n_all[:Td][res_d], spec.P, args.primary_rate)[None, :], (spec.E, 1)).astype(np.float32)
+            tau_d = torch.from_numpy(tab).to(dev)
+            ds.moe_route_and_mask(rctx, ld, Td, tau_d, r_idx, r_w, r_keep, r_gc)
+            torch.cuda.synchronize()
+            gc = r_gc.cpu().numpy()
+            active = int((gc > 0).sum())
+            wbytes = active * w_unit_bytes + 3 * spec.D * spec.F_sh * spec.n_shared * 2
+            yd = torch.empty((Td, spec.D), dtype=torch.bfloat16, device=dev)
+            fn = lambda: ds.moe_dualsparse_forward(layer.ctx, layer.packed, xd, ld, tau_d, Td, yd, layer.workspace, stream)
+            for _ in range(W):
+                fn()
+            torch.cuda.synchronize()
+            t_start = time.perf_counter()
+            for _ in range(K):
+                fn()
+            torch.cuda.synchronize()
+            ms_d = (time.perf_counter() - t_start) / K * 1e3
+            decode.append({"tokens": Td, "ms_per_step": ms_d, "tokens_per_s": Td / (ms_d * 1e-3), "active_sub_experts": active,
+                           "kept_units": int(gc.sum()), "weight_bytes": wbytes, "GBps": wbytes / (ms_d * 1e-3) / 1e9,
+                           "frac_hbm_peak": wbytes / (ms_d * 1e-3) / 1e9 / 8000.0})
+            log("decode T=%d: %.3f ms/step, weights of %d active sub-experts %.2f GB -> %.0f GB/s (%.0f %% of 8 TB/s)"
+                % (Td, ms_d, active, wbytes / 1e9, decode[-1]["GBps"], 100 * decode[-1]["frac_hbm_peak"]))
 
     # proportionality of the time saved at the primary rate, against the 0 % run
     t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
