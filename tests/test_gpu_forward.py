@@ -266,3 +266,27 @@ def test_shared_experts_with_a_batch_smaller_than_max_tokens(oracle, dtype, T):
     torch.cuda.synchronize()
     assert torch.isfinite(imp).all()
     layer.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_one_context_serves_batches_of_different_sizes(oracle, dtype):
+    """A serving loop reuses one context and one workspace for batches of any size up to
+    max_tokens, large after small and small after large, with different thresholds: nothing a call
+    leaves in the workspace may leak into the next."""
+    import torch
+    if dtype == "bf16":
+        spec = spec_of(T=1400, D=128, F=256, E=8, K=2, P=2, n_shared=1, F_sh=64, seed=48)
+    else:
+        spec = spec_of(dtype="f32", T=300, D=40, F=48, E=6, K=3, P=3, x_std=0.5, w_std=0.1, seed=49)
+    t = make_layer(spec)
+    layer, dev = make_gpu_layer(spec, t)
+    for T, kind in ((spec.T, "rate0.25"), (1, 0.0), (spec.T // 3, "rate0.5"), (17, 2.0), (spec.T, 0.0), (64, "rate0.25")):
+        sub = spec.with_(T=T)
+        ts = dict(t)
+        ts["x"], ts["logits"] = t["x"][:T], t["logits"][:T]
+        tau = resolve_tau(oracle, sub, ts, kind)
+        y_ref = oracle_forward(oracle, sub, ts, tau)
+        y = layer.forward(dev["x"][:T].contiguous(), dev["logits"][:T].contiguous(), to_dev(tau))
+        torch.cuda.synchronize()
+        assert_output_close(to_host64(y, dtype), y_ref, dtype)
+    layer.close()
