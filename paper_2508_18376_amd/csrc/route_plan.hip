@@ -39,10 +39,11 @@ __device__ __forceinline__ int sub_of_bits(int bits, int nsub_bits) {
   return (1 << nsub_bits) - 1 - rev;
 }
 
-__device__ __forceinline__ int keep_bits_of(float n, int e, const RouteArgs& a) {
+// tau: the [E][P] threshold table (the wavefront kernel keeps a copy in LDS)
+__device__ __forceinline__ int keep_bits_of(float n, int e, const RouteArgs& a, const float* tau) {
   int bits = 0;
   if (e >= a.lo && e < a.hi) {
-    for (int p = 0; p < a.P; ++p) bits |= (n >= a.tau[e * a.P + p] ? 1 : 0) << p;
+    for (int p = 0; p < a.P; ++p) bits |= (n >= tau[e * a.P + p] ? 1 : 0) << p;
   }
   return bits;
 }
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
     for (int k = 0; k < KMAX; ++k) {
       if (k < a.K) {
         float n = sk[k] / sel;  // Sec. 4.1: normalise over the K selected
-        int bits = keep_bits_of(n, ik[k], a);
+        int bits = keep_bits_of(n, ik[k], a, a.tau);
         size_t o = (size_t)t * a.K + k;
         a.idx[o] = ik[k];
         a.w[o] = a.renorm ? n : sk[k];
@@ -124,13 +125,31 @@ __global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
   }
 }
 
+// Wavefront reductions on the vector ALU's data-parallel primitives (row shifts inside the four
+// rows of 16 lanes, then the two row broadcasts): lane 63 ends up with the total, which is read
+// back as a wavefront-uniform value.  Lanes without a source take the identity.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float identity, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
 __device__ __forceinline__ float wave_max(float v) {
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_f32<kRowShr1, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_f32<kRowShr2, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_f32<kRowShr4, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_f32<kRowShr8, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_f32<kRowBcast15, 0xa>(-INFINITY, v));
+  v = fmaxf(v, dpp_f32<kRowBcast31, 0xc>(-INFINITY, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_f32<kRowShr1, 0xf>(0.f, v);
+  v += dpp_f32<kRowShr2, 0xf>(0.f, v);
+  v += dpp_f32<kRowShr4, 0xf>(0.f, v);
+  v += dpp_f32<kRowShr8, 0xf>(0.f, v);
+  v += dpp_f32<kRowBcast15, 0xa>(0.f, v);
+  v += dpp_f32<kRowBcast31, 0xc>(0.f, v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // One wavefront per token, LPT logits per lane (E <= 64*LPT).  Every logit gets its rank under
@@ -142,6 +161,9 @@ template <int LPT>
 __global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
   extern __shared__ int32_t hist[];
   for (int i = threadIdx.x; i < a.nhist; i += 1024) hist[i] = 0;
+  // the threshold table is fetched now, together with the logits, not after the scores are known
+  float* tau_l = (float*)(hist + a.nhist);
+  for (int i = threadIdx.x; i < a.E * a.P; i += 1024) tau_l[i] = a.tau[i];
   __syncthreads();
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int t_end = min(a.T, ((int)blockIdx.x + 1) * kWaveTokens);
@@ -154,60 +176,98 @@ __global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       int e = lane + 64 * i;
-      lall[u][i] = (t < t_end && e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
+      const float v = (t < t_end && e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
+      lall[u][i] = v != v ? -INFINITY : v;  // a NaN logit ranks last, so every round below finds a winner
     }
   }
+  // The wavefront's tokens go through every step together: their reduction and ranking chains are
+  // independent, so their latencies overlap.  Tokens past the end carry -inf logits and are not stored.
+  float m[kTokPerWave], z[kTokPerWave];
 #pragma unroll
   for (int u = 0; u < kTokPerWave; ++u) {
-    const int t = blockIdx.x * kWaveTokens + wv + 16 * u;
-    if (t >= t_end) break;
-    float l[LPT];
+    float v = lall[u][0];
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) l[i] = lall[u][i];
-    float m = l[0];
+    for (int i = 1; i < LPT; ++i) v = fmaxf(v, lall[u][i]);
+    m[u] = v;
+  }
 #pragma unroll
-    for (int i = 1; i < LPT; ++i) m = fmaxf(m, l[i]);
-    m = wave_max(m);
-    float z = 0.f;
+  for (int u = 0; u < kTokPerWave; ++u) m[u] = wave_max(m[u]);
+#pragma unroll
+  for (int u = 0; u < kTokPerWave; ++u) {
+    float v = 0.f;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
-      if (lane + 64 * i < a.E) z += expf(l[i] - m);
-    z = wave_sum(z);
-    int rank[LPT];
+      if (lane + 64 * i < a.E) v += expf(lall[u][i] - m[u]);
+    z[u] = v;
+  }
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) rank[i] = 0;
-    for (int j = 0; j < 64; ++j) {
+  for (int u = 0; u < kTokPerWave; ++u) z[u] = wave_sum(z[u]);
+  // Top-K in K rounds of "largest logit not yet taken, lowest expert id among equals" (Eq. 2): a
+  // wavefront maximum, then a ballot of the lanes that hold it; slot k of the token is round k's
+  // winner.  rank = slot of a selected logit, a.K for the others.
+  int rank[kTokPerWave][LPT];
+  bool taken[kTokPerWave][LPT];
 #pragma unroll
-      for (int i2 = 0; i2 < LPT; ++i2) {
-        float ov = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l[i2]), j));
-        int oe = j + 64 * i2;
-        if (oe < a.E) {
+  for (int u = 0; u < kTokPerWave; ++u)
 #pragma unroll
-          for (int i = 0; i < LPT; ++i) {
-            int e = lane + 64 * i;
-            rank[i] += (ov > l[i] || (ov == l[i] && oe < e)) ? 1 : 0;
+    for (int i = 0; i < LPT; ++i) {
+      rank[u][i] = a.K;
+      taken[u][i] = lane + 64 * i >= a.E;
+    }
+  for (int k = 0; k < a.K; ++k) {
+    float g[kTokPerWave];
+#pragma unroll
+    for (int u = 0; u < kTokPerWave; ++u) {
+      float v = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) v = fmaxf(v, taken[u][i] ? -INFINITY : lall[u][i]);
+      g[u] = v;
+    }
+#pragma unroll
+    for (int u = 0; u < kTokPerWave; ++u) g[u] = wave_max(g[u]);
+#pragma unroll
+    for (int u = 0; u < kTokPerWave; ++u) {
+      bool found = false;  // wavefront-uniform
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) {  // expert ids grow with i first, then with the lane
+        const unsigned long long cand = __ballot(!taken[u][i] && lall[u][i] == g[u]);
+        if (!found && cand != 0ull) {
+          found = true;
+          if (lane == (int)__builtin_ctzll(cand)) {
+            rank[u][i] = k;
+            taken[u][i] = true;
           }
         }
       }
     }
-    float ssum = 0.f;
-    float s[LPT];
+  }
+  float s[kTokPerWave][LPT], ssum[kTokPerWave];
+#pragma unroll
+  for (int u = 0; u < kTokPerWave; ++u) {
+    float v = 0.f;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
-      bool selq = (lane + 64 * i < a.E) && rank[i] < a.K;
-      s[i] = selq ? expf(l[i] - m) / z : 0.f;  // Eq. 1
-      ssum += s[i];
+      const bool selq = (lane + 64 * i < a.E) && rank[u][i] < a.K;
+      s[u][i] = selq ? expf(lall[u][i] - m[u]) / z[u] : 0.f;  // Eq. 1
+      v += s[u][i];
     }
-    ssum = wave_sum(ssum);
+    ssum[u] = v;
+  }
+#pragma unroll
+  for (int u = 0; u < kTokPerWave; ++u) ssum[u] = wave_sum(ssum[u]);
+#pragma unroll
+  for (int u = 0; u < kTokPerWave; ++u) {
+    const int t = blockIdx.x * kWaveTokens + wv + 16 * u;
+    if (t >= t_end) continue;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
-      int e = lane + 64 * i;
-      if (e < a.E && rank[i] < a.K) {
-        float n = s[i] / ssum;  // Sec. 4.1: normalise over the K selected
-        int bits = keep_bits_of(n, e, a);
-        size_t o = (size_t)t * a.K + rank[i];
+      const int e = lane + 64 * i;
+      if (e < a.E && rank[u][i] < a.K) {
+        const float n = s[u][i] / ssum[u];  // Sec. 4.1: normalise over the K selected
+        const int bits = keep_bits_of(n, e, a, tau_l);
+        const size_t o = (size_t)t * a.K + rank[u][i];
         a.idx[o] = e;
-        a.w[o] = a.renorm ? n : s[i];
+        a.w[o] = a.renorm ? n : s[u][i];
         a.keep[o] = (uint8_t)bits;
         count_pair(hist, bits, e, a);
       }
@@ -244,7 +304,7 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
   a.nsub = L.nsub;
   a.nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   a.nhist = (bin_count ? L.nbins : 0) + (group_count ? L.E * L.P : 0);
-  const size_t sh = sizeof(int32_t) * (size_t)(a.nhist > 0 ? a.nhist : 1);
+  const size_t sh = sizeof(int32_t) * (size_t)(a.nhist + L.E * L.P);  // histogram + (wavefront kernel) threshold table
   if (L.E <= 32) {  // few experts: a lane per token, no cross-lane traffic
     dim3 grid((T + 63) / 64), block(64);
     if (L.E <= 8) route_lane_kernel<8, 8><<<grid, block, sh, s>>>(a);

@@ -72,3 +72,29 @@ def test_route_zero_tokens_and_limits():
     with pytest.raises(DsmoeError):
         layer.route_and_mask(torch.zeros((17, 8), dtype=torch.float32, device="cuda:0"), tau)
     layer.close()
+
+
+@pytest.mark.parametrize("E,K", [(8, 2), (64, 8), (160, 6)])
+def test_non_finite_logits_still_give_valid_expert_ids(E, K):
+    """NaN / infinite router logits give unspecified scores but never an invalid selection: K
+    distinct expert ids in range per token, and the layer's later steps stay in bounds."""
+    import torch
+    from paper_2508_18376_amd import DualSparseLayer
+    rng = np.random.default_rng(E)
+    T = 200
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[0, :] = np.nan
+    logits[1, :] = -np.inf
+    logits[2, ::2] = np.inf
+    logits[3, 1] = np.nan
+    logits[4:40, rng.integers(0, E, 36)] = np.nan
+    layer = DualSparseLayer(d_model=32, d_ff=32, n_experts=E, top_k=K, n_part=1, max_tokens=T, dtype="f32")
+    idx, w, keep, gc = layer.route_and_mask(to_dev(logits), to_dev(np.full((E, 1), 0.1, np.float32)))
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    assert idx.min() >= 0 and idx.max() < E
+    assert all(len(set(row)) == K for row in idx)
+    finite = np.isfinite(logits).all(axis=1)
+    ref_top = np.argsort(-logits[finite], axis=1, kind="stable")[:, :K]
+    np.testing.assert_array_equal(idx[finite], ref_top)
+    layer.close()
