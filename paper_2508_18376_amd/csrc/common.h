@@ -30,7 +30,9 @@ constexpr int kGenBM = 64;
 constexpr int kGenBN = 64;
 
 struct Item1 {  // one tile of GEMM-1: rows [row0, row0+nrows) x neurons tile jt of partition p
-  int32_t row0, nrows, e, p, jt, pad0, pad1, pad2;
+  int32_t row0, nrows, e, p, jt;
+  int32_t nfill;  // rows of the whole row tile (>= nrows): rows [nrows, nfill) keep nothing of p and get zeros
+  int32_t pad1, pad2;
 };
 struct Item2 {  // one tile of GEMM-2: rows x output column tile jd, summed over partitions in kmask
   int32_t row0, nrows, e, jd, kmask;

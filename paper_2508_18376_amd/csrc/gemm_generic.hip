@@ -85,8 +85,8 @@ __global__ __launch_bounds__(256) void gemm1_generic_kernel(Layout L, const char
   }
   for (int i = 0; i < 4; ++i) {
     int r = ty * 4 + i;
-    if (r >= it.nrows) continue;
-    bool kept = (row_bits[it.row0 + r] >> it.p) & 1;
+    if (r >= it.nfill) continue;  // rows [nrows, nfill) keep nothing of this partition: zeros
+    bool kept = r < it.nrows && ((row_bits[it.row0 + r] >> it.p) & 1);
     for (int j = 0; j < 4; ++j) {
       int c = tx * 4 + j;
       if (c >= ncols) continue;

@@ -288,8 +288,8 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
 #pragma unroll 4
     for (int c = 0; c < 16; ++c) {
       const int r = c * 16 + (tid >> 4);
-      if (r < g.it.nrows) {
-        const uint4 v = *(const uint4*)(lds + r * kHsRow + (tid & 15) * 16);
+      if (r < g.it.nfill) {  // rows [nrows, nfill) of the row tile keep nothing of this partition: zeros
+        const uint4 v = r < g.it.nrows ? *(const uint4*)(lds + r * kHsRow + (tid & 15) * 16) : make_uint4(0, 0, 0, 0);
         *(uint4*)(g.H + (size_t)(g.hrow0 + r) * g.ld + (size_t)g.it.p * g.Fp + n_in) = v;
       }
     }

@@ -458,6 +458,22 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     }
     return bits;
   };
+  // rows of tile i of expert e up to the last one that keeps partition p.  The rows are sorted by
+  // keep pattern, so with thresholds that grow with p this is exactly the number of rows that need
+  // p; in general it bounds them (rows before it that lack p are zeroed by the GEMM-1 epilogue).
+  auto tile_rows_for = [&](int e, int i, int p) {
+    const int r0 = i * BM, r1 = min(ne[e], r0 + BM);
+    if (e >= E_res || p >= nsub_bits) return r1 - r0;
+    int last = 0, off = 0;
+    for (int sb = 0; sb < L.nsub; ++sb) {
+      const int c = bin_count[e * L.nsub + sb];
+      const int rev = L.nsub - 1 - sb;
+      const bool has = (rev >> (nsub_bits - 1 - p)) & 1;
+      if (has && c > 0 && off < r1 && off + c > r0) last = max(last, min(r1, off + c) - r0);
+      off += c;
+    }
+    return last;
+  };
   // 5. GEMM-2 items: every tile x every output column tile.  With few row
   //    tiles (decode-sized batches) that is fewer items than compute units, and each item streams a
   //    whole column tile of W2 by itself: K is then split into nsplit ranges, each an item of its
@@ -518,10 +534,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     const int i = g - ts[e];
     Item1 v;
     v.row0 = rs[e] + i * BM;
-    v.nrows = min(ne[e] - i * BM, BM);
+    v.nfill = min(ne[e] - i * BM, BM);
+    v.nrows = tile_rows_for(e, i, p);
     v.e = e;
     v.p = p;
-    v.pad0 = v.pad1 = v.pad2 = 0;
+    v.pad1 = v.pad2 = 0;
     Item1* dst = items1 + gb[gi] + rk;
     for (int jt = 0; jt < nt1; ++jt) {
       v.jt = jt;
