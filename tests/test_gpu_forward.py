@@ -114,6 +114,7 @@ BF16_CASES = [
     ("D_wider_than_tile", spec_of(T=300, D=320, F=128, E=4, K=2, P=2, seed=19), "rate0.25", True),
     ("generic_fallback", spec_of(T=200, D=72, F=80, E=4, K=2, P=2, seed=20), "rate0.25", False),
     # the limits of the configuration at once: 512 experts, top-16, 8 parts
+    ("many_tokens", spec_of(T=70001, D=64, F=128, E=8, K=2, P=2, seed=23), "rate0.25", True),  # > 1024 row tiles, > 1000 route blocks
     ("max_experts_topk_parts", spec_of(T=300, D=32, F=256, E=512, K=16, P=8, seed=22), "rate0.25", True),
 ]
 
