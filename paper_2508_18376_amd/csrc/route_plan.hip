@@ -325,6 +325,7 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
 // two work lists of the grouped GEMMs.  Everything stays on the device: the GEMM grids are sized
 // for the worst case and read their item count from the counters this kernel writes.
 constexpr int kPlanThreads = 1024;
+constexpr int kPlanTilesLds = 2048;  // row tiles whose keep patterns fit in the plan kernel's LDS
 
 // exclusive scan of a[0..n) in LDS (n <= 8 * kPlanThreads); returns the total. tmp: kPlanThreads ints.
 __device__ int block_excl_scan(int32_t* a, int n, int32_t* tmp) {
@@ -458,6 +459,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     }
     return bits;
   };
+  // the keep pattern of every row tile, worked out once and in parallel (the per-group loop of
+  // step 6 walks the tiles of an expert one after the other and must not redo this for each)
+  // (kept in LDS when there are at most kPlanTilesLds tiles, else in the workspace)
+  int32_t* tbits = total_tiles <= kPlanTilesLds ? tmp + kPlanThreads : (int32_t*)(ws + L.o_tile_bits);
+  for (int g = tid; g < total_tiles; g += kPlanThreads) {
+    const int e = tile_expert(g);
+    tbits[g] = tile_bits_of(e, g - ts[e]);
+  }
+  __syncthreads();
   // rows of tile i of expert e up to the last one that keeps partition p.  The rows are sorted by
   // keep pattern, so with thresholds that grow with p this is exactly the number of rows that need
   // p; in general it bounds them (rows before it that lack p are zeroed by the GEMM-1 epilogue).
@@ -496,7 +506,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     v.nrows = min(ne[e] - i * BM, BM);
     v.e = e;
     v.jd = jd;
-    v.kmask = tile_bits_of(e, i);
+    v.kmask = tbits[g];
     v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
     v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
     v.split = sp;
@@ -512,7 +522,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     int nt = (ne[e] + BM - 1) / BM;
     int cnt = 0;
     for (int i = 0; i < nt; ++i) {
-      bool act = (tile_bits_of(e, i) >> p) & 1;
+      bool act = (tbits[ts[e] + i] >> p) & 1;
       act_rank[(size_t)(ts[e] + i) * L.P + p] = act ? cnt : -1;
       cnt += act ? 1 : 0;
     }
@@ -556,11 +566,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
   const int E_tot = L.E_res + (L.n_shared > 0 ? 1 : 0);
   const int NG = E_tot * L.P;
-  size_t sh = sizeof(int32_t) * (size_t)(L.nbins + 4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + 8);
+  size_t sh = sizeof(int32_t) * (size_t)(L.nbins + 4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + kPlanTilesLds + 8);
   if (sh > 48 * 1024) {  // hundreds of experts x 8 parts: up to ~78 KB, above what a launch gets without asking
     static bool attr_set = false;
     if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)plan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+      hipError_t e = hipFuncSetAttribute((const void*)plan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 104 * 1024);
       if (e != hipSuccess) return e;
       attr_set = true;
     }
