@@ -328,24 +328,36 @@ constexpr int kPlanThreads = 1024;
 constexpr int kPlanTilesLds = 2048;  // row tiles whose keep patterns fit in the plan kernel's LDS
 
 // exclusive scan of a[0..n) in LDS (n <= 8 * kPlanThreads); returns the total. tmp: kPlanThreads ints.
+// Each thread owns a run of elements; the runs are scanned inside each wavefront with lane shifts
+// and the sixteen wavefront totals by the first wavefront: three barriers in all.
 __device__ int block_excl_scan(int32_t* a, int n, int32_t* tmp) {
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int per = (n + kPlanThreads - 1) / kPlanThreads;
-  int lo = tid * per, hi = min(n, lo + per);
+  const int lo = tid * per, hi = min(n, lo + per);
   int sum = 0;
   for (int i = lo; i < hi; ++i) sum += a[i];
-  tmp[tid] = sum;
-  __syncthreads();
-  for (int off = 1; off < kPlanThreads; off <<= 1) {
-    int v = (tid >= off) ? tmp[tid - off] : 0;
-    __syncthreads();
-    tmp[tid] += v;
-    __syncthreads();
+  int incl = sum;  // inclusive scan over the lanes of this wavefront
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
   }
-  int total = tmp[kPlanThreads - 1];
-  int run = tmp[tid] - sum;
+  if (lane == 63) tmp[wv] = incl;
+  __syncthreads();
+  if (wv == 0) {
+    const int t = lane < kPlanThreads / 64 ? tmp[lane] : 0;
+    int inc = t;
+    for (int o = 1; o < kPlanThreads / 64; o <<= 1) {
+      const int v = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += v;
+    }
+    if (lane < kPlanThreads / 64) tmp[64 + lane] = inc - t;  // exclusive offset of each wavefront
+    if (lane == kPlanThreads / 64 - 1) tmp[128] = inc;       // grand total
+  }
+  __syncthreads();
+  int run = tmp[64 + wv] + incl - sum;
+  const int total = tmp[128];
   for (int i = lo; i < hi; ++i) {
-    int v = a[i];
+    const int v = a[i];
     a[i] = run;
     run += v;
   }
