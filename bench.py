@@ -8,7 +8,7 @@ drop; the same line carries the 0 / 25 / 50 % sweep (tokens/s, algorithmic TFLOP
 bf16 MFMA peak), the roofline of the dominant kernel and the fp64 CPU oracle timed on a token
 sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--sample S] [--no-cpu] [--core-only]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--sample S] [--no-cpu] [--core-only] [--tokens T]
 """
 import argparse
 import json
@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--sample", type=int, default=0, help="tokens for the CPU oracle leg (0 = per workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--tokens", type=int, default=0, help="batch size instead of the workload's own (e.g. 64: a decode step)")
     ap.add_argument("--core-only", action="store_true",
                     help="only the layer's forward pass (no reconstruction / threshold selection / decode / router / "
                          "transformation timings): what the rocprofv3 summaries are taken from")
@@ -68,6 +69,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     spec = LAYERS[args.workload]
+    if args.tokens:
+        spec = spec.with_(T=args.tokens)  # same layer, another batch size (decode-sized batches: 16..256)
     K, W = args.steps, args.warmup
 
     t0 = time.time()
