@@ -293,3 +293,45 @@ def test_one_context_serves_batches_of_different_sizes(oracle, dtype):
         torch.cuda.synchronize()
         assert_output_close(to_host64(y, dtype), y_ref, dtype)
     layer.close()
+
+
+def test_forward_can_be_captured_in_a_hip_graph_and_replayed(oracle):
+    """The forward call only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a serving loop can capture it once and replay it on new inputs placed in
+    the same buffers.  Every replay is checked against the eager result and the oracle, with eager
+    work and synchronisations between the replays."""
+    import torch
+    import paper_2508_18376_amd as ds
+    spec = spec_of(T=96, D=128, F=256, E=8, K=2, P=2, n_shared=1, F_sh=64, seed=50)
+    t = make_layer(spec)
+    layer, dev = make_gpu_layer(spec, t)
+    x_buf, lg_buf = dev["x"].clone(), dev["logits"].clone()
+    tau = resolve_tau(oracle, spec, t, "rate0.25")
+    tau_dev = to_dev(tau)
+    y_buf = torch.empty((spec.T, spec.D), dtype=torch.bfloat16, device=x_buf.device)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):  # warm-up outside the capture (one-time kernel attributes)
+        ds.moe_dualsparse_forward(layer.ctx, layer.packed, x_buf, lg_buf, tau_dev, spec.T, y_buf, layer.workspace, stream)
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        ds.moe_dualsparse_forward(layer.ctx, layer.packed, x_buf, lg_buf, tau_dev, spec.T, y_buf, layer.workspace,
+                                  torch.cuda.current_stream())
+    for rep in range(3):
+        sub = spec.with_(seed=spec.seed + 10 * rep)
+        t2 = make_layer(sub, weights=False)
+        x_buf.copy_(to_dev(t2["x"]))
+        lg_buf.copy_(to_dev(t2["logits"]))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        y_graph = y_buf.clone()
+        y_eager = layer.forward(x_buf, lg_buf, tau_dev)  # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager)
+        ts = dict(t)
+        ts["x"], ts["logits"] = t2["x"], t2["logits"]
+        r = oracle.route(t2["logits"], spec.K, spec.P, tau)
+        if r.min_margin > GUARD:  # thresholds were picked for the first batch; later batches only where safe
+            assert_output_close(to_host64(y_graph, "bf16"), oracle_forward(oracle, spec, ts, tau), "bf16")
+    layer.close()
