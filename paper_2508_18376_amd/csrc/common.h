@@ -68,7 +68,7 @@ struct Layout {
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
 };
 
-constexpr int kNumKernels = 7;  // fill, route, plan, scatter, gemm1, gemm2, combine
+constexpr int kNumKernels = 7;  // router (if any), route, plan, scatter, gemm1, gemm2, combine
 
 struct Profile {
   int level = 0;       // 0 off, 1 GEMM-1 only, 2 every kernel
