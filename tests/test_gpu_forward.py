@@ -335,3 +335,33 @@ def test_forward_can_be_captured_in_a_hip_graph_and_replayed(oracle):
         if r.min_margin > GUARD:  # thresholds were picked for the first batch; later batches only where safe
             assert_output_close(to_host64(y_graph, "bf16"), oracle_forward(oracle, spec, ts, tau), "bf16")
     layer.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_empty_batch_is_a_no_op_everywhere(dtype):
+    """T = 0: every entry point returns OK without touching its outputs."""
+    import torch
+    import paper_2508_18376_amd as ds
+    spec = spec_of(dtype=dtype, T=8, D=64, F=64, E=4, K=2, P=2, seed=51)
+    t = make_layer(spec)
+    layer, dev = make_gpu_layer(spec, t)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x0 = torch.empty((0, spec.D), dtype=tdt, device="cuda")
+    l0 = torch.empty((0, spec.E), dtype=torch.float32, device="cuda")
+    tau = to_dev(tau_table(spec, 0.1))
+    y = layer.forward(x0, l0, tau)
+    assert y.shape == (0, spec.D)
+    idx, w, keep, gc = layer.route_and_mask(l0, tau)
+    torch.cuda.synchronize()
+    assert gc.cpu().numpy().tolist() == [0] * (spec.E * spec.P)
+    imp = layer.profile_importance(x0, l0, 0)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(imp).item() == 0
+    layer.pack_router(to_dev(__import__("synth").make_router(spec)))
+    assert layer.router_logits(x0).shape == (0, spec.E)
+    assert layer.forward_routed(x0, tau).shape == (0, spec.D)
+    # and the context still works afterwards
+    y = layer.forward(dev["x"], dev["logits"], tau)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    layer.close()
