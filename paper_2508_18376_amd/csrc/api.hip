@@ -69,7 +69,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.row_cap = L.sh_rows + rt * L.BM;
   L.max_tiles = rt + shared_tiles(L, Tm);
   L.max_items1 = rt * L.P * L.NT1 + shared_tiles(L, Tm) * L.NT1_sh;
-  L.max_items2 = L.max_tiles * L.ND2 > L.split_items ? L.max_tiles * L.ND2 : L.split_items;
+  L.max_items2 = L.max_tiles * L.ND2 + (L.split_items > 0 ? kPoolTiles : 0);
 
   int64_t o = 0;
   auto take = [&](int64_t bytes) {
@@ -98,14 +98,13 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_row_bits = take((int64_t)L.row_cap);
   L.o_H = take((int64_t)(L.row_cap - L.sh_rows) * L.F * elem);
   L.o_Hs = take((int64_t)L.sh_rows * L.F_shT * elem);
-  {  // partial outputs of a split K need one slab of rows per split: splits * tiles <= split_items / ND2
-    const int64_t split_rows = (int64_t)(L.split_items / L.ND2) * L.BM;
-    L.o_Yp = take((split_rows > L.row_cap ? split_rows : (int64_t)L.row_cap) * L.D * 4);
-  }
+  L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
   L.o_sel = take((int64_t)L.E * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both
   L.o_logits = take((int64_t)Tm * L.E * 4);
   L.o_perm_check = take(((int64_t)L.E_res * L.F + 1) * 4);
+  L.o_pool = take(L.split_items > 0 ? (int64_t)kPoolTiles * kMfmaBM * kMfmaBN2 * 4 : 0);  // partial outputs of split K ranges
+  L.o_split_of = take(L.split_items > 0 ? (int64_t)L.max_tiles * L.ND2 * 4 : 0);          // (row tile, column tile) -> first pool tile, or -1
   L.ws_bytes = o;
 
   // packed weights

@@ -11,8 +11,10 @@ constexpr int kMaxTopK = 16;
 constexpr int kMaxExperts = 512;
 constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
-constexpr int kSplitItems = 256;  // GEMM-2 splits K while that keeps its items within one per compute unit (measured best)
-constexpr int kMaxSplit = 8;   // most K ranges GEMM-2 is split into when there are few row tiles
+constexpr int kSplitItems = 256;  // one GEMM-2 item per compute unit: the granularity K splits aim at (measured best)
+constexpr int kMaxSplit = 8;      // most K ranges an item is split into when there are few row tiles (decode-sized batches)
+constexpr int kMaxTailSplit = 4;  // most K ranges an item of the last, partly filled round of items is split into
+constexpr int kPoolTiles = 256;   // partial-output tiles (256 x 256 fp32) the extra K ranges can need at most
 constexpr int kSelBins = 4096;  // grid of the row-budget thresholds: multiples of 2^-12 (a power of two keeps n * kSelBins exact)
 constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels (one histogram row each)
 
@@ -37,7 +39,7 @@ struct Item1 {  // one tile of GEMM-1: rows [row0, row0+nrows) x neurons tile jt
 struct Item2 {  // one tile of GEMM-2: rows x output column tile jd, summed over partitions in kmask
   int32_t row0, nrows, e, jd, kmask;
   int32_t ks_lo, ks_n;  // K stages [ks_lo, ks_lo + ks_n) of every kept partition (the whole partition unless K is split)
-  int32_t split;        // index of the partial-output slab this item writes (0 unless K is split)
+  int32_t split;        // 0: the item writes its rows of Yp; n > 0: it writes partial-output tile n-1 of the pool
 };
 
 // Everything the device code needs to know about the layer and the workspace.
@@ -48,7 +50,7 @@ struct Layout {
   int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
   int32_t renorm, dtype, mfma, router_mfma;
   int32_t g2_rows_inner;  // GEMM-2 item order: 1 = (expert, column tile, row tile), 0 = (expert, row tile, column tile)
-  int32_t split_items;  // GEMM-2 splits K while tiles * column tiles * splits <= split_items (0: never)
+  int32_t split_items;  // kSplitItems if GEMM-2 may split K (MFMA path), else 0
   int32_t max_tokens;
   // plan geometry
   int32_t BM;                 // row tile height
@@ -62,7 +64,7 @@ struct Layout {
   // workspace byte offsets
   int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
   int64_t o_tile_e, o_tile_row0, o_tile_nrows, o_tile_bits, o_act_rank, o_items1, o_items2;
-  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, o_logits, o_perm_check, ws_bytes;
+  int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, o_logits, o_perm_check, o_pool, o_split_of, ws_bytes;
   // packed weights byte offsets
   int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes, router_bytes;
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
@@ -93,7 +95,7 @@ inline int items1_bound(const Layout& L, int T) {
 }
 inline int items2_bound(const Layout& L, int T) {
   const int whole = (routed_tiles_bound(L, T) + shared_tiles(L, T)) * L.ND2;
-  return whole > L.split_items ? whole : L.split_items;  // K is split only while the items stay within split_items
+  return whole + (L.split_items > 0 ? kPoolTiles : 0);  // every extra K range of a split item is one more item
 }
 
 // launchers (each returns hipError_t of the launch)

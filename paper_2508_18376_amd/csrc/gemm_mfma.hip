@@ -354,7 +354,8 @@ struct G2Args {
   int np, KSp, nstages, D;
   i32x4 rsW, rsH;
   uint32_t hoff[4], woff, lds_w;
-  float* Yp;
+  float* Y;   // where row 0, column 0 of this item's output tile goes
+  int ldy;    // its row stride: D in Yp, 256 in a pool tile
 };
 
 // MFMA A = pair rows of H, B = output columns of W2.
@@ -393,7 +394,7 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
     for (int v = 0; v < 16; ++v) {
       const int r = a_row0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
       if (r >= g.it.nrows) continue;
-      float* yrow = g.Yp + (size_t)(g.it.row0 + r) * g.D + g.it.jd * kMfmaBN2;
+      float* yrow = g.Y + (size_t)r * g.ldy;
 #pragma unroll
       for (int j = 0; j < J; ++j) {
         const int c = b_row0 + j * 32 + (lane & 31);
@@ -425,7 +426,13 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   const char* hbase = (const char*)(H + (size_t)hrow0 * ld);
   g.rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
   g.rsH = make_rsrc(hbase, (uint32_t)((int64_t)g.it.nrows * ld * 2));
-  g.Yp = (float*)(ws + L.o_Yp) + (size_t)g.it.split * counters[2] * kMfmaBM * L.D;  // this split's slab of partial outputs
+  if (g.it.split == 0) {  // the item's rows of Yp
+    g.Y = (float*)(ws + L.o_Yp) + (size_t)g.it.row0 * L.D + g.it.jd * kMfmaBN2;
+    g.ldy = L.D;
+  } else {  // an extra K range of a split item: a partial-output tile of the pool
+    g.Y = (float*)(ws + L.o_pool) + (size_t)(g.it.split - 1) * kMfmaBM * kMfmaBN2;
+    g.ldy = kMfmaBN2;
+  }
 
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll

@@ -496,19 +496,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     }
     return last;
   };
-  // 5. GEMM-2 items: every tile x every output column tile.  With few row
-  //    tiles (decode-sized batches) that is fewer items than compute units, and each item streams a
-  //    whole column tile of W2 by itself: K is then split into nsplit ranges, each an item of its
-  //    own that writes a partial-output slab; the combine kernel adds the slabs in a fixed order.
-  int nsplit = 1;
-  {
+  // 5. GEMM-2 items: every tile x every output column tile.  The compute units take the items in
+  //    list order, one each.  Where that leaves units idle, items are split along K: every extra K
+  //    range is an item of its own that writes a partial-output tile into a pool, and the combine
+  //    kernel adds those tiles to the item's rows of Yp in a fixed order.
+  //    (a) few row tiles (decode-sized batches): fewer items than units, each streaming a whole
+  //        column tile of W2 alone -> all items are split, into as many ranges as keep the list
+  //        within one item per unit;
+  //    (b) the last round of a longer list is less than half full -> its items are split so that
+  //        the round is about full.
+  const int W2n = total_tiles * L.ND2;
+  int nsplit = 1, first_split = W2n;  // items first_split .. W2n-1 (in list order) are split nsplit ways
+  if (L.split_items > 0 && W2n > 0) {
     int ksp = L.Fp / kBK;
     if (has_sh) ksp = min(ksp, L.F_shT / kBK);
-    const int whole = total_tiles * L.ND2;
-    while (nsplit < kMaxSplit && whole * nsplit * 2 <= L.split_items && nsplit * 2 <= ksp) nsplit *= 2;
+    if (W2n * 2 <= L.split_items) {
+      while (nsplit < kMaxSplit && W2n * nsplit * 2 <= L.split_items && nsplit * 2 <= ksp) nsplit *= 2;
+      first_split = 0;
+    } else {
+      const int rest = W2n % L.split_items;
+      if (rest > 0 && rest * 2 <= L.split_items) {
+        nsplit = min(min(L.split_items / rest, kMaxTailSplit), ksp);
+        first_split = W2n - rest;
+      }
+    }
+    if (nsplit == 1) first_split = W2n;
   }
-  for (int it = tid; it < total_tiles * L.ND2 * nsplit; it += kPlanThreads) {
-    const int sp = it % nsplit, gj = it / nsplit;
+  int32_t* split_of = (int32_t*)(ws + L.o_split_of);
+  for (int gj = tid; gj < W2n; gj += kPlanThreads) {
     const int g = gj / L.ND2, jd = gj % L.ND2;
     const int e = tile_expert(g);
     const int i = g - ts[e];
@@ -519,14 +534,27 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     v.e = e;
     v.jd = jd;
     v.kmask = tbits[g];
-    v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
-    v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
-    v.split = sp;
-    // order (expert, column tile, row tile, split): the row tiles that share one column tile of W2
-    // are adjacent, so they run at the same time on one XCD and the weights are fetched once
+    // list order (expert, column tile, row tile) if g2_rows_inner: the row tiles that share one column
+    // tile of W2 are adjacent, run at the same time on one XCD and fetch the weights once;
+    // else (row tile, column tile)
     const int nt_e = (ne[e] + BM - 1) / BM;
-    const size_t slot = L.g2_rows_inner ? (size_t)ts[e] * L.ND2 + (size_t)jd * nt_e + i : (size_t)gj;
-    items2[slot * nsplit + sp] = v;
+    const int slot = L.g2_rows_inner ? ts[e] * L.ND2 + jd * nt_e + i : gj;
+    if (slot < first_split) {
+      v.ks_lo = 0;
+      v.ks_n = ksp;
+      v.split = 0;
+      items2[slot] = v;
+      if (L.split_items > 0) split_of[gj] = -1;
+    } else {
+      const int q = slot - first_split;  // q-th split item: its extra ranges use pool tiles q*(nsplit-1) ..
+      for (int sp = 0; sp < nsplit; ++sp) {
+        v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
+        v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
+        v.split = sp == 0 ? 0 : 1 + q * (nsplit - 1) + (sp - 1);
+        items2[first_split + q * nsplit + sp] = v;
+      }
+      split_of[gj] = q * (nsplit - 1);
+    }
   }
   // 6. per (expert, partition): rank of each active tile
   for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
@@ -569,7 +597,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   }
   if (tid == 0) {
     counters[0] = total1;
-    counters[1] = total_tiles * L.ND2 * nsplit;
+    counters[1] = first_split + (W2n - first_split) * nsplit;
     counters[2] = total_tiles;
     counters[3] = nsplit;
   }
@@ -676,28 +704,28 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
   if (L.n_shared > 0) acc = *(const float4*)(Yp + (size_t)t * L.D + d);  // shared rows sit first in the row space
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   const int nsplit = counters[3];
-  if (nsplit > 1) {  // GEMM-2 split K: add the partial-output slabs in slab order
-    const size_t slab = (size_t)counters[2] * L.BM * L.D;
-    for (int sp = 1; sp < nsplit; ++sp) {
-      const float* Ys = Yp + sp * slab;
+  if (nsplit > 1) {  // GEMM-2 split K: add the partial-output tiles of the extra K ranges, in range order
+    const int32_t* split_of = (const int32_t*)(ws + L.o_split_of);
+    const float* pool = (const float*)(ws + L.o_pool);
+    const int jd = d / kMfmaBN2, dc = d - jd * kMfmaBN2;
+    auto add_extra = [&](int r, float4& into) {  // r: a row of the row space
+      const int tile = r / L.BM;
+      const int first = split_of[(size_t)tile * L.ND2 + jd];
+      if (first < 0) return;
+      const float* src = pool + ((size_t)first * L.BM + (r - tile * L.BM)) * kMfmaBN2 + dc;
+      for (int sp = 1; sp < nsplit; ++sp) {
+        const float4 u = *(const float4*)src;
+        into.x += u.x;
+        into.y += u.y;
+        into.z += u.z;
+        into.w += u.w;
+        src += (size_t)L.BM * kMfmaBN2;
+      }
+    };
 #pragma unroll
-      for (int k = 0; k < KB; ++k) {
-        if (row[k] >= 0) {
-          const float4 u = *(const float4*)(Ys + (size_t)row[k] * L.D + d);
-          v[k].x += u.x;
-          v[k].y += u.y;
-          v[k].z += u.z;
-          v[k].w += u.w;
-        }
-      }
-      if (L.n_shared > 0) {
-        const float4 u = *(const float4*)(Ys + (size_t)t * L.D + d);
-        acc.x += u.x;
-        acc.y += u.y;
-        acc.z += u.z;
-        acc.w += u.w;
-      }
-    }
+    for (int k = 0; k < KB; ++k)
+      if (row[k] >= 0) add_extra(row[k], v[k]);
+    if (L.n_shared > 0) add_extra(t, acc);
   }
 #pragma unroll
   for (int k = 0; k < KB; ++k) {
