@@ -82,7 +82,10 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_w = take(npairs * 4);
   L.o_keep = take(npairs);
   L.o_pair_row = take(npairs * 4);
-  L.o_bin_count = take((int64_t)cdiv(Tm, kRouteBlockTokens) * L.nbins * 4);  // one histogram row per route block
+  {  // one histogram row per route block
+    const int rows_small = cdiv(Tm < kWaveSmallBatch ? Tm : kWaveSmallBatch, kWaveBlockTokens), rows_big = cdiv(Tm, kRouteBlockTokens);
+    L.o_bin_count = take((int64_t)(rows_small > rows_big ? rows_small : rows_big) * L.nbins * 4);
+  }
   L.o_cursor = take((int64_t)L.nbins * 4);
   L.o_exp_nrows = take((int64_t)L.E_res * 4);
   L.o_exp_row0 = take((int64_t)L.E_res * 4);

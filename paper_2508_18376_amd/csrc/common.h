@@ -16,7 +16,12 @@ constexpr int kMaxSplit = 8;      // most K ranges an item is split into when th
 constexpr int kMaxTailSplit = 4;  // most K ranges an item of the last, partly filled round of items is split into
 constexpr int kPoolTiles = 256;   // partial-output tiles (256 x 256 fp32) the extra K ranges can need at most
 constexpr int kSelBins = 4096;  // grid of the row-budget thresholds: multiples of 2^-12 (a power of two keeps n * kSelBins exact)
-constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels (one histogram row each)
+constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels, one histogram row each ...
+constexpr int kWaveBlockTokens = 16;   // ... except the wavefront kernel (E > 32) on small batches: 4 wavefronts x 4 tokens
+constexpr int kWaveSmallBatch = 2048;  // largest batch that uses the small blocks (more blocks would swamp the plan kernel's sum)
+inline __host__ __device__ int route_block_tokens(int E, int T) {
+  return (E <= 32 || T > kWaveSmallBatch) ? kRouteBlockTokens : kWaveBlockTokens;
+}
 
 // MFMA path tile shape: 256 rows (token-expert pairs) x 128 neurons (gate+up = 256 weight rows)
 // for GEMM-1, 256 rows x 256 output columns for GEMM-2, K stage 32.

@@ -153,26 +153,28 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // One wavefront per token, LPT logits per lane (E <= 64*LPT).  Every logit gets its rank under
-// (value descending, index ascending); ranks below K are the selected slots.  A block is sixteen
-// wavefronts that walk kWaveTokens tokens and share one LDS histogram.
-constexpr int kWaveTokens = kRouteBlockTokens;  // tokens per block
+// (value descending, index ascending); ranks below K are the selected slots.  A block is WAVES
+// wavefronts that walk 4 tokens each and share one LDS histogram: 16 wavefronts (64 tokens) for
+// large batches, 4 (one per SIMD: the Top-K rounds are bound by instruction issue) for small ones.
 
-template <int LPT>
-__global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
+template <int LPT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void route_wave_kernel(RouteArgs a) {
+  constexpr int kWaveThreads = WAVES * 64, kWaveTokens = WAVES * 4;
   extern __shared__ int32_t hist[];
-  for (int i = threadIdx.x; i < a.nhist; i += 1024) hist[i] = 0;
+  for (int i = threadIdx.x; i < a.nhist; i += kWaveThreads) hist[i] = 0;
   // the threshold table is fetched now, together with the logits, not after the scores are known
   float* tau_l = (float*)(hist + a.nhist);
-  for (int i = threadIdx.x; i < a.E * a.P; i += 1024) tau_l[i] = a.tau[i];
-  __syncthreads();
+  for (int i = threadIdx.x; i < a.E * a.P; i += kWaveThreads) tau_l[i] = a.tau[i];
+  // (the barrier that publishes hist and tau_l sits right before their first use, after the scores)
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int t_end = min(a.T, ((int)blockIdx.x + 1) * kWaveTokens);
   // all logits of this wavefront's tokens are requested before the first is used
-  constexpr int kTokPerWave = kWaveTokens / 16;
+  constexpr int kWaves = kWaveThreads / 64;
+  constexpr int kTokPerWave = kWaveTokens / kWaves;
   float lall[kTokPerWave][LPT];
 #pragma unroll
   for (int u = 0; u < kTokPerWave; ++u) {
-    const int t = blockIdx.x * kWaveTokens + wv + 16 * u;
+    const int t = blockIdx.x * kWaveTokens + wv + kWaves * u;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       int e = lane + 64 * i;
@@ -255,9 +257,10 @@ __global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
   }
 #pragma unroll
   for (int u = 0; u < kTokPerWave; ++u) ssum[u] = wave_sum(ssum[u]);
+  __syncthreads();  // hist is cleared and tau_l is complete
 #pragma unroll
   for (int u = 0; u < kTokPerWave; ++u) {
-    const int t = blockIdx.x * kWaveTokens + wv + 16 * u;
+    const int t = blockIdx.x * kWaveTokens + wv + kWaves * u;
     if (t >= t_end) continue;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(1024) void route_wave_kernel(RouteArgs a) {
   }
   __syncthreads();
   const int nb = a.bin_count ? (a.hi - a.lo) * a.nsub : 0;
-  for (int i = threadIdx.x; i < a.nhist; i += 1024) {
+  for (int i = threadIdx.x; i < a.nhist; i += kWaveThreads) {
     int c = hist[i];
     if (i < nb) a.bin_count[(size_t)blockIdx.x * nb + i] = c;  // this block's row of the histogram: no atomics
     else if (c) atomicAdd(&a.group_count[i - nb], c);
@@ -310,12 +313,18 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
     if (L.E <= 8) route_lane_kernel<8, 8><<<grid, block, sh, s>>>(a);
     else if (L.E <= 16) route_lane_kernel<16, 16><<<grid, block, sh, s>>>(a);
     else route_lane_kernel<32, 16><<<grid, block, sh, s>>>(a);
-  } else {  // many experts: a wavefront per token
-    dim3 grid((T + kWaveTokens - 1) / kWaveTokens), block(1024);
-    if (L.E <= 64) route_wave_kernel<1><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 128) route_wave_kernel<2><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 256) route_wave_kernel<4><<<grid, block, sh, s>>>(a);
-    else route_wave_kernel<8><<<grid, block, sh, s>>>(a);
+  } else if (T > kWaveSmallBatch) {  // many experts: a wavefront per token, 64 tokens per block
+    dim3 grid((T + kRouteBlockTokens - 1) / kRouteBlockTokens), block(1024);
+    if (L.E <= 64) route_wave_kernel<1, 16><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 128) route_wave_kernel<2, 16><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 256) route_wave_kernel<4, 16><<<grid, block, sh, s>>>(a);
+    else route_wave_kernel<8, 16><<<grid, block, sh, s>>>(a);
+  } else {  // small batch: 16 tokens per block
+    dim3 grid((T + kWaveBlockTokens - 1) / kWaveBlockTokens), block(256);
+    if (L.E <= 64) route_wave_kernel<1, 4><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 128) route_wave_kernel<2, 4><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 256) route_wave_kernel<4, 4><<<grid, block, sh, s>>>(a);
+    else route_wave_kernel<8, 4><<<grid, block, sh, s>>>(a);
   }
   return hipGetLastError();
 }
@@ -371,7 +380,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   int32_t* bin_count = sm;  // [nbins]
   {
     const int32_t* blk_hist = (const int32_t*)(ws + L.o_bin_count);
-    const int nblk = (T + kRouteBlockTokens - 1) / kRouteBlockTokens;
+    const int nblk = (T + route_block_tokens(L.E, T) - 1) / route_block_tokens(L.E, T);
     for (int i = threadIdx.x; i < L.nbins; i += kPlanThreads) bin_count[i] = 0;
     __syncthreads();
     const int total = nblk * L.nbins;
