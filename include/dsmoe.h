@@ -24,7 +24,11 @@
  *   - moe_route_and_mask and moe_dualsparse_forward only enqueue kernels: no host
  *     synchronisation, no allocation.  moe_partition_weights synchronises the stream once
  *     (it reads back the permutation check).
- *   - NaN router logits give unspecified routing (not an error).
+ *   - NaN router logits give unspecified routing (not an error): a NaN logit ranks last, every token
+ *     still gets K distinct expert ids in range, and no later step leaves its buffers.
+ *   - A context keeps a little host-side state per call (profiling events, the last plan's row
+ *     layout): host threads must not call into the SAME context at the same time.  Several
+ *     contexts, each with its own workspace, may run concurrently on different streams.
  */
 #ifndef DSMOE_H
 #define DSMOE_H
