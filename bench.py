@@ -255,7 +255,8 @@ def main():
         router_bytes = spec.T * spec.D * 2 + spec.T * spec.E * 4
         router = {"router_logits_ms": router_ms, "GBps": router_bytes / (router_ms * 1e-3) / 1e9,
                   "forward_routed_ms": routed_ms}
-        log("router x W_g: %.4f ms (%.0f GB/s of x); whole layer with its own router %.3f ms" % (router_ms, router["GBps"], routed_ms))
+        log("router x W_g: %.4f ms (%.0f GB/s of x); layer driven by those logits (another routing, same tau table) %.3f ms"
+            % (router_ms, router["GBps"], routed_ms))
         del lg_out
         w_dev = {k: up(host[k]) for k in ("w1", "w3", "w2")}
         w_out = {k: torch.empty_like(v) for k, v in w_dev.items()}
