@@ -163,3 +163,53 @@ def test_generators_are_seeded_and_order_independent():
     bias = zipf_logit_bias(c5)
     assert abs(np.exp(bias).sum() - 1.0) < 1e-5 and bias.argmax() == 0 and c5.resident == (0, 2)
     assert [LAYERS[k].T for k in ("C1", "C2", "C3", "C4", "C5")] == [64, 4096, 8192, 8192, 16384]
+
+
+def test_later_entry_points_validate_before_touching_the_gpu(lib):
+    """Bad arguments of the reconstruction / threshold / router / transformation calls are refused
+    on the host (no GPU is present in this test)."""
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    rc, ctx = create(lib, max_tokens=64)
+    assert rc == 0
+    fake = ctypes.c_void_p(4096)       # non-null, 256-byte aligned; never dereferenced by a refused call
+    odd = ctypes.c_void_p(4096 + 8)    # misaligned workspace
+    lib.moe_profile_importance.restype = ctypes.c_int
+    lib.moe_profile_importance.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
+    assert lib.moe_profile_importance(ctx, fake, fake, fake, 4, 4, fake, fake, None) == -1    # metric 0..3
+    assert lib.moe_profile_importance(ctx, fake, fake, fake, 65, 0, fake, fake, None) == -1   # T > max_tokens
+    assert lib.moe_profile_importance(ctx, fake, fake, fake, 4, 0, fake, odd, None) == -1     # workspace alignment
+    assert lib.moe_profile_importance(ctx, fake, None, fake, 4, 0, fake, fake, None) == -1    # x missing
+    lib.moe_importance_to_perm.restype = ctypes.c_int
+    lib.moe_importance_to_perm.argtypes = [vp, vp, vp, vp]
+    assert lib.moe_importance_to_perm(ctx, None, fake, None) == -1
+    lib.moe_select_thresholds.restype = ctypes.c_int
+    lib.moe_select_thresholds.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
+    assert lib.moe_select_thresholds(ctx, fake, 4, fake, 3, 0, fake, None, fake, None) == -1   # 3 does not divide 8 experts
+    assert lib.moe_select_thresholds(ctx, fake, 4, fake, 0, 0, fake, None, fake, None) == -1
+    assert lib.moe_select_thresholds(ctx, fake, 4, fake, 1, -1, fake, None, fake, None) == -1  # negative row budget
+    assert lib.moe_select_thresholds(ctx, fake, 4, None, 1, 0, fake, None, fake, None) == -1   # tau_max missing
+    assert lib.moe_select_thresholds(ctx, fake, 65, fake, 1, 0, fake, None, fake, None) == -1
+    lib.moe_pack_router.restype = lib.moe_router_logits.restype = ctypes.c_int
+    lib.moe_pack_router.argtypes = [vp, vp, vp, vp]
+    lib.moe_router_logits.argtypes = [vp, vp, vp, i32, vp, vp]
+    assert lib.moe_pack_router(ctx, None, fake, None) == -1
+    assert lib.moe_router_logits(ctx, None, fake, 4, fake, None) == -1
+    assert lib.moe_router_logits(ctx, fake, fake, 4, None, None) == -1
+    assert lib.moe_router_logits(ctx, fake, odd, 4, fake, None) == -1                          # x must be 16-byte aligned
+    lib.moe_dualsparse_forward_routed.restype = ctypes.c_int
+    lib.moe_dualsparse_forward_routed.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    assert lib.moe_dualsparse_forward_routed(ctx, fake, None, fake, fake, 4, fake, None, fake, None) == -1
+    assert lib.moe_dualsparse_forward_routed(ctx, fake, fake, fake, fake, 65, fake, None, fake, None) == -1
+    lib.moe_transform_complete.restype = ctypes.c_int
+    lib.moe_transform_complete.argtypes = [vp] * 12
+    assert lib.moe_transform_complete(ctx, None, None, fake, fake, None, None, fake, fake, fake, None, None) == -1   # w1 missing
+    assert lib.moe_transform_complete(ctx, fake, fake, fake, fake, None, None, fake, fake, fake, None, None) == -1   # wg without wg_out
+    assert lib.moe_transform_complete(ctx, None, fake, fake, fake, fake, None, fake, fake, fake, None, None) == -1   # perm needs a workspace
+    lib.dsmoe_router_packed_bytes.restype = ctypes.c_size_t
+    lib.dsmoe_router_packed_bytes.argtypes = [vp]
+    assert lib.dsmoe_router_packed_bytes(ctx) == 128 * 8 * 4          # fp32 layer: W_g widened to float, [D][E]
+    rc, c2 = create(lib, d_model=4096, d_ff=14336, n_part=4, max_tokens=64, dtype=1)
+    assert lib.dsmoe_router_packed_bytes(c2) == 4096 * 32 * 2         # MFMA operand order, experts padded to 32
+    lib.dsmoe_destroy.argtypes = [vp]
+    lib.dsmoe_destroy(ctx)
+    lib.dsmoe_destroy(c2)
