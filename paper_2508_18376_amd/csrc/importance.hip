@@ -27,8 +27,17 @@ __global__ __launch_bounds__(256) void colsum_kernel(Layout L, const char* ws, f
   const T* H = (const T*)(ws + L.o_H);
   const int n = exp_nrows[e];
   const size_t r0 = (size_t)(exp_row0[e] - L.sh_rows);
+  // rows are added in order (deterministic); eight loads are in flight at a time
   float acc = 0.f;
-  for (int r = 0; r < n; ++r) acc += ld_h<T>(H, (r0 + r) * L.F + q);
+  int r = 0;
+  for (; r + 8 <= n; r += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = ld_h<T>(H, (r0 + r + u) * L.F + q);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; r < n; ++r) acc += ld_h<T>(H, (r0 + r) * L.F + q);
   importance[(size_t)e * L.F + q] = acc;
 }
 
