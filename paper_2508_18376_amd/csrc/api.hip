@@ -90,9 +90,6 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_exp_nrows = take((int64_t)L.E_res * 4);
   L.o_exp_row0 = take((int64_t)L.E_res * 4);
   L.o_counters = take(16);
-  L.o_tile_e = take((int64_t)L.max_tiles * 4);
-  L.o_tile_row0 = take((int64_t)L.max_tiles * 4);
-  L.o_tile_nrows = take((int64_t)L.max_tiles * 4);
   L.o_tile_bits = take((int64_t)L.max_tiles * 4);
   L.o_act_rank = take((int64_t)L.max_tiles * L.P * 4);
   L.o_items1 = take((int64_t)L.max_items1 * sizeof(Item1));

@@ -68,7 +68,7 @@ struct Layout {
   int32_t max_tiles, max_items1, max_items2;
   // workspace byte offsets
   int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
-  int64_t o_tile_e, o_tile_row0, o_tile_nrows, o_tile_bits, o_act_rank, o_items1, o_items2;
+  int64_t o_tile_bits, o_act_rank, o_items1, o_items2;
   int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, o_logits, o_perm_check, o_pool, o_split_of, ws_bytes;
   // packed weights byte offsets
   int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes, router_bytes;
