@@ -264,3 +264,49 @@ def complete_transform(wg: np.ndarray, w1: np.ndarray, w3: np.ndarray, w2: np.nd
             rows = w2[e][own, :]
             w2_t[e * P + p] = _narrow_like(_widen(rows) * P, w2) if scale_w2 else rows
     return wg_t, w1_t, w3_t, w2_t
+
+
+@dataclass
+class DropRateThresholds:
+    tau: np.ndarray        # [E][P] float32, the same row for every expert
+    centre_bin: int        # b: thresholds are (b + offset_bins[p]) / n_bins
+    dropped_units: int     # units of resident pairs below their threshold
+    total_units: int       # resident pairs * P
+    min_margin: float      # min distance of a resident score to the grid values that decide centre_bin
+
+
+def thresholds_for_drop_rate(logits: np.ndarray, K: int, P: int, rate: float, offset_bins, lo: int = 0,
+                             hi: Optional[int] = None, n_bins: int = 4096) -> DropRateThresholds:
+    """The map from a target drop rate to thresholds (Sec. 5.3.3: the relation is not linear, so it
+    is read off the batch's own score distribution; Sec. 4.2 c: the partitions' thresholds keep fixed
+    offsets around a centre, e.g. -0.01 / +0.01).
+
+    Thresholds live on the grid of multiples of 1/n_bins: tau_p = (b + offset_bins[p]) / n_bins.  b is
+    the smallest integer for which at least rate * total_units units of the pairs routed to the
+    resident experts [lo, hi) fall below their threshold (unit (pair, p) is dropped iff n < tau_p).
+    Plain counting over the candidates, scores compared in single precision."""
+    f32 = np.float32
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    hi = E if hi is None else hi
+    off = [int(v) for v in offset_bins]
+    assert len(off) == P
+    r = route(logits, K, P, np.zeros((E, P), np.float32))
+    n = r.n.astype(np.float32)[(r.idx >= lo) & (r.idx < hi)]
+    total = int(n.size) * P
+    need = rate * total
+
+    def dropped(b):
+        return sum(int((n < f32(b + k) / f32(n_bins)).sum()) for k in off)
+
+    b = -max(off)                        # every threshold <= 0: nothing can be dropped
+    top = n_bins + 1 - min(off)          # every threshold > 1: everything is dropped
+    while b < top and dropped(b) < need:
+        b += 1
+    tau = np.tile(np.array([f32(b + k) / f32(n_bins) for k in off], dtype=np.float32)[None, :], (E, 1))
+    margin = np.inf
+    if n.size:
+        for k in off:
+            for edge in (b + k, b - 1 + k):
+                margin = min(margin, float(np.abs(n.astype(np.float64) - edge / n_bins).min()))
+    return DropRateThresholds(tau, b, dropped(b), total, float(margin))

@@ -659,3 +659,46 @@ def test_thresholds_of_the_transformed_layer_are_the_originals_over_P(oracle):
     assert min(r.min_margin, rt.min_margin) > 1e-9
     np.testing.assert_array_equal(rt.keep[:, :, 0], np.repeat(r.keep[:, :, 0], P, axis=1))
     np.testing.assert_allclose(rt.n, np.repeat(r.n, P, axis=1) / P, rtol=1e-12)
+
+
+# ------------------------------------------------ drop rate -> thresholds (Sec. 5.3.3, Sec. 4.2 c)
+def test_drop_rate_thresholds_follow_the_order_statistics(oracle):
+    """One partition: dropping at least a fraction `rate` of m scores needs the threshold just above
+    the ceil(rate*m)-th smallest score v: b = floor(v*B) + 1 (closed form, not the counting loop)."""
+    rng = np.random.default_rng(23)
+    T, E, K, B = 500, 8, 2, 4096
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    r = oracle.route(logits, K, 1, np.zeros((E, 1), np.float32))
+    n32 = np.sort(r.n.astype(np.float32).ravel())
+    for rate in (0.1, 0.25, 0.5, 0.9):
+        res = oracle.thresholds_for_drop_rate(logits, K, 1, rate, [0], n_bins=B)
+        need = int(np.ceil(rate * n32.size))
+        v = float(n32[need - 1])
+        assert res.centre_bin == int(np.floor(v * B)) + 1
+        assert res.total_units == n32.size and res.dropped_units >= need
+        # one grid step lower drops too little; the keep decision itself agrees with the count
+        keep = oracle.route(logits, K, 1, res.tau).keep
+        assert int((keep == 0).sum()) == res.dropped_units
+        lower = oracle.route(logits, K, 1, res.tau - np.float32(1.0 / B)).keep
+        assert int((lower == 0).sum()) < need
+
+
+def test_drop_rate_thresholds_with_partition_offsets_and_window(oracle):
+    rng = np.random.default_rng(24)
+    T, E, K, P, B = 400, 8, 2, 2, 4096
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    res = oracle.thresholds_for_drop_rate(logits, K, P, 0.3, [-41, 41], lo=2, hi=6, n_bins=B)
+    # the two thresholds are 82 grid steps (~0.02) apart, the same for every expert
+    assert np.all(res.tau == res.tau[0]) and res.tau[0, 1] - res.tau[0, 0] == np.float32(82 / B)
+    rr = oracle.route(logits, K, P, res.tau, lo=2, hi=6)
+    resident = (rr.idx >= 2) & (rr.idx < 6)
+    assert res.total_units == int(resident.sum()) * P
+    dropped = int((rr.keep[resident] == 0).sum())
+    assert dropped == res.dropped_units and dropped >= 0.3 * res.total_units
+    one_less = oracle.route(logits, K, P, res.tau - np.float32(1.0 / B), lo=2, hi=6)
+    assert int((one_less.keep[resident] == 0).sum()) < 0.3 * res.total_units
+    # extremes: rate 0 drops nothing (thresholds <= 0), rate 1 drops everything (thresholds > 1)
+    r0 = oracle.thresholds_for_drop_rate(logits, K, P, 0.0, [-41, 41], n_bins=B)
+    assert r0.dropped_units == 0 and np.all(r0.tau <= 0)
+    r1 = oracle.thresholds_for_drop_rate(logits, K, P, 1.0, [-41, 41], n_bins=B)
+    assert r1.dropped_units == r1.total_units and np.all(r1.tau[:, 0] > 0.9)
