@@ -240,8 +240,16 @@ def main():
         cap_rows = int(1.25 * spec.T * spec.K / spec.E)
         sel_ms = ev_ms(lambda: ds.moe_select_thresholds(layer.ctx, logits, spec.T, tau_max_dev, 1, cap_rows, tau_sel, pairs_sel,
                                                         layer.workspace, stream), max(10, K))
-        selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows}
-        log("threshold selection (ratio rule + row cap %d): %.4f ms" % (cap_rows, sel_ms))
+        off_bins = [0] if spec.P == 1 else [round(41 * (2 * p - (spec.P - 1)) / (spec.P - 1)) for p in range(spec.P)]
+        stats_sel = torch.empty((2,), dtype=torch.int32, device=dev)
+        rate_ms = ev_ms(lambda: ds.moe_thresholds_for_drop_rate(layer.ctx, logits, spec.T, args.primary_rate, off_bins, tau_sel,
+                                                                stats_sel, layer.workspace, stream), max(10, K))
+        st = stats_sel.cpu().numpy()
+        selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows,
+                     "thresholds_for_drop_rate_ms": rate_ms, "target_drop": args.primary_rate,
+                     "device_chosen_drop": float(st[0]) / max(float(st[1]), 1.0)}
+        log("threshold selection (ratio rule + row cap %d): %.4f ms; thresholds for %.0f %% drop: %.4f ms (realised %.1f %%)"
+            % (cap_rows, sel_ms, 100 * args.primary_rate, rate_ms, 100 * selection["device_chosen_drop"]))
 
         # gating product x W_g in front of the path (Sec. 3.1, first equation) and the complete transformation
         from synth import make_router

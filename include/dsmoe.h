@@ -205,6 +205,21 @@ int moe_select_thresholds(dsmoe_ctx* ctx, const float* logits, int32_t T, const 
                           int32_t row_cap, float* tau, int32_t* pair_count, void* workspace, void* stream);
 
 /*
+ * Thresholds for a target drop rate, chosen on the device from the batch's own score distribution
+ * (Sec. 5.3.3: the relation between threshold and drop rate is not linear; Sec. 4.2 c: the
+ * partitions' thresholds keep fixed offsets around a centre, e.g. T - 0.01 / T + 0.01).
+ *   Thresholds live on the grid of multiples of 2^-12: tau[e][p] = (b + offset_bins[p]) / 4096, the
+ *   same row for every expert.  b is the smallest integer for which at least rate * (resident pairs
+ *   * P) units of the pairs routed to the resident experts fall below their threshold.
+ *   logits device float [T][E]; rate in [0, 1]; offset_bins HOST int32 [P], each in [-4096, 4096]
+ *   (0.01 is 41 grid steps); tau device float [E][P] (output);
+ *   stats device int32 [2] (output, may be NULL): dropped units, resident pairs * P.
+ *   workspace as for moe_dualsparse_forward (overwritten).  Asynchronous, no allocation.
+ */
+int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx, const float* logits, int32_t T, float rate, const int32_t* offset_bins,
+                                 float* tau, int32_t* stats, void* workspace, void* stream);
+
+/*
  * Inspection of the last forward call's plan, for tests: byte offsets into the workspace.
  * Fills out[0..DSMOE_PLAN_FIELDS-1]; returns the number of fields.
  *   0 topk_idx int32[T*K]      1 topk_w float[T*K]        2 keep_bits uint8[T*K]

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     moe_profile_importance,
     moe_importance_to_perm,
     moe_select_thresholds,
+    moe_thresholds_for_drop_rate,
     moe_pack_router,
     moe_router_logits,
     moe_dualsparse_forward_routed,

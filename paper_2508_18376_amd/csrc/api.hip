@@ -100,7 +100,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_Hs = take((int64_t)L.sh_rows * L.F_shT * elem);
   L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
-  L.o_sel = take((int64_t)L.E * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both
+  L.o_sel = take((int64_t)(L.E + 1) * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both; row E: resident pairs
   L.o_logits = take((int64_t)Tm * L.E * 4);
   L.o_perm_check = take(((int64_t)L.E_res * L.F + 1) * 4);
   L.o_pool = take(L.split_items > 0 ? (int64_t)kPoolTiles * kMfmaBM * kMfmaBN2 * 4 : 0);  // partial outputs of split K ranges
@@ -452,12 +452,34 @@ int moe_select_thresholds(dsmoe_ctx* ctx_, const float* logits, int32_t T, const
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
   // zero thresholds for the routing pass and a cleared score histogram (adjacent in the workspace)
-  const int64_t clear = (L.o_sel - L.o_tau0) / 4 + (int64_t)L.E * (kSelBins + 2);
+  const int64_t clear = (L.o_sel - L.o_tau0) / 4 + (int64_t)(L.E + 1) * (kSelBins + 2);
   hipError_t err = launch_fill_i32((int32_t*)(ws + L.o_tau0), clear, 0, s);
   if (err == hipSuccess && T > 0)
     err = launch_route(L, logits, T, (const float*)(ws + L.o_tau0), (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w),
                        (uint8_t*)(ws + L.o_keep), nullptr, nullptr, s, true);
   if (err == hipSuccess) err = launch_select_thresholds(L, T, tau_max, group_size, row_cap, ws, tau, pair_count, s);
+  if (err != hipSuccess) return hip_fail(ctx, err);
+  return DSMOE_OK;
+}
+
+int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx_, const float* logits, int32_t T, float rate, const int32_t* offset_bins,
+                                 float* tau, int32_t* stats, void* workspace, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !offset_bins || !tau || !workspace || !(rate >= 0.f && rate <= 1.f)) return DSMOE_EINVAL;
+  if (T > 0 && !logits) return DSMOE_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0) return DSMOE_EINVAL;
+  const Layout& L = ctx->L;
+  if (T > L.max_tokens) return DSMOE_EINVAL;
+  for (int p = 0; p < L.P; ++p)
+    if (offset_bins[p] < -kSelBins || offset_bins[p] > kSelBins) return DSMOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  const int64_t clear = (L.o_sel - L.o_tau0) / 4 + (int64_t)(L.E + 1) * (kSelBins + 2);
+  hipError_t err = launch_fill_i32((int32_t*)(ws + L.o_tau0), clear, 0, s);
+  if (err == hipSuccess && T > 0)
+    err = launch_route(L, logits, T, (const float*)(ws + L.o_tau0), (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w),
+                       (uint8_t*)(ws + L.o_keep), nullptr, nullptr, s, true);
+  if (err == hipSuccess) err = launch_drop_rate_thresholds(L, T, rate, offset_bins, ws, tau, stats, s);
   if (err != hipSuccess) return hip_fail(ctx, err);
   return DSMOE_OK;
 }

@@ -14,15 +14,21 @@ namespace dsmoe {
 
 constexpr int kSelRow = kSelBins + 2;
 
+// row E of sel (when asked for) is the histogram over the pairs of the resident experts [lo, hi)
 __global__ __launch_bounds__(256) void score_hist_kernel(const int32_t* __restrict__ idx, const float* __restrict__ n,
-                                                         int64_t npairs, int32_t* __restrict__ sel) {
+                                                         int64_t npairs, int32_t* __restrict__ sel, int E, int lo, int hi,
+                                                         int resident_row) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= npairs) return;
   const int e = idx[i];
   int b = (int)floorf(n[i] * (float)kSelBins);
   b = b < 0 ? 0 : (b > kSelBins ? kSelBins : b);
-  atomicAdd(&sel[(int64_t)e * kSelRow + b], 1);
-  atomicAdd(&sel[(int64_t)e * kSelRow + kSelBins + 1], 1);
+  if (!resident_row) {
+    atomicAdd(&sel[(int64_t)e * kSelRow + b], 1);
+    atomicAdd(&sel[(int64_t)e * kSelRow + kSelBins + 1], 1);
+  } else if (e >= lo && e < hi) {
+    atomicAdd(&sel[(int64_t)E * kSelRow + b], 1);
+  }
 }
 
 // One workgroup per expert.
@@ -88,11 +94,97 @@ hipError_t launch_select_thresholds(const Layout& L, int T, const float* tau_max
   const int64_t npairs = (int64_t)T * L.K;
   if (npairs > 0) {
     score_hist_kernel<<<dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s>>>((const int32_t*)(ws + L.o_idx),
-                                                                                     (const float*)(ws + L.o_w), npairs, sel);
+                                                                                     (const float*)(ws + L.o_w), npairs, sel, L.E, L.lo, L.hi, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   tau_pick_kernel<<<dim3(L.E), dim3(256), 0, s>>>(sel, tau_max, T, L.E, L.K, L.P, group_size, row_cap, tau, pair_count);
+  return hipGetLastError();
+}
+
+// Thresholds for a target drop rate (Sec. 5.3.3: the relation between threshold and drop rate is
+// read off the batch's own score distribution; Sec. 4.2 c: the partitions keep fixed offsets).
+// h = histogram of floor(n * kSelBins) over the resident pairs.  Unit (pair, p) is dropped iff
+// n < (b + off[p]) / kSelBins, i.e. iff bin(n) < b + off[p]: with C(x) = pairs whose bin is below x,
+// the dropped units at centre b are sum_p C(b + off[p]).  One workgroup: prefix counts in LDS, then
+// the smallest b with at least `need` dropped units by bisection (the count grows with b).
+struct DropRateArgs {
+  int32_t off[kMaxPart];
+  int P, E;
+  float rate;
+};
+__global__ __launch_bounds__(1024) void drop_rate_pick_kernel(const int32_t* __restrict__ h, DropRateArgs a,
+                                                              float* __restrict__ tau, int32_t* __restrict__ stats) {
+  __shared__ int32_t below[kSelBins + 2];  // below[x] = pairs with bin < x, x = 0 .. kSelBins+1
+  __shared__ int32_t part[1024];
+  const int tid = threadIdx.x;
+  constexpr int per = (kSelBins + 1 + 1023) / 1024;  // bins per thread (5)
+  int sum = 0;
+  for (int j = 0; j < per; ++j) {
+    const int b = tid * per + j;
+    sum += b <= kSelBins ? h[b] : 0;
+  }
+  part[tid] = sum;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {  // inclusive scan of the per-thread sums
+    const int v = tid >= o ? part[tid - o] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = part[tid] - sum;
+  for (int j = 0; j < per; ++j) {
+    const int b = tid * per + j;
+    if (b <= kSelBins + 1) below[b] = run;
+    run += b <= kSelBins ? h[b] : 0;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int pairs = below[kSelBins + 1];
+    auto C = [&](int x) { return x <= 0 ? 0 : (x > kSelBins + 1 ? pairs : below[x]); };
+    auto dropped = [&](int b) {
+      int d = 0;
+      for (int p = 0; p < a.P; ++p) d += C(b + a.off[p]);
+      return d;
+    };
+    int omax = a.off[0], omin = a.off[0];
+    for (int p = 1; p < a.P; ++p) {
+      omax = max(omax, a.off[p]);
+      omin = min(omin, a.off[p]);
+    }
+    const double need = (double)a.rate * ((double)pairs * a.P);
+    int lo_b = -omax, hi_b = kSelBins + 1 - omin;  // nothing dropped .. everything dropped
+    while (lo_b < hi_b) {                          // smallest b with dropped(b) >= need
+      const int mid = lo_b + ((hi_b - lo_b) >> 1);
+      if ((double)dropped(mid) >= need) hi_b = mid;
+      else lo_b = mid + 1;
+    }
+    for (int e = 0; e < a.E; ++e)
+      for (int p = 0; p < a.P; ++p) tau[e * a.P + p] = (float)(lo_b + a.off[p]) / (float)kSelBins;
+    if (stats) {
+      stats[0] = dropped(lo_b);
+      stats[1] = pairs * a.P;
+    }
+  }
+}
+
+hipError_t launch_drop_rate_thresholds(const Layout& L, int T, float rate, const int32_t* offset_bins, char* ws, float* tau,
+                                       int32_t* stats, hipStream_t s) {
+  int32_t* sel = (int32_t*)(ws + L.o_sel);
+  const int64_t npairs = (int64_t)T * L.K;
+  if (npairs > 0) {
+    score_hist_kernel<<<dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s>>>((const int32_t*)(ws + L.o_idx),
+                                                                                     (const float*)(ws + L.o_w), npairs, sel,
+                                                                                     L.E, L.lo, L.hi, 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  DropRateArgs a;
+  for (int p = 0; p < kMaxPart; ++p) a.off[p] = p < L.P ? offset_bins[p] : 0;
+  a.P = L.P;
+  a.E = L.E;
+  a.rate = rate;
+  drop_rate_pick_kernel<<<dim3(1), dim3(1024), 0, s>>>(sel + (int64_t)L.E * kSelRow, a, tau, stats);
   return hipGetLastError();
 }
 

@@ -189,6 +189,13 @@ def test_later_entry_points_validate_before_touching_the_gpu(lib):
     assert lib.moe_select_thresholds(ctx, fake, 4, fake, 1, -1, fake, None, fake, None) == -1  # negative row budget
     assert lib.moe_select_thresholds(ctx, fake, 4, None, 1, 0, fake, None, fake, None) == -1   # tau_max missing
     assert lib.moe_select_thresholds(ctx, fake, 65, fake, 1, 0, fake, None, fake, None) == -1
+    lib.moe_thresholds_for_drop_rate.restype = ctypes.c_int
+    lib.moe_thresholds_for_drop_rate.argtypes = [vp, vp, i32, ctypes.c_float, ctypes.POINTER(i32), vp, vp, vp, vp]
+    offs = (i32 * 2)(-41, 41)
+    assert lib.moe_thresholds_for_drop_rate(ctx, fake, 4, 1.5, offs, fake, None, fake, None) == -1             # rate in [0, 1]
+    assert lib.moe_thresholds_for_drop_rate(ctx, fake, 4, float("nan"), offs, fake, None, fake, None) == -1
+    assert lib.moe_thresholds_for_drop_rate(ctx, fake, 4, 0.25, (i32 * 2)(0, 5000), fake, None, fake, None) == -1  # offset off the grid
+    assert lib.moe_thresholds_for_drop_rate(ctx, fake, 4, 0.25, None, fake, None, fake, None) == -1
     lib.moe_pack_router.restype = lib.moe_router_logits.restype = ctypes.c_int
     lib.moe_pack_router.argtypes = [vp, vp, vp, vp]
     lib.moe_router_logits.argtypes = [vp, vp, vp, i32, vp, vp]

@@ -98,3 +98,54 @@ def test_full_size_olmoe_router(oracle):
     np.testing.assert_array_equal(tau.cpu().numpy().view(np.uint32), sel.tau.view(np.uint32))
     assert (sel.cap_bin > 0).any() and (sel.ratio < 1).any() and (sel.ratio > 1).any()
     layer.close()
+
+
+DROP_CASES = [
+    # name, T, E, K, P, window, rate, offsets
+    ("one_threshold", 2000, 8, 2, 1, None, 0.25, [0]),
+    ("two_thresholds", 3000, 8, 2, 2, None, 0.25, [-41, 41]),
+    ("four_parts", 4096, 8, 2, 4, None, 0.5, [-41, -14, 14, 41]),
+    ("fine_grained_window", 2500, 64, 8, 2, (8, 24), 0.3, [-41, 41]),
+    ("many_experts", 600, 160, 6, 2, None, 0.1, [-20, 20]),
+    ("drop_nothing", 500, 8, 2, 2, None, 0.0, [-41, 41]),
+    ("drop_everything", 500, 8, 2, 2, None, 1.0, [-41, 41]),
+]
+
+
+@pytest.mark.parametrize("name,T,E,K,P,window,rate,offsets", DROP_CASES, ids=[c[0] for c in DROP_CASES])
+def test_thresholds_for_a_target_drop_rate_equal_the_oracle(oracle, name, T, E, K, P, window, rate, offsets):
+    import torch
+    lo, hi = window if window else (0, E)
+    for seed in range(200, 230):  # a batch whose scores keep clear of the deciding grid values
+        logits = skewed_logits(T, E, seed, 0.5)
+        ref = oracle.thresholds_for_drop_rate(logits, K, P, rate, offsets, lo=lo, hi=hi)
+        if rate in (0.0, 1.0) or ref.min_margin > GUARD:
+            break
+    else:
+        raise AssertionError("no batch with a safe margin")
+    layer = make_layer_obj(E, K, P, T, lo=lo, hi=hi)
+    tau, stats = layer.thresholds_for_drop_rate(to_dev(logits), rate, offsets)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(tau.cpu().numpy().view(np.uint32), ref.tau.view(np.uint32))
+    assert stats.cpu().numpy().tolist() == [ref.dropped_units, ref.total_units]
+    # the table does what it says when the layer's own mask uses it
+    idx, w, keep, gc = layer.route_and_mask(to_dev(logits), tau)
+    torch.cuda.synchronize()
+    kept = int(gc.sum().item())
+    assert ref.total_units - kept == ref.dropped_units
+    if 0 < rate < 1:
+        assert ref.dropped_units >= rate * ref.total_units > ref.dropped_units - P * max(1, T * K // 50)
+    layer.close()
+
+
+def test_default_offsets_spread_one_hundredth_each_way():
+    import torch
+    layer = make_layer_obj(8, 2, 4, 64)
+    logits = to_dev(skewed_logits(64, 8, 1, 0.0))
+    tau, _ = layer.thresholds_for_drop_rate(logits, 0.25)
+    torch.cuda.synchronize()
+    row = tau[0].cpu().numpy()
+    np.testing.assert_allclose(np.diff(row), [27 / 4096, 28 / 4096, 27 / 4096], atol=1e-7)   # -41, -14, 14, 41 grid steps
+    with pytest.raises(RuntimeError):
+        layer.thresholds_for_drop_rate(logits, 1.5)
+    layer.close()

@@ -672,7 +672,7 @@ def test_drop_rate_thresholds_follow_the_order_statistics(oracle):
     n32 = np.sort(r.n.astype(np.float32).ravel())
     for rate in (0.1, 0.25, 0.5, 0.9):
         res = oracle.thresholds_for_drop_rate(logits, K, 1, rate, [0], n_bins=B)
-        need = int(np.ceil(rate * n32.size))
+        need = int(np.ceil(float(np.float32(rate)) * n32.size))  # the rate is a single-precision argument
         v = float(n32[need - 1])
         assert res.centre_bin == int(np.floor(v * B)) + 1
         assert res.total_units == n32.size and res.dropped_units >= need
@@ -694,9 +694,9 @@ def test_drop_rate_thresholds_with_partition_offsets_and_window(oracle):
     resident = (rr.idx >= 2) & (rr.idx < 6)
     assert res.total_units == int(resident.sum()) * P
     dropped = int((rr.keep[resident] == 0).sum())
-    assert dropped == res.dropped_units and dropped >= 0.3 * res.total_units
+    assert dropped == res.dropped_units and dropped >= float(np.float32(0.3)) * res.total_units
     one_less = oracle.route(logits, K, P, res.tau - np.float32(1.0 / B), lo=2, hi=6)
-    assert int((one_less.keep[resident] == 0).sum()) < 0.3 * res.total_units
+    assert int((one_less.keep[resident] == 0).sum()) < float(np.float32(0.3)) * res.total_units
     # extremes: rate 0 drops nothing (thresholds <= 0), rate 1 drops everything (thresholds > 1)
     r0 = oracle.thresholds_for_drop_rate(logits, K, P, 0.0, [-41, 41], n_bins=B)
     assert r0.dropped_units == 0 and np.all(r0.tau <= 0)
