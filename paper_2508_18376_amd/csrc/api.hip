@@ -474,8 +474,10 @@ int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx_, const float* logits, int32_t T
     if (offset_bins[p] < -kSelBins || offset_bins[p] > kSelBins) return DSMOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  const int64_t clear = (L.o_sel - L.o_tau0) / 4 + (int64_t)(L.E + 1) * (kSelBins + 2);
-  hipError_t err = launch_fill_i32((int32_t*)(ws + L.o_tau0), clear, 0, s);
+  // zero thresholds for the routing pass; of the score histograms only the resident row is used here
+  hipError_t err = launch_fill_i32((int32_t*)(ws + L.o_tau0), (int64_t)L.E * L.P, 0, s);
+  if (err == hipSuccess)
+    err = launch_fill_i32((int32_t*)(ws + L.o_sel) + (int64_t)L.E * (kSelBins + 2), kSelBins + 2, 0, s);
   if (err == hipSuccess && T > 0)
     err = launch_route(L, logits, T, (const float*)(ws + L.o_tau0), (int32_t*)(ws + L.o_idx), (float*)(ws + L.o_w),
                        (uint8_t*)(ws + L.o_keep), nullptr, nullptr, s, true);
