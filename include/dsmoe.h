@@ -79,7 +79,8 @@ const char* dsmoe_strerror(int status);
 /* hipError_t value of the last failed HIP call on this context (0 if none). */
 int dsmoe_last_hip_error(const dsmoe_ctx* ctx);
 /* 1 if this context runs the bf16 MFMA kernels, 0 if it runs the generic fp32-accumulate kernels
- * (fp32 layers, or bf16 layers whose D, F/P or shared width is not a multiple of 32). */
+ * (fp32 layers, bf16 layers whose D, F/P or shared width is not a multiple of 32, or contexts whose
+ * max_tokens * D * 2 bytes of activations reach 2 GiB: split such batches). */
 int dsmoe_uses_mfma(const dsmoe_ctx* ctx);
 
 /*
