@@ -220,3 +220,14 @@ def test_later_entry_points_validate_before_touching_the_gpu(lib):
     lib.dsmoe_destroy.argtypes = [vp]
     lib.dsmoe_destroy(ctx)
     lib.dsmoe_destroy(c2)
+
+
+def test_build_script_is_importable_without_the_library():
+    """A fresh tree has no libdsmoe.so: importing the package or its build script must not need it
+    (only the first use of the binding does, and that fails loudly)."""
+    import subprocess
+    import sys
+    code = ("import sys, paper_2508_18376_amd, paper_2508_18376_amd.build, paper_2508_18376_amd.thresholds; "
+            "assert 'paper_2508_18376_amd.binding' not in sys.modules; print('ok')")
+    out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
