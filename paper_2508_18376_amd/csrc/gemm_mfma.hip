@@ -34,6 +34,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 constexpr int kStages = 4;                          // LDS ring depth
 constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
 constexpr int kLdsBytes = kStages * kStagePair;     // 128 KiB
+constexpr int64_t kStreamOutBytes = 192ll << 20;    // GEMM-2 outputs larger than this bypass the caches (256 MiB of last-level cache, shared with H)
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
 constexpr int kRowBytes = kBK * 2;                  // one tile row in LDS: 64 bytes
@@ -101,7 +102,7 @@ struct Frags {
 // DMA loads.  With one wavefront per SIMD nothing else hides an instruction that stalls the
 // stream, so the reads and loads are threaded between the MFMAs by hand and pinned with
 // scheduling barriers.
-template <int I, int J, int NI, int NJ, int NLOADS>
+template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false>
 struct WaveTile {
   static_assert(I * J == 16, "256 accumulator registers");
   static_assert(NLOADS >= 1 && NLOADS <= kLoadsPerStage, "DMA loads per thread and stage");
@@ -155,7 +156,9 @@ struct WaveTile {
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
       const int i = m / J, j = m % J;
-      if (act_i(i) && act_j(j)) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      if (act_i(i) && act_j(j))
+        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j], cur.a[i], acc[i][j], 0, 0, 0)
+                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
       if (DMA && (m & 1) && (m >> 1) < NLOADS) one(m >> 1);
       if (READS) {
 #pragma unroll
@@ -359,11 +362,11 @@ struct G2Args {
 };
 
 // MFMA A = pair rows of H, B = output columns of W2.
-template <int I, int J, int NI>
+template <int I, int J, int NI, bool NT>
 __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
   asm volatile("" : "+v"(tid));  // see gemm1_tile
   const int lane = tid & 63;
-  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage)> t;
+  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage), true> t;
   t.init(a_row0, b_row0, lane);
   // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
   // begin() is called with increasing st, so a running cursor maps st -> K position.
@@ -387,24 +390,54 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   };
   t.mainloop(g.nstages, begin, one, lds);
 
-  // epilogue: acc[i][j][v]: pair row a_row0 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, column b_row0 + j*32 + lane%32
+  // epilogue.  The weight fragment is the MFMA's A operand, so acc[i][j][v] is pair row
+  // a_row0 + i*32 + lane%32, column b_row0 + j*32 + 8*(v/4) + 4*(lane/32) + v%4.  Each wavefront
+  // turns one block of 32 rows at a time around in its own quarter of the (now idle) ring and
+  // writes it out as whole row segments of J*128 bytes, 16 bytes per lane.
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  constexpr int kYsRow = J * 128 + 16;           // bytes; the pad spreads the rows over the banks
+  constexpr int kLanesRow = J * 8;               // lanes that share a row in the write-out
+  constexpr int kRowsPass = 64 / kLanesRow;      // rows per store instruction
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  char* mine = lds + w * (kLdsBytes / 4);
+  block_barrier();  // every wave is done reading the last stage
+  const int cw = g.it.jd * kMfmaBN2 + b_row0 + (lane % kLanesRow) * 4;  // first of this lane's 4 columns in the write-out
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int r = a_row0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-      if (r >= g.it.nrows) continue;
-      float* yrow = g.Y + (size_t)r * g.ldy;
+    for (int j = 0; j < J; ++j)
 #pragma unroll
-      for (int j = 0; j < J; ++j) {
-        const int c = b_row0 + j * 32 + (lane & 31);
-        if (g.it.jd * kMfmaBN2 + c < g.D) yrow[c] = t.acc[i][j][v];
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4_t o;
+        o.x = t.acc[i][j][vq * 4 + 0];
+        o.y = t.acc[i][j][vq * 4 + 1];
+        o.z = t.acc[i][j][vq * 4 + 2];
+        o.w = t.acc[i][j][vq * 4 + 3];
+        *(f32x4_t*)(mine + (lane & 31) * kYsRow + (j * 32 + vq * 8 + (lane >> 5) * 4) * 4) = o;
+      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int k = 0; k < 32 / kRowsPass; ++k) {
+      const int rl = k * kRowsPass + lane / kLanesRow;
+      const int r = a_row0 + i * 32 + rl;
+      const f32x4_t o = *(const f32x4_t*)(mine + rl * kYsRow + (lane % kLanesRow) * 16);
+      if (r < g.it.nrows && cw < g.D) {
+        f32x4_t* dst = (f32x4_t*)(g.Y + (size_t)r * g.ldy + b_row0 + (lane % kLanesRow) * 4);
+        if (NT) __builtin_nontemporal_store(o, dst);
+        else *dst = o;
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_sched_barrier(0);
   }
 }
 
+// NT: the output leaves with non-temporal stores (for outputs far larger than the caches: the
+// combine step reads them from HBM anyway, and the weight and activation tiles keep their place in L2)
+template <bool NT>
 __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const char* packed, char* ws) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
@@ -447,17 +480,17 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   for (int p = 0; p < g.np; ++p) g.nstages += ((g.it.kmask >> p) & 1) ? g.it.ks_n : 0;
 
   if (g.it.nrows == kMfmaBM) {
-    gemm2_tile<4, 4, 4>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
+    gemm2_tile<4, 4, 4, NT>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
   } else {  // 1 x 4: the ceil(nrows/32) blocks of pair rows that exist x 64 columns
     switch ((g.it.nrows + 31) >> 5) {
-      case 1: gemm2_tile<8, 2, 1>(g, lds, 0, w * 64, tid); break;
-      case 2: gemm2_tile<8, 2, 2>(g, lds, 0, w * 64, tid); break;
-      case 3: gemm2_tile<8, 2, 3>(g, lds, 0, w * 64, tid); break;
-      case 4: gemm2_tile<8, 2, 4>(g, lds, 0, w * 64, tid); break;
-      case 5: gemm2_tile<8, 2, 5>(g, lds, 0, w * 64, tid); break;
-      case 6: gemm2_tile<8, 2, 6>(g, lds, 0, w * 64, tid); break;
-      case 7: gemm2_tile<8, 2, 7>(g, lds, 0, w * 64, tid); break;
-      default: gemm2_tile<8, 2, 8>(g, lds, 0, w * 64, tid); break;
+      case 1: gemm2_tile<8, 2, 1, NT>(g, lds, 0, w * 64, tid); break;
+      case 2: gemm2_tile<8, 2, 2, NT>(g, lds, 0, w * 64, tid); break;
+      case 3: gemm2_tile<8, 2, 3, NT>(g, lds, 0, w * 64, tid); break;
+      case 4: gemm2_tile<8, 2, 4, NT>(g, lds, 0, w * 64, tid); break;
+      case 5: gemm2_tile<8, 2, 5, NT>(g, lds, 0, w * 64, tid); break;
+      case 6: gemm2_tile<8, 2, 6, NT>(g, lds, 0, w * 64, tid); break;
+      case 7: gemm2_tile<8, 2, 7, NT>(g, lds, 0, w * 64, tid); break;
+      default: gemm2_tile<8, 2, 8, NT>(g, lds, 0, w * 64, tid); break;
     }
   }
 }
@@ -469,7 +502,9 @@ static hipError_t set_lds_attr() {
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
   attr_set = true;
   return hipSuccess;
@@ -491,7 +526,10 @@ hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* w
   hipError_t e = set_lds_attr();
   if (e != hipSuccess) return e;
   const int g2 = (items2_bound(L, T) + 255) & ~255;
-  gemm2_mfma_kernel<<<dim3(g2), dim3(256), kLdsBytes, s>>>(L, T, packed, ws);
+  // per-pair outputs of this batch, at most; beyond the size of the last-level cache they stream
+  const int64_t out_bytes = (int64_t)T * (L.K + (L.n_shared > 0 ? 1 : 0)) * L.D * 4;
+  if (out_bytes > kStreamOutBytes) gemm2_mfma_kernel<true><<<dim3(g2), dim3(256), kLdsBytes, s>>>(L, T, packed, ws);
+  else gemm2_mfma_kernel<false><<<dim3(g2), dim3(256), kLdsBytes, s>>>(L, T, packed, ws);
   return hipGetLastError();
 }
 
