@@ -88,23 +88,24 @@ struct Frags {
 };
 
 // One wavefront's share of the tile product.
-//   I x J   MFMA blocks (32 x 32) of this wavefront; I * J == 16.
+//   I x J   MFMA blocks (32 x 32) of this wavefront; I * J == 16, or 8 for a tile of half the weight rows.
 //   NI / NJ: only the first NI (NJ) blocks of that dimension hold rows (ragged tile); the others
 //   are neither read nor multiplied.  They are template parameters, not run-time values: branches
 //   around single MFMAs would push the accumulators out of their registers.
 // The main loop below is shared by both GEMMs:
 //   begin(st): fix the ring slot and the K offsets of stage st (called once per stage, in order);
-//   one(q):    enqueue this thread's q-th DMA load (0..NLOADS-1) of the stage begun last; loads 0..3
-//              bring the weight tile, load 4+g brings pair rows 64g .. 64g+63 (only those that exist).
+//   one(q):    enqueue this thread's q-th DMA load (0..NLOADS-1) of the stage begun last: first the
+//              loads of the weight tile (4; 2 for half a tile), then one per 64 pair rows that exist.
 // On return every DMA has completed and acc holds the tile.
 //
-// Per stage a wavefront issues 32 MFMAs (1024 matrix-core cycles), I+J LDS reads per substep and 8
-// DMA loads.  With one wavefront per SIMD nothing else hides an instruction that stalls the
-// stream, so the reads and loads are threaded between the MFMAs by hand and pinned with
-// scheduling barriers.
+// Per stage a wavefront issues 32 MFMAs (1024 matrix-core cycles; half of that when I * J == 8),
+// I+J LDS reads per substep and up to 8 DMA loads.  With one wavefront per SIMD nothing else hides
+// an instruction that stalls the stream, so the reads and loads are threaded between the MFMAs by
+// hand and pinned with scheduling barriers.
 template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false>
 struct WaveTile {
-  static_assert(I * J == 16, "256 accumulator registers");
+  static_assert(I * J == 16 || I * J == 8, "256 or 128 accumulator registers");
+  static constexpr int M = I * J;  // MFMAs per K substep
   static_assert(NLOADS >= 1 && NLOADS <= kLoadsPerStage, "DMA loads per thread and stage");
   f32x16 acc[I][J];
   uint32_t offA, offB;  // byte offset of this lane's row in the A / B tile of a stage (block 0)
@@ -154,15 +155,19 @@ struct WaveTile {
                                             One&& one) {
     constexpr int R = I + J;
 #pragma unroll
-    for (int m = 0; m < 16; ++m) {
+    for (int m = 0; m < M; ++m) {
       const int i = m / J, j = m % J;
       if (act_i(i) && act_j(j))
         acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j], cur.a[i], acc[i][j], 0, 0, 0)
                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
-      if (DMA && (m & 1) && (m >> 1) < NLOADS) one(m >> 1);
+      if (M == 16) {  // a DMA slot after every second MFMA, or after every one of 8
+        if (DMA && (m & 1) && (m >> 1) < NLOADS) one(m >> 1);
+      } else {
+        if (DMA && m < NLOADS) one(m);
+      }
       if (READS) {
 #pragma unroll
-        for (int k = (m * R) / 16; k < ((m + 1) * R) / 16; ++k) read_k(nxt, nxt_stage, nxt_c, k);
+        for (int k = (m * R) / M; k < ((m + 1) * R) / M; ++k) read_k(nxt, nxt_stage, nxt_c, k);
       }
       if (m & 1) __builtin_amdgcn_sched_barrier(0);
     }
@@ -231,7 +236,7 @@ struct G1Args {
 
 // MFMA A = weight rows, B = pair rows.  Weight rows come in blocks of 32: block 2b is the gate
 // projection of neurons 32b .. 32b+31 of the tile, block 2b+1 their up projection.
-template <int I, int J, int NJ, bool PROFILE>
+template <int I, int J, int NJ, bool PROFILE, int NW = 4>
 __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int tid) {
   // Each instantiation derives its lane-dependent offsets from its own opaque copy of the thread
   // id: shared, they would stay live across all the instantiations of the kernel and be parked in
@@ -239,7 +244,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   // the ragged layout (J == 8) walks all pair rows: only the 64-row groups that exist are loaded
-  WaveTile<I, J, I, NJ, (J == 8 ? 4 + (NJ * 32 + 63) / 64 : kLoadsPerStage)> t;
+  WaveTile<I, J, I, NJ, (J == 8 ? 4 + (NJ * 32 + 63) / 64 : NW + 4)> t;
   t.init(a_row0, b_row0, lane);
   uint32_t slot = 0, sW = 0, sX = 0;
   auto begin = [&](int st) {
@@ -248,8 +253,8 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     sX = (uint32_t)(st * kRowBytes);
   };
   auto one = [&](int q) {
-    if (q < 4) dma16(g.rsW, slot + q * 4096, g.woff, sW + q * 4096);
-    else dma16(g.rsX, slot + kStageBytes + (q - 4) * 4096, g.xoff[q - 4], sX);
+    if (q < NW) dma16(g.rsW, slot + q * 4096, g.woff, sW + q * 4096);
+    else dma16(g.rsX, slot + kStageBytes + (q - NW) * 4096, g.xoff[q - NW], sX);
   };
   t.mainloop(g.KS1, begin, one, lds);
 
@@ -336,7 +341,10 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
 
   if (g.it.nrows == kMfmaBM) {
-    gemm1_tile<4, 4, 4, PROFILE>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts, 128 x 128 each
+    // 2 x 2 wavefronts, 128 weight rows x 128 pair rows each; a last neuron tile that is at most half
+    // full takes the first 128 weight rows only (64 x 128 per wavefront)
+    if (g.Fp - g.it.jt * kMfmaNeur <= kMfmaNeur / 2) gemm1_tile<2, 4, 4, PROFILE, 2>(g, lds, (w >> 1) * 64, (w & 1) * 128, tid);
+    else gemm1_tile<4, 4, 4, PROFILE>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);
   } else {  // 4 x 1: 64 weight rows x the ceil(nrows/32) blocks of pair rows that exist
     switch ((g.it.nrows + 31) >> 5) {
       case 1: gemm1_tile<2, 8, 1, PROFILE>(g, lds, w * 64, 0, tid); break;
