@@ -104,6 +104,9 @@ BF16_CASES = [
     ("half_drop_P4", spec_of(T=900, D=128, F=512, E=4, K=2, P=4, seed=9), "rate0.5", True),
     ("fine_grained", spec_of(T=600, D=128, F=128, E=16, K=4, P=2, seed=10), "rate0.25", True),
     ("Fp_704_like", spec_of(T=400, D=128, F=384, E=4, K=2, P=2, seed=11), "rate0.33", True),  # Fp=192: half-empty neuron tile
+    # full row tiles under a last neuron tile that is half full (Fp = 192) or a quarter full (Fp = 160)
+    ("half_neuron_tile", spec_of(T=1400, D=128, F=384, E=4, K=2, P=2, seed=24), "rate0.25", True),
+    ("quarter_neuron_tile", spec_of(T=1200, D=192, F=320, E=4, K=2, P=2, seed=25), 0.0, True),
     ("shared", spec_of(T=500, D=128, F=256, E=8, K=2, P=2, n_shared=2, F_sh=192, seed=12), "rate0.33", True),
     ("window", spec_of(T=800, D=128, F=256, E=8, K=2, P=4, resident=(1, 3), seed=13), "rate0.25", True),
     ("general_masks", spec_of(T=700, D=128, F=512, E=4, K=3, P=4, seed=14), "ragged", True),
