@@ -68,7 +68,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   const int rt = routed_tiles_bound(L, Tm);
   L.row_cap = L.sh_rows + rt * L.BM;
   L.max_tiles = rt + shared_tiles(L, Tm);
-  L.max_items1 = rt * L.P * L.NT1 + shared_tiles(L, Tm) * L.NT1_sh;
+  L.max_items1 = items1_whole_bound(L, Tm) + L.split_items / 2;  // a smaller batch may cut its last items in two
   L.max_items2 = L.max_tiles * L.ND2 + (L.split_items > 0 ? kPoolTiles : 0);
 
   int64_t o = 0;
@@ -96,14 +96,18 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_items2 = take((int64_t)L.max_items2 * sizeof(Item2));
   L.o_row_token = take((int64_t)L.row_cap * 4);
   L.o_row_bits = take((int64_t)L.row_cap);
-  L.o_H = take((int64_t)(L.row_cap - L.sh_rows) * L.F * elem);
-  L.o_Hs = take((int64_t)L.sh_rows * L.F_shT * elem);
-  L.o_Yp = take((int64_t)L.row_cap * L.D * 4);
+  auto take_big = [&](int64_t bytes) {  // the large arrays start on 2 MiB boundaries
+    o = align_up(o, 2 << 20);
+    return take(bytes);
+  };
+  L.o_H = take_big((int64_t)(L.row_cap - L.sh_rows) * L.F * elem);
+  L.o_Hs = take_big((int64_t)L.sh_rows * L.F_shT * elem);
+  L.o_Yp = take_big((int64_t)L.row_cap * L.D * 4);
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
   L.o_sel = take((int64_t)(L.E + 1) * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both; row E: resident pairs
   L.o_logits = take((int64_t)Tm * L.E * 4);
   L.o_perm_check = take(((int64_t)L.E_res * L.F + 1) * 4);
-  L.o_pool = take(L.split_items > 0 ? (int64_t)kPoolTiles * kMfmaBM * kMfmaBN2 * 4 : 0);  // partial outputs of split K ranges
+  L.o_pool = take_big(L.split_items > 0 ? (int64_t)kPoolTiles * kMfmaBM * kMfmaBN2 * 4 : 0);  // partial outputs of split K ranges
   L.o_split_of = take(L.split_items > 0 ? (int64_t)L.max_tiles * L.ND2 * 4 : 0);          // (row tile, column tile) -> first pool tile, or -1
   L.ws_bytes = o;
 

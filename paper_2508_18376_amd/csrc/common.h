@@ -39,7 +39,8 @@ constexpr int kGenBN = 64;
 struct Item1 {  // one tile of GEMM-1: rows [row0, row0+nrows) x neurons tile jt of partition p
   int32_t row0, nrows, e, p, jt;
   int32_t nfill;  // rows of the whole row tile (>= nrows): rows [nrows, nfill) keep nothing of p and get zeros
-  int32_t pad1, pad2;
+  int32_t half;   // 0: the whole neuron tile; 1 / 2: its first / second 64 neurons (MFMA path, at most 128 rows)
+  int32_t pad;
 };
 struct Item2 {  // one tile of GEMM-2: rows x output column tile jd, summed over partitions in kmask
   int32_t row0, nrows, e, jd, kmask;
@@ -95,8 +96,15 @@ struct Ctx {
 // upper bounds of the plan sizes for a call with T tokens (the exact sizes only exist on the device)
 inline int routed_tiles_bound(const Layout& L, int T) { return (int)(((int64_t)T * L.K) / L.BM) + L.E_res; }
 inline int shared_tiles(const Layout& L, int T) { return L.n_shared > 0 ? (T + L.BM - 1) / L.BM : 0; }
-inline int items1_bound(const Layout& L, int T) {
+inline int items1_whole_bound(const Layout& L, int T) {
   return routed_tiles_bound(L, T) * L.P * L.NT1 + shared_tiles(L, T) * L.NT1_sh;
+}
+// A last round of items is cut into halves only if no expert has more than half a tile of rows.
+__host__ __device__ inline bool may_halve_items1(const Layout& L, int T) {
+  return L.split_items > 0 && (int64_t)T * L.K <= (int64_t)L.E_res * (L.BM / 2) && (L.n_shared == 0 || T <= L.BM / 2);
+}
+inline int items1_bound(const Layout& L, int T) {
+  return items1_whole_bound(L, T) + (may_halve_items1(L, T) ? L.split_items / 2 : 0);
 }
 inline int items2_bound(const Layout& L, int T) {
   const int whole = (routed_tiles_bound(L, T) + shared_tiles(L, T)) * L.ND2;

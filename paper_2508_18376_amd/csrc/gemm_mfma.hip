@@ -34,6 +34,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 constexpr int kStages = 4;                          // LDS ring depth
 constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
 constexpr int kLdsBytes = kStages * kStagePair;     // 128 KiB
+constexpr int kHalfStages = 8;                      // ring of the half-tile items of GEMM-1
+constexpr int kHalfStride = kStageBytes;            // 8 KiB of weights + 8 KiB of rows
+static_assert(kHalfStages * kHalfStride <= kLdsBytes, "same allocation");
 constexpr int64_t kStreamOutBytes = 192ll << 20;    // GEMM-2 outputs larger than this bypass the caches (256 MiB of last-level cache, shared with H)
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
@@ -102,7 +105,7 @@ struct Frags {
 // I+J LDS reads per substep and up to 8 DMA loads.  With one wavefront per SIMD nothing else hides
 // an instruction that stalls the stream, so the reads and loads are threaded between the MFMAs by
 // hand and pinned with scheduling barriers.
-template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false>
+template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false, int NS = kStages, int SB = kStagePair, int BOFF = kStageBytes>
 struct WaveTile {
   static_assert(I * J == 16 || I * J == 8, "256 or 128 accumulator registers");
   static constexpr int M = I * J;  // MFMAs per K substep
@@ -115,7 +118,7 @@ struct WaveTile {
     const int r32 = lane & 31, half = lane >> 5;
     const int sw = (r32 >> 2) & 3;
     offA = (uint32_t)(a_row0 + r32) * kRowBytes;
-    offB = (uint32_t)(b_row0 + r32) * kRowBytes + kStageBytes;
+    offB = (uint32_t)(b_row0 + r32) * kRowBytes + BOFF;
     c0 = (uint32_t)((half ^ sw) * 16);
     c1 = (uint32_t)(((2 + half) ^ sw) * 16);
 #pragma unroll
@@ -173,8 +176,25 @@ struct WaveTile {
     }
   }
 
+  // s_waitcnt takes an immediate: all but the last k stages' loads of this thread have landed
+  static __device__ __forceinline__ void wait_stages(int k) {
+    static_assert((NS - 2) * NLOADS < 64, "vmcnt is a 6-bit counter");
+    switch (k) {
+      case 0: wait_vm<0>(); break;
+      case 1: wait_vm<NLOADS>(); break;
+      case 2: wait_vm<(NS > 3 ? 2 : 0) * NLOADS>(); break;
+      case 3: wait_vm<(NS > 4 ? 3 : 0) * NLOADS>(); break;
+      case 4: wait_vm<(NS > 5 ? 4 : 0) * NLOADS>(); break;
+      case 5: wait_vm<(NS > 6 ? 5 : 0) * NLOADS>(); break;
+      default: wait_vm<(NS > 7 ? 6 : 0) * NLOADS>(); break;
+    }
+  }
+
+  // Ring of NS stages, SB bytes apart; stage st + NS - 1 is enqueued while stage st is multiplied.
   template <class Begin, class One>
   __device__ __forceinline__ void mainloop(int n, Begin&& begin, One&& one, const char* lds) {
+    static_assert(NS >= 3 && NS <= 8, "ring depth");
+    constexpr int PD = NS - 1;  // prefetch distance
     Frags<I, J> f0, f1;
     if (n <= 0) return;
     auto issue_all = [&](int st) {
@@ -182,12 +202,10 @@ struct WaveTile {
 #pragma unroll
       for (int q = 0; q < NLOADS; ++q) one(q);
     };
-    issue_all(0);
-    if (n > 1) issue_all(1);
-    if (n > 2) issue_all(2);
-    if (n > 2) wait_vm<2 * NLOADS>();
-    else if (n > 1) wait_vm<NLOADS>();
-    else wait_vm<0>();
+#pragma unroll
+    for (int s = 0; s < PD; ++s)
+      if (s < n) issue_all(s);
+    wait_stages((n < PD ? n : PD) - 1);
     block_barrier();
     read_all(f0, lds, c0);
     // c1 is first needed inside the loop; if the register allocator parked it in scratch, make it
@@ -195,29 +213,28 @@ struct WaveTile {
     // and drains the DMA queue every iteration
     asm volatile("" ::"v"(c1), "v"(offA), "v"(offB));
     int st = 0;
-    for (; st + 3 < n; ++st) {
-      const char* cur = lds + (st % kStages) * kStagePair;
+    for (; st + PD < n; ++st) {
+      const char* cur = lds + (st % NS) * SB;
       // first half: multiply substep 0 while the substep 1 operands stream in from LDS
       half_stage<true, false>(f0, f1, cur, c1, one);
-      // stage st+1 must have landed for every wave (st+2 may still be in flight); after the barrier
-      // every wave has also finished reading stage st-1, whose slot stage st+3 takes
-      wait_vm<NLOADS>();
+      // stage st+1 must have landed for every wave (the later ones may still be in flight); after
+      // the barrier every wave has also finished reading stage st-1, whose slot stage st+PD takes
+      wait_vm<(PD - 2) * NLOADS>();
       block_barrier();
-      begin(st + 3);
-      // second half: multiply substep 1; between the MFMAs enqueue stage st+3 and fetch substep 0 of stage st+1
-      const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
+      begin(st + PD);
+      // second half: multiply substep 1; between the MFMAs enqueue stage st+PD and fetch substep 0 of stage st+1
+      const char* nxt = lds + ((st + 1) % NS) * SB;
       half_stage<true, true>(f1, f0, nxt, c0, one);
     }
     for (; st + 1 < n; ++st) {  // last stages: nothing left to enqueue
-      const char* cur = lds + (st % kStages) * kStagePair;
+      const char* cur = lds + (st % NS) * SB;
       half_stage<true, false>(f0, f1, cur, c1, one);
-      if (st + 2 < n) wait_vm<NLOADS>();
-      else wait_vm<0>();
+      wait_stages(n - 2 - st);
       block_barrier();
-      const char* nxt = lds + ((st + 1) % kStages) * kStagePair;
+      const char* nxt = lds + ((st + 1) % NS) * SB;
       half_stage<true, false>(f1, f0, nxt, c0, one);
     }
-    const char* last = lds + ((n - 1) % kStages) * kStagePair;
+    const char* last = lds + ((n - 1) % NS) * SB;
     half_stage<true, false>(f0, f1, last, c1, one);
     half_stage<false, false>(f1, f0, last, c0, one);
   }
@@ -236,7 +253,7 @@ struct G1Args {
 
 // MFMA A = weight rows, B = pair rows.  Weight rows come in blocks of 32: block 2b is the gate
 // projection of neurons 32b .. 32b+31 of the tile, block 2b+1 their up projection.
-template <int I, int J, int NJ, bool PROFILE, int NW = 4>
+template <int I, int J, int NJ, bool PROFILE, int NW = 4, bool HALF = false>
 __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int tid) {
   // Each instantiation derives its lane-dependent offsets from its own opaque copy of the thread
   // id: shared, they would stay live across all the instantiations of the kernel and be parked in
@@ -244,17 +261,22 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   // the ragged layout (J == 8) walks all pair rows: only the 64-row groups that exist are loaded
-  WaveTile<I, J, I, NJ, (J == 8 ? 4 + (NJ * 32 + 63) / 64 : NW + 4)> t;
+  // HALF: one half (64 neurons) of a neuron tile under at most 128 pair rows, in the streaming
+  // regime: stages of 8 KiB of weights + 8 KiB of rows in a ring of 8, so that as many bytes are in
+  // flight as with whole tiles; wavefronts 2 and 3 only help to load (NJ == 0).
+  constexpr int NS = HALF ? kHalfStages : kStages, SB = HALF ? kHalfStride : kStagePair, BOFF = HALF ? kHalfStride / 2 : kStageBytes;
+  const int half = HALF ? g.it.half - 1 : 0;
+  WaveTile<I, J, I, NJ, (HALF ? 4 : J == 8 ? 4 + (NJ * 32 + 63) / 64 : NW + 4), false, NS, SB, BOFF> t;
   t.init(a_row0, b_row0, lane);
   uint32_t slot = 0, sW = 0, sX = 0;
   auto begin = [&](int st) {
-    slot = (uint32_t)(st % kStages) * kStagePair + g.lds_w;
-    sW = (uint32_t)(st * kStageBytes);
+    slot = (uint32_t)(st % NS) * SB + g.lds_w;
+    sW = (uint32_t)(st * kStageBytes + half * (kStageBytes / 2));
     sX = (uint32_t)(st * kRowBytes);
   };
   auto one = [&](int q) {
     if (q < NW) dma16(g.rsW, slot + q * 4096, g.woff, sW + q * 4096);
-    else dma16(g.rsX, slot + kStageBytes + (q - NW) * 4096, g.xoff[q - NW], sX);
+    else dma16(g.rsX, slot + BOFF + (q - NW) * 4096, g.xoff[q - NW], sX);
   };
   t.mainloop(g.KS1, begin, one, lds);
 
@@ -270,7 +292,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
 #pragma unroll
     for (int i = 0; i < I; i += 2) {
-      const int nb = (a_row0 >> 5) + i;  // weight block index; neurons of the tile: (nb/2)*32 ..
+      const int nb = (a_row0 >> 5) + i + 4 * half;  // weight block index; neurons of the tile: (nb/2)*32 ..
       char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (lane >> 5) * 4) * 2;
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
@@ -292,7 +314,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   }
   __syncthreads();
   const int n_in = g.it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
-  if (n_in < g.Fp) {
+  if (n_in < g.Fp && (!HALF || ((tid & 15) >> 3) == half)) {
 #pragma unroll 4
     for (int c = 0; c < 16; ++c) {
       const int r = c * 16 + (tid >> 4);
@@ -340,7 +362,18 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   g.woff = (uint32_t)tid * 16;
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
 
-  if (g.it.nrows == kMfmaBM) {
+  if (g.it.half) {  // at most 128 rows (the plan guarantees it): wavefronts 0 and 1 multiply, 64 weight rows each
+    if (w < 2) {
+      switch ((g.it.nrows + 31) >> 5) {
+        case 1: gemm1_tile<2, 4, 1, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
+        case 2: gemm1_tile<2, 4, 2, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
+        case 3: gemm1_tile<2, 4, 3, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
+        default: gemm1_tile<2, 4, 4, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
+      }
+    } else {
+      gemm1_tile<2, 4, 0, PROFILE, 2, true>(g, lds, 0, 0, tid);
+    }
+  } else if (g.it.nrows == kMfmaBM) {
     // 2 x 2 wavefronts, 128 weight rows x 128 pair rows each; a last neuron tile that is at most half
     // full takes the first 128 weight rows only (64 x 128 per wavefront)
     if (g.Fp - g.it.jt * kMfmaNeur <= kMfmaNeur / 2) gemm1_tile<2, 4, 4, PROFILE, 2>(g, lds, (w >> 1) * 64, (w & 1) * 128, tid);

@@ -416,6 +416,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // 1. rows per expert.  Order of the experts in the row space: the shared pseudo-expert first
   //    (its size is known without the histogram), then the resident experts by id.
   //    position i -> expert: with shared experts, position 0 is id E_res and position i is id i-1.
+  __shared__ int wave_big[kPlanThreads / 64];  // per wavefront: one of its experts has more than half a tile of rows
+  bool big = false;
   for (int e = tid; e < E_tot; e += kPlanThreads) {
     int n = 0;
     if (e < E_res)
@@ -423,6 +425,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     else
       n = T;
     ne[e] = n;
+    big = big || n > BM / 2;
+  }
+  {
+    const unsigned long long any = __ballot(big);
+    if ((tid & 63) == 0) wave_big[tid >> 6] = any != 0;
   }
   __syncthreads();
   // 2. tile-aligned row starts: exclusive scan of the tile counts in position order
@@ -581,9 +588,28 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   __syncthreads();
   int total1 = block_excl_scan(gb, NG, tmp);
   // 7. GEMM-1 items in the order (expert, partition, neuron tile, row tile): the row tiles that
-  //    share one weight tile are adjacent.  One thread per (row tile, partition): it looks its
-  //    tile up once and writes the items of all neuron tiles.
-  for (int q = tid; q < total_tiles * L.P; q += kPlanThreads) {
+  //    share one weight tile are adjacent.  1 to 8 threads per (row tile, partition): each looks
+  //    the tile up and writes the items of every S-th neuron tile.
+  //    Batches so small that every item only streams its weights (no expert has more than 128
+  //    rows) take as long as their last round of items, one item per compute unit: when that
+  //    round is at most half full its items are cut into halves of 64 neurons, which fill it.
+  int first_half = total1;  // list positions >= first_half become two items each
+  {
+    auto halves_ok = [](int f) { return f % kMfmaNeur == 0 || f % kMfmaNeur > kMfmaNeur / 2; };
+    const int rest = L.split_items > 0 ? total1 % L.split_items : 0;
+    bool small = true;  // no expert has more than half a tile of rows
+    for (int w = 0; w < kPlanThreads / 64; ++w) small = small && !wave_big[w];
+    if (may_halve_items1(L, T) && small && halves_ok(L.Fp) && (!has_sh || halves_ok(L.F_shT)) && rest > 0 &&
+        rest * 2 <= L.split_items)
+      first_half = total1 - rest;
+  }
+  const int nt1_max = has_sh && L.NT1_sh > L.NT1 ? L.NT1_sh : L.NT1;
+  // threads that share the neuron tiles of one (row tile, partition): as many as would otherwise idle
+  int S = kPlanThreads / max(total_tiles * L.P, 1);
+  S = S < 1 ? 1 : S > 8 ? 8 : S;
+  S = S > nt1_max ? nt1_max : S;
+  for (int qs = tid; qs < total_tiles * L.P * S; qs += kPlanThreads) {
+    const int part = qs % S, q = qs / S;
     const int p = q % L.P, g = q / L.P;
     const int rk = act_rank[(size_t)g * L.P + p];
     if (rk < 0) continue;
@@ -597,15 +623,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     v.nrows = tile_rows_for(e, i, p);
     v.e = e;
     v.p = p;
-    v.pad1 = v.pad2 = 0;
-    Item1* dst = items1 + gb[gi] + rk;
-    for (int jt = 0; jt < nt1; ++jt) {
+    v.pad = 0;
+    for (int jt = part; jt < nt1; jt += S) {
       v.jt = jt;
-      dst[(size_t)jt * ga[gi]] = v;
+      const int pos = gb[gi] + jt * ga[gi] + rk;
+      if (pos < first_half) {
+        v.half = 0;
+        items1[pos] = v;
+      } else {
+        v.half = 1;
+        items1[first_half + 2 * (pos - first_half)] = v;
+        v.half = 2;
+        items1[first_half + 2 * (pos - first_half) + 1] = v;
+      }
     }
   }
   if (tid == 0) {
-    counters[0] = total1;
+    counters[0] = total1 + (total1 - first_half);
     counters[1] = first_split + (W2n - first_split) * nsplit;
     counters[2] = total_tiles;
     counters[3] = nsplit;

@@ -261,6 +261,45 @@ def test_gemm2_split_k_on_few_row_tiles(oracle, name, spec, tau_kind, nsplit):
         assert counters[1] == tiles_x_cols
 
 
+# ------------------------------------------------- decode-sized batches: GEMM-1 items cut into halves
+HALF_CASES = [
+    # name, spec, tau, whether the last round of items is expected to be cut in two
+    # 8 experts x 4 parts x 9 neuron tiles = 288 items: the 32 of the second round become 64
+    ("last_round_halved", spec_of(T=64, D=128, F=4608, E=8, K=2, P=4, seed=50), 0.0, True),
+    ("halved_under_drop", spec_of(T=48, D=128, F=4608, E=8, K=2, P=4, seed=51), "rate0.25", None),
+    ("halved_with_shared", spec_of(T=32, D=128, F=2048, E=8, K=2, P=2, n_shared=1, F_sh=512, seed=52), 0.0, None),
+    # 448 items: the second round is three quarters full and stays whole
+    ("last_round_too_full", spec_of(T=64, D=128, F=7168, E=8, K=2, P=4, seed=53), 0.0, False),
+    # an expert with more than half a tile of rows: not the streaming regime
+    ("too_many_rows", spec_of(T=300, D=128, F=4608, E=4, K=2, P=4, seed=54), 0.0, False),
+    # the last neuron tile of a partition has 64 neurons: nothing to cut
+    ("half_empty_neuron_tile", spec_of(T=64, D=128, F=768, E=16, K=2, P=4, seed=55), 0.0, False),
+]
+
+
+@pytest.mark.parametrize("name,spec,tau_kind,halved", HALF_CASES, ids=[c[0] for c in HALF_CASES])
+def test_gemm1_items_of_a_sparse_last_round_are_halved(oracle, name, spec, tau_kind, halved):
+    """At decode sizes every GEMM-1 item only streams its weight tile, so the step lasts as long
+    as its last round of 256 items: when that round is at most half full the plan cuts its items
+    into halves of 64 neurons.  Same result as the oracle either way; the item count shows the rule."""
+    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
+    counters = plan["counters"].cpu().numpy()
+    Fp = spec.F // spec.P
+    nt1 = (Fp + 127) // 128
+    active = int((r.group_count.reshape(spec.E, spec.P)[spec.lo:spec.hi] > 0).sum())  # sub-experts with a kept unit: one row tile each
+    whole = active * nt1 + (((spec.n_shared * spec.F_sh) + 127) // 128 if spec.n_shared else 0)
+    rows = np.bincount(r.idx.ravel(), minlength=spec.E)[spec.lo:spec.hi]
+    if rows.max() > 128 or (spec.n_shared and spec.T > 128):
+        assert not halved
+        return  # several row tiles per expert: the item count is not this simple, and nothing is cut
+    rest = whole % 256
+    ok_tiles = Fp % 128 == 0 or Fp % 128 > 64
+    expect_cut = 0 < rest <= 128 and ok_tiles
+    if halved is not None:
+        assert expect_cut == halved, (whole, rest)
+    assert counters[0] == whole + (rest if expect_cut else 0), (counters, whole, rest)
+
+
 @pytest.mark.parametrize("dtype,T", [("bf16", 16), ("bf16", 300), ("f32", 40)])
 def test_shared_experts_with_a_batch_smaller_than_max_tokens(oracle, dtype, T):
     """The routed rows start right after the shared experts' rows of THIS batch: a context sized
