@@ -24,6 +24,8 @@ CASES = [
     ("bf16_window", spec_of(T=600, E=8, resident=(2, 5), seed=33)),
     ("f32_generic", spec_of(dtype="f32", T=150, D=40, F=72, E=5, K=2, P=3, seed=34)),
     ("empty_expert", spec_of(T=3, E=16, K=2, seed=35)),
+    # 8 x 4 x 9 = 288 GEMM-1 items at a decode-sized batch: the items of the last round are cut into halves
+    ("halved_items", spec_of(T=64, D=128, F=4608, E=8, K=2, P=4, seed=37)),
 ]
 
 
