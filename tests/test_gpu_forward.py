@@ -267,7 +267,8 @@ HALF_CASES = [
     # 8 experts x 4 parts x 9 neuron tiles = 288 items: the 32 of the second round become 64
     ("last_round_halved", spec_of(T=64, D=128, F=4608, E=8, K=2, P=4, seed=50), 0.0, True),
     ("halved_under_drop", spec_of(T=48, D=128, F=4608, E=8, K=2, P=4, seed=51), "rate0.25", None),
-    ("halved_with_shared", spec_of(T=32, D=128, F=2048, E=8, K=2, P=2, n_shared=1, F_sh=512, seed=52), 0.0, None),
+    # 288 routed items + the 4 of the shared experts, which sit last in the list and are among those cut
+    ("halved_with_shared", spec_of(T=32, D=128, F=4608, E=8, K=2, P=4, n_shared=1, F_sh=512, seed=52), 0.0, True),
     # 448 items: the second round is three quarters full and stays whole
     ("last_round_too_full", spec_of(T=64, D=128, F=7168, E=8, K=2, P=4, seed=53), 0.0, False),
     # an expert with more than half a tile of rows: not the streaming regime
