@@ -23,6 +23,25 @@ def _needs_build() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+# The MFMA GEMM kernels use the whole register file (256 accumulators + 256 others per lane).  A
+# spill to scratch memory inside a main loop makes the loop wait for every outstanding load each
+# time round, and a small edit of the kernel is enough to cause one: the build refuses it.
+NO_SCRATCH = {"gemm_mfma.hip": ("gemm1_mfma_kernel", "gemm2_mfma_kernel")}
+
+
+def _scratch_users(remarks: str, kernels) -> list:
+    """Kernels among `kernels` whose 'ScratchSize [bytes/lane]' remark is not 0."""
+    bad, name = [], None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize [bytes/lane]:" in line and name is not None:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size != 0 and any(k in name for k in kernels):
+                bad.append("%s: %d bytes/lane" % (name, size))
+    return bad
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link the shared library.  Returns its path."""
     if not force and not _needs_build():
@@ -33,10 +52,16 @@ def build(force: bool = True, verbose: bool = False) -> str:
     def cc(src: str) -> str:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if src in NO_SCRATCH:
+            cmd.append("-Rpass-analysis=kernel-resource-usage")
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
-        if verbose and r.stderr.strip():
+        if src in NO_SCRATCH:
+            bad = _scratch_users(r.stderr, NO_SCRATCH[src])
+            if bad:
+                raise RuntimeError("%s: kernels that must not spill use scratch memory: %s" % (src, "; ".join(bad)))
+        elif verbose and r.stderr.strip():
             sys.stderr.write(r.stderr)
         return obj
 

@@ -99,9 +99,10 @@ inline int shared_tiles(const Layout& L, int T) { return L.n_shared > 0 ? (T + L
 inline int items1_whole_bound(const Layout& L, int T) {
   return routed_tiles_bound(L, T) * L.P * L.NT1 + shared_tiles(L, T) * L.NT1_sh;
 }
-// A last round of items is cut into halves only if no expert has more than half a tile of rows.
+// A last round of items may be cut into halves only in the weight-streaming regime: at most half a
+// tile of rows per expert on average.
 __host__ __device__ inline bool may_halve_items1(const Layout& L, int T) {
-  return L.split_items > 0 && (int64_t)T * L.K <= (int64_t)L.E_res * (L.BM / 2) && (L.n_shared == 0 || T <= L.BM / 2);
+  return L.split_items > 0 && (int64_t)T * L.K <= (int64_t)L.E_res * (L.BM / 2);
 }
 inline int items1_bound(const Layout& L, int T) {
   return items1_whole_bound(L, T) + (may_halve_items1(L, T) ? L.split_items / 2 : 0);

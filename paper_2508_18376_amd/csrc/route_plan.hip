@@ -416,8 +416,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // 1. rows per expert.  Order of the experts in the row space: the shared pseudo-expert first
   //    (its size is known without the histogram), then the resident experts by id.
   //    position i -> expert: with shared experts, position 0 is id E_res and position i is id i-1.
-  __shared__ int wave_big[kPlanThreads / 64];  // per wavefront: one of its experts has more than half a tile of rows
-  bool big = false;
   for (int e = tid; e < E_tot; e += kPlanThreads) {
     int n = 0;
     if (e < E_res)
@@ -425,11 +423,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     else
       n = T;
     ne[e] = n;
-    big = big || n > BM / 2;
-  }
-  {
-    const unsigned long long any = __ballot(big);
-    if ((tid & 63) == 0) wave_big[tid >> 6] = any != 0;
   }
   __syncthreads();
   // 2. tile-aligned row starts: exclusive scan of the tile counts in position order
@@ -590,18 +583,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // 7. GEMM-1 items in the order (expert, partition, neuron tile, row tile): the row tiles that
   //    share one weight tile are adjacent.  1 to 8 threads per (row tile, partition): each looks
   //    the tile up and writes the items of every S-th neuron tile.
-  //    Batches so small that every item only streams its weights (no expert has more than 128
-  //    rows) take as long as their last round of items, one item per compute unit: when that
-  //    round is at most half full its items are cut into halves of 64 neurons, which fill it.
-  int first_half = total1;  // list positions >= first_half become two items each
-  {
-    auto halves_ok = [](int f) { return f % kMfmaNeur == 0 || f % kMfmaNeur > kMfmaNeur / 2; };
-    const int rest = L.split_items > 0 ? total1 % L.split_items : 0;
-    bool small = true;  // no expert has more than half a tile of rows
-    for (int w = 0; w < kPlanThreads / 64; ++w) small = small && !wave_big[w];
-    if (may_halve_items1(L, T) && small && halves_ok(L.Fp) && (!has_sh || halves_ok(L.F_shT)) && rest > 0 &&
-        rest * 2 <= L.split_items)
-      first_half = total1 - rest;
+  //    In the weight-streaming regime (few rows per expert) every item lasts as long as its weight
+  //    tile takes to arrive, so the kernel lasts a whole number of rounds of one item per compute
+  //    unit: when the last round is at most half full, its items are cut into halves of 64
+  //    neurons, which fill it (an item of more than 128 rows, or of a last neuron tile of at most
+  //    64 neurons, stays whole).
+  int first_half = total1;  // list positions >= first_half belong to that last round
+  if (may_halve_items1(L, T)) {
+    const int rest = total1 % L.split_items;
+    if (rest > 0 && rest * 2 <= L.split_items) first_half = total1 - rest;
   }
   const int nt1_max = has_sh && L.NT1_sh > L.NT1 ? L.NT1_sh : L.NT1;
   // threads that share the neuron tiles of one (row tile, partition): as many as would otherwise idle
@@ -626,20 +616,51 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     v.pad = 0;
     for (int jt = part; jt < nt1; jt += S) {
       v.jt = jt;
-      const int pos = gb[gi] + jt * ga[gi] + rk;
-      if (pos < first_half) {
-        v.half = 0;
-        items1[pos] = v;
-      } else {
-        v.half = 1;
-        items1[first_half + 2 * (pos - first_half)] = v;
-        v.half = 2;
-        items1[first_half + 2 * (pos - first_half) + 1] = v;
-      }
+      // MFMA path, at most 128 rows, a last neuron tile of at most 64 neurons: the half-tile variant of
+      // the kernel takes it as a first half without a second one (half the weight bytes)
+      const int live = (e < E_res ? L.Fp : L.F_shT) - jt * kMfmaNeur;
+      v.half = L.split_items > 0 && v.nrows <= kMfmaBM / 2 && live <= kMfmaNeur / 2 ? 1 : 0;
+      items1[gb[gi] + jt * ga[gi] + rk] = v;
     }
   }
+  int total_slots = total1;
+  if (first_half < total1) {  // the same for every thread
+    // cut the items of the last round in two where that is possible (at most 128 rows, both halves
+    // of the neuron tile exist); the list stays dense: item i moves up by the cuts before it
+    __shared__ int slots_wave0, slots_all;
+    __syncthreads();  // the items above are written
+    const int rest = total1 - first_half;  // <= 128: wavefronts 0 and 1
+    Item1 mine;
+    int slots = 0;
+    if (tid < rest) {
+      mine = items1[first_half + tid];
+      const int live = (mine.e < E_res ? L.Fp : L.F_shT) - mine.jt * kMfmaNeur;
+      slots = mine.nrows <= kMfmaBM / 2 && live > kMfmaNeur / 2 ? 2 : 1;
+    }
+    int incl = slots;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o, 64);
+      if ((tid & 63) >= o) incl += up;
+    }
+    if (tid == 63) slots_wave0 = incl;
+    __syncthreads();  // and every item of the tail has been read before any is moved
+    if (tid < rest) {
+      const int at = first_half + incl - slots + (tid >= 64 ? slots_wave0 : 0);
+      if (slots == 2) {
+        mine.half = 1;
+        items1[at] = mine;
+        mine.half = 2;
+        items1[at + 1] = mine;
+      } else {
+        items1[at] = mine;
+      }
+      if (tid == rest - 1) slots_all = at + slots;
+    }
+    __syncthreads();
+    total_slots = slots_all;
+  }
   if (tid == 0) {
-    counters[0] = total1 + (total1 - first_half);
+    counters[0] = total_slots;
     counters[1] = first_split + (W2n - first_split) * nsplit;
     counters[2] = total_tiles;
     counters[3] = nsplit;

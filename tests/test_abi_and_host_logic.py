@@ -231,3 +231,22 @@ def test_build_script_is_importable_without_the_library():
             "assert 'paper_2508_18376_amd.binding' not in sys.modules; print('ok')")
     out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
     assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
+
+
+def test_build_refuses_register_spills_in_the_gemm_kernels():
+    """The build reads the compiler's resource remarks and fails when one of the MFMA GEMM kernels
+    uses scratch memory (a spill inside their main loops stalls the load queue): the parser that
+    decides it, on a remark text of the compiler's format."""
+    from paper_2508_18376_amd import build
+    remarks = "\n".join([
+        "a.hip:1:1: remark: Function Name: _ZN5dsmoe17gemm1_mfma_kernelILb0EEEvNS_6LayoutEi [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 20 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark: Function Name: _ZN5dsmoe17gemm2_mfma_kernelILb1EEEvNS_6LayoutEi [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark: Function Name: _ZN5dsmoe11some_helperEv [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 64 [-Rpass-analysis=kernel-resource-usage]",
+    ])
+    bad = build._scratch_users(remarks, build.NO_SCRATCH["gemm_mfma.hip"])
+    assert len(bad) == 1 and "gemm1_mfma_kernel" in bad[0] and "20" in bad[0]
+    assert build._scratch_users(remarks.replace(": 20 ", ": 0 "), build.NO_SCRATCH["gemm_mfma.hip"]) == []

@@ -263,18 +263,20 @@ def test_gemm2_split_k_on_few_row_tiles(oracle, name, spec, tau_kind, nsplit):
 
 # ------------------------------------------------- decode-sized batches: GEMM-1 items cut into halves
 HALF_CASES = [
-    # name, spec, tau, whether the last round of items is expected to be cut in two
+    # name, spec, tau, whether the last round of items is expected to get two slots per item
     # 8 experts x 4 parts x 9 neuron tiles = 288 items: the 32 of the second round become 64
     ("last_round_halved", spec_of(T=64, D=128, F=4608, E=8, K=2, P=4, seed=50), 0.0, True),
     ("halved_under_drop", spec_of(T=48, D=128, F=4608, E=8, K=2, P=4, seed=51), "rate0.25", None),
     # 288 routed items + the 4 of the shared experts, which sit last in the list and are among those cut
     ("halved_with_shared", spec_of(T=32, D=128, F=4608, E=8, K=2, P=4, n_shared=1, F_sh=512, seed=52), 0.0, True),
-    # 448 items: the second round is three quarters full and stays whole
+    # the shared experts' row tile has more than 128 rows: their items keep one slot and leave one empty
+    ("uncut_shared_items", spec_of(T=200, D=128, F=4480, E=32, K=2, P=1, n_shared=1, F_sh=512, seed=56), 0.0, True),
+    # 448 items: the second round is three quarters full and stays as it is
     ("last_round_too_full", spec_of(T=64, D=128, F=7168, E=8, K=2, P=4, seed=53), 0.0, False),
-    # an expert with more than half a tile of rows: not the streaming regime
+    # more than half a tile of rows per expert: not the streaming regime
     ("too_many_rows", spec_of(T=300, D=128, F=4608, E=4, K=2, P=4, seed=54), 0.0, False),
-    # the last neuron tile of a partition has 64 neurons: nothing to cut
-    ("half_empty_neuron_tile", spec_of(T=64, D=128, F=768, E=16, K=2, P=4, seed=55), 0.0, False),
+    # the last neuron tile of a partition has 64 neurons: it runs as a first half without a second one
+    ("half_empty_neuron_tile", spec_of(T=64, D=128, F=768, E=16, K=2, P=4, seed=55), 0.0, True),
 ]
 
 
@@ -282,23 +284,36 @@ HALF_CASES = [
 def test_gemm1_items_of_a_sparse_last_round_are_halved(oracle, name, spec, tau_kind, halved):
     """At decode sizes every GEMM-1 item only streams its weight tile, so the step lasts as long
     as its last round of 256 items: when that round is at most half full the plan cuts its items
-    into halves of 64 neurons.  Same result as the oracle either way; the item count shows the rule."""
+    into halves of 64 neurons (an item of more than 128 rows, or of a last neuron tile of at most
+    64 neurons, stays whole).  Same result as the oracle either way; the item count shows the rule."""
     y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
     counters = plan["counters"].cpu().numpy()
+    E_res = spec.hi - spec.lo
+    streaming = spec.T * spec.K <= E_res * 128
+    rows = np.bincount(r.idx.ravel(), minlength=spec.E)[spec.lo:spec.hi]
+    if rows.max() > 256 or (spec.n_shared and spec.T > 256):
+        assert not halved and not streaming
+        return  # several row tiles per expert: the item count is not this simple
     Fp = spec.F // spec.P
     nt1 = (Fp + 127) // 128
-    active = int((r.group_count.reshape(spec.E, spec.P)[spec.lo:spec.hi] > 0).sum())  # sub-experts with a kept unit: one row tile each
-    whole = active * nt1 + (((spec.n_shared * spec.F_sh) + 127) // 128 if spec.n_shared else 0)
-    rows = np.bincount(r.idx.ravel(), minlength=spec.E)[spec.lo:spec.hi]
-    if rows.max() > 128 or (spec.n_shared and spec.T > 128):
-        assert not halved
-        return  # several row tiles per expert: the item count is not this simple, and nothing is cut
+    act = r.group_count.reshape(spec.E, spec.P)[spec.lo:spec.hi] > 0  # sub-experts with a kept unit: one row tile each
+    # the list in its order (expert, partition, neuron tile), shared experts last: (rows, neurons of the tile)
+    items = [(rows[e], min(128, Fp - 128 * jt)) for e in range(E_res) for p in range(spec.P) if act[e, p] for jt in range(nt1)]
+    if spec.n_shared:
+        F_sh = spec.n_shared * spec.F_sh
+        items += [(spec.T, min(128, F_sh - 128 * jt)) for jt in range((F_sh + 127) // 128)]
+    whole = len(items)
     rest = whole % 256
-    ok_tiles = Fp % 128 == 0 or Fp % 128 > 64
-    expect_cut = 0 < rest <= 128 and ok_tiles
+    rule = streaming and 0 < rest <= 128
     if halved is not None:
-        assert expect_cut == halved, (whole, rest)
-    assert counters[0] == whole + (rest if expect_cut else 0), (counters, whole, rest)
+        assert rule == halved, (whole, rest)
+    if not rule:
+        assert counters[0] == whole, (counters, whole, rest)
+    elif tau_kind == 0.0:  # no drop: every row of an expert keeps every partition
+        cuts = sum(1 for n, live in items[whole - rest:] if n <= 128 and live > 64)
+        assert counters[0] == whole + cuts, (counters, whole, rest, cuts)
+    else:
+        assert whole <= counters[0] <= whole + rest, (counters, whole, rest)
 
 
 @pytest.mark.parametrize("dtype,T", [("bf16", 16), ("bf16", 300), ("f32", 40)])
