@@ -34,9 +34,15 @@ typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 constexpr int kStages = 4;                          // LDS ring depth
 constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
 constexpr int kLdsBytes = kStages * kStagePair;     // 128 KiB
-constexpr int kHalfStages = 8;                      // ring of the half-tile items of GEMM-1
-constexpr int kHalfStride = kStageBytes;            // 8 KiB of weights + 8 KiB of rows
-static_assert(kHalfStages * kHalfStride <= kLdsBytes, "same allocation");
+// An LDS ring: NS stages, SB bytes apart, the MFMA B tile BOFF bytes into a stage.
+template <int NS_, int SB_, int BOFF_>
+struct Ring {
+  static constexpr int NS = NS_, SB = SB_, BOFF = BOFF_, BYTES = NS_ * SB_;
+};
+using RingWhole = Ring<kStages, kStagePair, kStageBytes>;  // 16 KiB A tile + 16 KiB B tile
+// half-tile items of GEMM-1 (at most 128 rows): 8 KiB of weights + 8 KiB of rows, twice as deep
+using RingHalf = Ring<8, kStageBytes, kStageBytes / 2>;
+static_assert(RingHalf::BYTES <= kLdsBytes, "same allocation");
 constexpr int64_t kStreamOutBytes = 192ll << 20;    // GEMM-2 outputs larger than this bypass the caches (256 MiB of last-level cache, shared with H)
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
@@ -253,7 +259,8 @@ struct G1Args {
 
 // MFMA A = weight rows, B = pair rows.  Weight rows come in blocks of 32: block 2b is the gate
 // projection of neurons 32b .. 32b+31 of the tile, block 2b+1 their up projection.
-template <int I, int J, int NJ, bool PROFILE, int NW = 4, bool HALF = false>
+// NW / NX: 4 KiB loads per thread and stage for the weight tile / for the rows (64 rows each).
+template <int I, int J, int NJ, bool PROFILE, int NW = 4, bool HALF = false, class RING = RingWhole, int NX = (J == 8 ? (NJ * 32 + 63) / 64 : 4)>
 __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int tid) {
   // Each instantiation derives its lane-dependent offsets from its own opaque copy of the thread
   // id: shared, they would stay live across all the instantiations of the kernel and be parked in
@@ -264,9 +271,9 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   // HALF: one half (64 neurons) of a neuron tile under at most 128 pair rows, in the streaming
   // regime: stages of 8 KiB of weights + 8 KiB of rows in a ring of 8, so that as many bytes are in
   // flight as with whole tiles; wavefronts 2 and 3 only help to load (NJ == 0).
-  constexpr int NS = HALF ? kHalfStages : kStages, SB = HALF ? kHalfStride : kStagePair, BOFF = HALF ? kHalfStride / 2 : kStageBytes;
+  constexpr int NS = RING::NS, SB = RING::SB, BOFF = RING::BOFF;
   const int half = HALF ? g.it.half - 1 : 0;
-  WaveTile<I, J, I, NJ, (HALF ? 4 : J == 8 ? 4 + (NJ * 32 + 63) / 64 : NW + 4), false, NS, SB, BOFF> t;
+  WaveTile<I, J, I, NJ, NW + NX, false, NS, SB, BOFF> t;
   t.init(a_row0, b_row0, lane);
   uint32_t slot = 0, sW = 0, sX = 0;
   auto begin = [&](int st) {
@@ -326,15 +333,11 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   }
 }
 
-// PROFILE = false is the layer's kernel (epilogue fixed at compile time); PROFILE = true picks the
-// importance metric of the epilogue at run time (epi 1..4), which costs a few per cent.
-template <bool PROFILE>
-__global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws, int epi) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int32_t* counters = (const int32_t*)(ws + L.o_counters);
-  const int item_id = xcd_remap(blockIdx.x);
-  if (item_id >= counters[0]) return;
-  G1Args g;
+// What every GEMM-1 workgroup does first: its item, the buffer descriptors, and this thread's part
+// of the activation gather (chunk (tid & 3) of rows i*64 + (tid >> 2), i < SLABS).
+template <int SLABS>
+__device__ __forceinline__ void gemm1_setup(G1Args& g, int item_id, const Layout& L, int T, const char* packed, const uint16_t* x, char* ws,
+                                            int epi, const char* lds, int tid, int w) {
   g.it = ((const Item1*)(ws + L.o_items1))[item_id];
   const int32_t* row_token = (const int32_t*)(ws + L.o_row_token);
   g.row_bits = (const uint8_t*)(ws + L.o_row_bits);
@@ -349,11 +352,8 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   g.H = g.sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
   g.hrow0 = g.sh ? g.it.row0 : g.it.row0 - L.sh_rows;
   g.epi = epi;
-
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // activation gather: this thread copies chunk (tid & 3) of rows i*64 + (tid >> 2)
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < SLABS; ++i) {
     const int r = i * 64 + (tid >> 2);
     const int rr = r < g.it.nrows ? r : g.it.nrows - 1;  // rows past the end re-read the last valid row
     const int tok = row_token[g.it.row0 + rr];
@@ -361,17 +361,29 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   }
   g.woff = (uint32_t)tid * 16;
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
+}
+
+// PROFILE = false is the layer's kernel (epilogue fixed at compile time); PROFILE = true picks the
+// importance metric of the epilogue at run time (epi 1..4), which costs a few per cent.
+template <bool PROFILE>
+__global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws, int epi) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int item_id = xcd_remap(blockIdx.x);
+  if (item_id >= ((const int32_t*)(ws + L.o_counters))[0]) return;  // past the end of the list
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  G1Args g;
+  gemm1_setup<4>(g, item_id, L, T, packed, x, ws, epi, lds, tid, w);
 
   if (g.it.half) {  // at most 128 rows (the plan guarantees it): wavefronts 0 and 1 multiply, 64 weight rows each
     if (w < 2) {
       switch ((g.it.nrows + 31) >> 5) {
-        case 1: gemm1_tile<2, 4, 1, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
-        case 2: gemm1_tile<2, 4, 2, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
-        case 3: gemm1_tile<2, 4, 3, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
-        default: gemm1_tile<2, 4, 4, PROFILE, 2, true>(g, lds, w * 64, 0, tid); break;
+        case 1: gemm1_tile<2, 4, 1, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
+        case 2: gemm1_tile<2, 4, 2, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
+        case 3: gemm1_tile<2, 4, 3, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
+        default: gemm1_tile<2, 4, 4, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
       }
     } else {
-      gemm1_tile<2, 4, 0, PROFILE, 2, true>(g, lds, 0, 0, tid);
+      gemm1_tile<2, 4, 0, PROFILE, 2, true, RingHalf, 2>(g, lds, 0, 0, tid);
     }
   } else if (g.it.nrows == kMfmaBM) {
     // 2 x 2 wavefronts, 128 weight rows x 128 pair rows each; a last neuron tile that is at most half
@@ -403,11 +415,11 @@ struct G2Args {
 };
 
 // MFMA A = pair rows of H, B = output columns of W2.
-template <int I, int J, int NI, bool NT>
+template <int I, int J, int NI, bool NT, class RING = RingWhole>
 __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
   asm volatile("" : "+v"(tid));  // see gemm1_tile
   const int lane = tid & 63;
-  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage), true> t;
+  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage), true, RING::NS, RING::SB, RING::BOFF> t;
   t.init(a_row0, b_row0, lane);
   // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
   // begin() is called with increasing st, so a running cursor maps st -> K position.
@@ -421,12 +433,12 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
       ++p_cur;
       while (p_cur < g.np && !((g.it.kmask >> p_cur) & 1)) ++p_cur;
     }
-    slot = (uint32_t)(st % kStages) * kStagePair + g.lds_w;
+    slot = (uint32_t)(st % RING::NS) * RING::SB + g.lds_w;
     sH = (uint32_t)(kt * kRowBytes);
     sW = (uint32_t)(kt * kStageBytes);
   };
   auto one = [&](int q) {
-    if (q < 4) dma16(g.rsW, slot + kStageBytes + q * 4096, g.woff, sW + q * 4096);
+    if (q < 4) dma16(g.rsW, slot + RING::BOFF + q * 4096, g.woff, sW + q * 4096);
     else dma16(g.rsH, slot + (q - 4) * 4096, g.hoff[q - 4], sH);
   };
   t.mainloop(g.nstages, begin, one, lds);
@@ -440,7 +452,8 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   constexpr int kLanesRow = J * 8;               // lanes that share a row in the write-out
   constexpr int kRowsPass = 64 / kLanesRow;      // rows per store instruction
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  char* mine = lds + w * (kLdsBytes / 4);
+  char* mine = lds + w * (RING::BYTES / 4);
+  static_assert(32 * kYsRow <= RING::BYTES / 4, "a block of 32 rows fits a wavefront's quarter of the ring");
   block_barrier();  // every wave is done reading the last stage
   const int cw = g.it.jd * kMfmaBN2 + b_row0 + (lane % kLanesRow) * 4;  // first of this lane's 4 columns in the write-out
 #pragma unroll
@@ -476,15 +489,10 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   }
 }
 
-// NT: the output leaves with non-temporal stores (for outputs far larger than the caches: the
-// combine step reads them from HBM anyway, and the weight and activation tiles keep their place in L2)
-template <bool NT>
-__global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const char* packed, char* ws) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int32_t* counters = (const int32_t*)(ws + L.o_counters);
-  const int item_id = xcd_remap(blockIdx.x);
-  if (item_id >= counters[1]) return;
-  G2Args g;
+// What every GEMM-2 workgroup does first (see gemm1_setup); SLABS: 64-row groups of H it may load.
+template <int SLABS>
+__device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout& L, const char* packed, char* ws, const char* lds, int tid,
+                                            int w) {
   g.it = ((const Item2*)(ws + L.o_items2))[item_id];
   const bool sh = g.it.e == L.E_res;
   const int Fp = sh ? L.F_shT : L.Fp;
@@ -507,10 +515,8 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
     g.Y = (float*)(ws + L.o_pool) + (size_t)(g.it.split - 1) * kMfmaBM * kMfmaBN2;
     g.ldy = kMfmaBN2;
   }
-
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < SLABS; ++i) {
     const int r = i * 64 + (tid >> 2);
     const int rr = r < g.it.nrows ? r : g.it.nrows - 1;
     g.hoff[i] = (uint32_t)rr * (uint32_t)(ld * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
@@ -519,6 +525,18 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
   g.nstages = 0;
   for (int p = 0; p < g.np; ++p) g.nstages += ((g.it.kmask >> p) & 1) ? g.it.ks_n : 0;
+}
+
+// NT: the output leaves with non-temporal stores (for outputs far larger than the caches: the
+// combine step reads them from HBM anyway, and the weight and activation tiles keep their place in L2)
+template <bool NT>
+__global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const char* packed, char* ws) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int item_id = xcd_remap(blockIdx.x);
+  if (item_id >= ((const int32_t*)(ws + L.o_counters))[1]) return;  // past the end of the list
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  G2Args g;
+  gemm2_setup<4>(g, item_id, L, packed, ws, lds, tid, w);
 
   if (g.it.nrows == kMfmaBM) {
     gemm2_tile<4, 4, 4, NT>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
@@ -539,14 +557,17 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
 static hipError_t set_lds_attr() {
   static bool attr_set = false;
   if (attr_set) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)gemm1_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)gemm2_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e != hipSuccess) return e;
+  const struct {
+    const void* fn;
+    int bytes;
+  } kernels[] = {
+      {(const void*)gemm1_mfma_kernel<false>, kLdsBytes},       {(const void*)gemm1_mfma_kernel<true>, kLdsBytes},
+      {(const void*)gemm2_mfma_kernel<false>, kLdsBytes},       {(const void*)gemm2_mfma_kernel<true>, kLdsBytes},
+  };
+  for (const auto& k : kernels) {
+    hipError_t e = hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.bytes);
+    if (e != hipSuccess) return e;
+  }
   attr_set = true;
   return hipSuccess;
 }
@@ -557,8 +578,9 @@ hipError_t launch_gemm1_mfma(const Layout& L, int T, const char* packed, const v
   hipError_t e = set_lds_attr();
   if (e != hipSuccess) return e;
   const int g1 = (items1_bound(L, T) + 255) & ~255;
-  if (epi == 0) gemm1_mfma_kernel<false><<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws, 0);
-  else gemm1_mfma_kernel<true><<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, (const uint16_t*)x, ws, epi);
+  const uint16_t* xp = (const uint16_t*)x;
+  if (epi == 0) gemm1_mfma_kernel<false><<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, xp, ws, 0);
+  else gemm1_mfma_kernel<true><<<dim3(g1), dim3(256), kLdsBytes, s>>>(L, T, packed, xp, ws, epi);
   return hipGetLastError();
 }
 
