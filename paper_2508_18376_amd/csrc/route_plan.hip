@@ -381,12 +381,31 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   {
     const int32_t* blk_hist = (const int32_t*)(ws + L.o_bin_count);
     const int nblk = (T + route_block_tokens(L.E, T) - 1) / route_block_tokens(L.E, T);
-    for (int i = threadIdx.x; i < L.nbins; i += kPlanThreads) bin_count[i] = 0;
-    __syncthreads();
-    const int total = nblk * L.nbins;
-    for (int i = threadIdx.x; i < total; i += kPlanThreads) {
-      int c = blk_hist[i];
-      if (c) atomicAdd(&bin_count[i % L.nbins], c);
+    // rows r0, r0 + step, .. of column c, eight independent loads at a time (the sum is latency bound)
+    auto col_sum = [&](int c, int r0, int step) {
+      const int32_t* col = blk_hist + c;
+      int sum = 0, r = r0;
+      for (; r + 7 * step < nblk; r += 8 * step) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = col[(size_t)(r + u * step) * L.nbins];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+      }
+      for (; r < nblk; r += step) sum += col[(size_t)r * L.nbins];
+      return sum;
+    };
+    const int G = kPlanThreads / L.nbins;  // threads that share a column (0: more columns than threads)
+    if (G <= 1) {
+      for (int c = threadIdx.x; c < L.nbins; c += kPlanThreads) bin_count[c] = col_sum(c, 0, 1);
+    } else {
+      for (int i = threadIdx.x; i < L.nbins; i += kPlanThreads) bin_count[i] = 0;
+      __syncthreads();
+      const int c = threadIdx.x % L.nbins, g = threadIdx.x / L.nbins;
+      if (g < G) {
+        const int sum = col_sum(c, g, G);
+        if (sum) atomicAdd(&bin_count[c], sum);
+      }
     }
     __syncthreads();
   }
@@ -565,18 +584,36 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       split_of[gj] = q * (nsplit - 1);
     }
   }
-  // 6. per (expert, partition): rank of each active tile
-  for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
-    int e = gidx / L.P, p = gidx % L.P;
-    int nt = (ne[e] + BM - 1) / BM;
-    int cnt = 0;
-    for (int i = 0; i < nt; ++i) {
-      bool act = (tbits[ts[e] + i] >> p) & 1;
-      act_rank[(size_t)(ts[e] + i) * L.P + p] = act ? cnt : -1;
-      cnt += act ? 1 : 0;
+  // 6. per (expert, partition): rank of each active tile among the active tiles of its group
+  if (total_tiles <= kPlanTilesLds) {
+    // keep patterns in LDS: one thread per (tile, partition) counts the active tiles before its own
+    for (int gidx = tid; gidx < NG; gidx += kPlanThreads) ga[gidx] = gb[gidx] = 0;  // groups without tiles
+    __syncthreads();
+    for (int q = tid; q < total_tiles * L.P; q += kPlanThreads) {
+      const int p = q % L.P, g = q / L.P;
+      const int e = tile_expert(g);
+      int cnt = 0;
+      for (int j = ts[e]; j < g; ++j) cnt += (tbits[j] >> p) & 1;
+      const int act = (tbits[g] >> p) & 1;
+      act_rank[(size_t)g * L.P + p] = act ? cnt : -1;
+      if (g - ts[e] == (ne[e] + BM - 1) / BM - 1) {  // the expert's last tile closes the group
+        ga[e * L.P + p] = cnt + act;
+        gb[e * L.P + p] = (cnt + act) * (e < E_res ? L.NT1 : L.NT1_sh);
+      }
     }
-    ga[gidx] = cnt;
-    gb[gidx] = cnt * (e < E_res ? L.NT1 : L.NT1_sh);
+  } else {  // very many tiles: one thread walks the tiles of a group
+    for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
+      int e = gidx / L.P, p = gidx % L.P;
+      int nt = (ne[e] + BM - 1) / BM;
+      int cnt = 0;
+      for (int i = 0; i < nt; ++i) {
+        bool act = (tbits[ts[e] + i] >> p) & 1;
+        act_rank[(size_t)(ts[e] + i) * L.P + p] = act ? cnt : -1;
+        cnt += act ? 1 : 0;
+      }
+      ga[gidx] = cnt;
+      gb[gidx] = cnt * (e < E_res ? L.NT1 : L.NT1_sh);
+    }
   }
   __syncthreads();
   int total1 = block_excl_scan(gb, NG, tmp);

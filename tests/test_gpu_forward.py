@@ -118,6 +118,8 @@ BF16_CASES = [
     ("generic_fallback", spec_of(T=200, D=72, F=80, E=4, K=2, P=2, seed=20), "rate0.25", False),
     # the limits of the configuration at once: 512 experts, top-16, 8 parts
     ("many_tokens", spec_of(T=70001, D=64, F=128, E=8, K=2, P=2, seed=23), "rate0.25", True),  # > 1024 row tiles, > 1000 route blocks
+    # 64-row tiles on the generic path: > 2048 row tiles, whose keep patterns no longer fit the plan kernel's LDS
+    ("many_tiles_generic", spec_of(T=70001, D=40, F=48, E=8, K=2, P=2, seed=26), "rate0.25", False),
     ("max_experts_topk_parts", spec_of(T=300, D=32, F=256, E=512, K=16, P=8, seed=22), "rate0.25", True),
 ]
 
