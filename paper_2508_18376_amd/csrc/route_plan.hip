@@ -725,6 +725,10 @@ hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
 // is arbitrary (it is decided by atomics); the layer output does not depend on it because every
 // row is computed independently of its tile neighbours.
 constexpr int kScatterThreads = 256;
+// PPT pairs per thread (pair u of a thread is block base + u * 256 + thread: coalesced).  A block
+// claims its rows with one global atomic per bin it fills, so larger blocks mean fewer of those
+// (with 256 bins and 256 pairs per block they were the whole cost on the fine-grained layers).
+template <int PPT>
 __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(Layout L, int T, char* ws) {
   extern __shared__ int32_t lh[];  // [nbins]
   const int32_t* idx = (const int32_t*)(ws + L.o_idx);
@@ -735,15 +739,23 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(Layout L, int 
   uint8_t* row_bits = (uint8_t*)(ws + L.o_row_bits);
   const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   const int64_t npairs = (int64_t)T * L.K;
-  const int64_t pr = (int64_t)blockIdx.x * kScatterThreads + threadIdx.x;
+  const int64_t pr0 = (int64_t)blockIdx.x * (kScatterThreads * PPT) + threadIdx.x;
   for (int i = threadIdx.x; i < L.nbins; i += kScatterThreads) lh[i] = 0;
+  int bits[PPT], ex[PPT], bin[PPT], rank[PPT];
+#pragma unroll
+  for (int u = 0; u < PPT; ++u) {
+    const int64_t pr = pr0 + u * kScatterThreads;
+    bits[u] = pr < npairs ? keep[pr] : 0;
+    ex[u] = pr < npairs ? idx[pr] : 0;
+  }
   __syncthreads();
-  int bin = -1, rank = 0, bits = 0;
-  if (pr < npairs) {
-    bits = keep[pr];
-    if (bits) {
-      bin = (idx[pr] - L.lo) * L.nsub + sub_of_bits(bits, nsub_bits);
-      rank = atomicAdd(&lh[bin], 1);
+#pragma unroll
+  for (int u = 0; u < PPT; ++u) {
+    bin[u] = -1;
+    rank[u] = 0;
+    if (bits[u]) {
+      bin[u] = (ex[u] - L.lo) * L.nsub + sub_of_bits(bits[u], nsub_bits);
+      rank[u] = atomicAdd(&lh[bin[u]], 1);
     }
   }
   __syncthreads();
@@ -752,19 +764,23 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_kernel(Layout L, int 
     if (c) lh[i] = atomicAdd(&cursor[i], c);
   }
   __syncthreads();
-  if (pr < npairs) {
-    int row = -1;
-    if (bin >= 0) {
-      row = lh[bin] + rank;
-      row_token[row] = (int32_t)(pr / L.K);
-      row_bits[row] = (uint8_t)bits;
+#pragma unroll
+  for (int u = 0; u < PPT; ++u) {
+    const int64_t pr = pr0 + u * kScatterThreads;
+    if (pr < npairs) {
+      int row = -1;
+      if (bin[u] >= 0) {
+        row = lh[bin[u]] + rank[u];
+        row_token[row] = (int32_t)(pr / L.K);
+        row_bits[row] = (uint8_t)bits[u];
+      }
+      pair_row[pr] = row;
     }
-    pair_row[pr] = row;
-  }
-  // the shared pseudo-expert's rows are the tokens themselves, at the start of the row space
-  if (L.n_shared > 0 && pr < T) {
-    row_token[pr] = (int32_t)pr;
-    row_bits[pr] = 1;
+    // the shared pseudo-expert's rows are the tokens themselves, at the start of the row space
+    if (L.n_shared > 0 && pr < T) {
+      row_token[pr] = (int32_t)pr;
+      row_bits[pr] = 1;
+    }
   }
 }
 
@@ -772,7 +788,13 @@ hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s) {
   int64_t n = (int64_t)T * L.K;
   if (n <= 0) return hipSuccess;
   size_t sh = sizeof(int32_t) * (size_t)(L.nbins > 0 ? L.nbins : 1);
-  scatter_kernel<<<dim3((unsigned)((n + kScatterThreads - 1) / kScatterThreads)), dim3(kScatterThreads), sh, s>>>(L, T, ws);
+  // as many pairs per thread as leave about 64 blocks or more
+  const int64_t per = n / (64 * kScatterThreads);
+  auto blocks = [&](int ppt) { return dim3((unsigned)((n + (int64_t)kScatterThreads * ppt - 1) / ((int64_t)kScatterThreads * ppt))); };
+  if (per >= 8) scatter_kernel<8><<<blocks(8), dim3(kScatterThreads), sh, s>>>(L, T, ws);
+  else if (per >= 4) scatter_kernel<4><<<blocks(4), dim3(kScatterThreads), sh, s>>>(L, T, ws);
+  else if (per >= 2) scatter_kernel<2><<<blocks(2), dim3(kScatterThreads), sh, s>>>(L, T, ws);
+  else scatter_kernel<1><<<blocks(1), dim3(kScatterThreads), sh, s>>>(L, T, ws);
   return hipGetLastError();
 }
 
