@@ -17,7 +17,7 @@ constexpr int kMaxTailSplit = 4;  // most K ranges an item of the last, partly f
 constexpr int kPoolTiles = 256;   // partial-output tiles (256 x 256 fp32) the extra K ranges can need at most
 constexpr int kSelBins = 4096;  // grid of the row-budget thresholds: multiples of 2^-12 (a power of two keeps n * kSelBins exact)
 constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels, one histogram row each ...
-constexpr int kWaveBlockTokens = 16;   // ... except the wavefront kernel (E > 32) on small batches: 4 wavefronts x 4 tokens
+constexpr int kWaveBlockTokens = 16;   // ... except the sixteen-lanes-per-token kernel (E > 32) on small batches: 4 wavefronts x 4 tokens
 constexpr int kWaveSmallBatch = 2048;  // largest batch that uses the small blocks (more blocks would swamp the plan kernel's sum)
 inline __host__ __device__ int route_block_tokens(int E, int T) {
   return (E <= 32 || T > kWaveSmallBatch) ? kRouteBlockTokens : kWaveBlockTokens;

@@ -39,7 +39,7 @@ __device__ __forceinline__ int sub_of_bits(int bits, int nsub_bits) {
   return (1 << nsub_bits) - 1 - rev;
 }
 
-// tau: the [E][P] threshold table (the wavefront kernel keeps a copy in LDS)
+// tau: the [E][P] threshold table (the sixteen-lanes-per-token kernel keeps a copy in LDS)
 __device__ __forceinline__ int keep_bits_of(float n, int e, const RouteArgs& a, const float* tau) {
   int bits = 0;
   if (e >= a.lo && e < a.hi) {
@@ -125,152 +125,164 @@ __global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
   }
 }
 
-// Wavefront reductions on the vector ALU's data-parallel primitives (row shifts inside the four
-// rows of 16 lanes, then the two row broadcasts): lane 63 ends up with the total, which is read
-// back as a wavefront-uniform value.  Lanes without a source take the identity.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_f32(float identity, float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+// Sixteen lanes per token (one row of the wavefront), NCH * 4 logits per lane: lane r of the row
+// holds experts 64c + 4r .. 64c + 4r + 3 of every chunk c of 64 experts (16-byte loads, 256
+// contiguous bytes per row and chunk).  All reductions stay inside a row: four data-parallel
+// steps (mirror, half mirror, two quad permutations) leave the result in every lane, with no
+// scalar round trip, and the four rows of a wavefront work on four tokens at once.  U tokens per
+// row are carried through every step together so that their dependency chains overlap.
+// A block is WV wavefronts = WV * 4 * U tokens.
+constexpr int kRowMirror = 0x140, kRowHalfMirror = 0x141, kQuadSwap2 = 0x4E, kQuadSwap1 = 0xB1;
+template <int CTRL>
+__device__ __forceinline__ int dpp_all(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
 }
-constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
-__device__ __forceinline__ float wave_max(float v) {
-  v = fmaxf(v, dpp_f32<kRowShr1, 0xf>(-INFINITY, v));
-  v = fmaxf(v, dpp_f32<kRowShr2, 0xf>(-INFINITY, v));
-  v = fmaxf(v, dpp_f32<kRowShr4, 0xf>(-INFINITY, v));
-  v = fmaxf(v, dpp_f32<kRowShr8, 0xf>(-INFINITY, v));
-  v = fmaxf(v, dpp_f32<kRowBcast15, 0xa>(-INFINITY, v));
-  v = fmaxf(v, dpp_f32<kRowBcast31, 0xc>(-INFINITY, v));
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+__device__ __forceinline__ float row_max(float v) {
+  v = fmaxf(v, __int_as_float(dpp_all<kRowMirror>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_all<kRowHalfMirror>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_all<kQuadSwap2>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_all<kQuadSwap1>(__float_as_int(v))));
+  return v;
 }
-__device__ __forceinline__ float wave_sum(float v) {
-  v += dpp_f32<kRowShr1, 0xf>(0.f, v);
-  v += dpp_f32<kRowShr2, 0xf>(0.f, v);
-  v += dpp_f32<kRowShr4, 0xf>(0.f, v);
-  v += dpp_f32<kRowShr8, 0xf>(0.f, v);
-  v += dpp_f32<kRowBcast15, 0xa>(0.f, v);
-  v += dpp_f32<kRowBcast31, 0xc>(0.f, v);
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+__device__ __forceinline__ float row_sum(float v) {  // every step adds two partners' values: the same bits in every lane
+  v += __int_as_float(dpp_all<kRowMirror>(__float_as_int(v)));
+  v += __int_as_float(dpp_all<kRowHalfMirror>(__float_as_int(v)));
+  v += __int_as_float(dpp_all<kQuadSwap2>(__float_as_int(v)));
+  v += __int_as_float(dpp_all<kQuadSwap1>(__float_as_int(v)));
+  return v;
+}
+__device__ __forceinline__ int row_min(int v) {
+  v = min(v, dpp_all<kRowMirror>(v));
+  v = min(v, dpp_all<kRowHalfMirror>(v));
+  v = min(v, dpp_all<kQuadSwap2>(v));
+  v = min(v, dpp_all<kQuadSwap1>(v));
+  return v;
 }
 
-// One wavefront per token, LPT logits per lane (E <= 64*LPT).  Every logit gets its rank under
-// (value descending, index ascending); ranks below K are the selected slots.  A block is WAVES
-// wavefronts that walk 4 tokens each and share one LDS histogram: 16 wavefronts (64 tokens) for
-// large batches, 4 (one per SIMD: the Top-K rounds are bound by instruction issue) for small ones.
-
-template <int LPT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void route_wave_kernel(RouteArgs a) {
-  constexpr int kWaveThreads = WAVES * 64, kWaveTokens = WAVES * 4;
+template <int NCH, int U, int WV>
+__global__ __launch_bounds__(WV * 64) void route_row_kernel(RouteArgs a) {
+  constexpr int kThreads = WV * 64, kTokens = WV * 4 * U, V = NCH * 4;
   extern __shared__ int32_t hist[];
-  for (int i = threadIdx.x; i < a.nhist; i += kWaveThreads) hist[i] = 0;
+  for (int i = threadIdx.x; i < a.nhist; i += kThreads) hist[i] = 0;
   // the threshold table is fetched now, together with the logits, not after the scores are known
   float* tau_l = (float*)(hist + a.nhist);
-  for (int i = threadIdx.x; i < a.E * a.P; i += kWaveThreads) tau_l[i] = a.tau[i];
+  for (int i = threadIdx.x; i < a.E * a.P; i += kThreads) tau_l[i] = a.tau[i];
   // (the barrier that publishes hist and tau_l sits right before their first use, after the scores)
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int t_end = min(a.T, ((int)blockIdx.x + 1) * kWaveTokens);
-  // all logits of this wavefront's tokens are requested before the first is used
-  constexpr int kWaves = kWaveThreads / 64;
-  constexpr int kTokPerWave = kWaveTokens / kWaves;
-  float lall[kTokPerWave][LPT];
+  const int r = threadIdx.x & 15, row = threadIdx.x >> 4;  // lane in its row; row in the block (WV * 4 of them)
+  const int t_end = min(a.T, ((int)blockIdx.x + 1) * kTokens);
+  auto token = [&](int u) { return (int)blockIdx.x * kTokens + u * (WV * 4) + row; };
+  auto expert = [&](int j) { return 64 * (j >> 2) + 4 * r + (j & 3); };
+  float l[U][V];
+  const bool vec = (a.E & 3) == 0;  // rows of the logits are 16-byte aligned
 #pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) {
-    const int t = blockIdx.x * kWaveTokens + wv + kWaves * u;
+  for (int u = 0; u < U; ++u) {
+    const int t = token(u);
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      int e = lane + 64 * i;
-      const float v = (t < t_end && e < a.E) ? a.logits[(size_t)t * a.E + e] : -INFINITY;
-      lall[u][i] = v != v ? -INFINITY : v;  // a NaN logit ranks last, so every round below finds a winner
-    }
-  }
-  // The wavefront's tokens go through every step together: their reduction and ranking chains are
-  // independent, so their latencies overlap.  Tokens past the end carry -inf logits and are not stored.
-  float m[kTokPerWave], z[kTokPerWave];
-#pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) {
-    float v = lall[u][0];
-#pragma unroll
-    for (int i = 1; i < LPT; ++i) v = fmaxf(v, lall[u][i]);
-    m[u] = v;
-  }
-#pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) m[u] = wave_max(m[u]);
-#pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) {
-    float v = 0.f;
-#pragma unroll
-    for (int i = 0; i < LPT; ++i)
-      if (lane + 64 * i < a.E) v += expf(lall[u][i] - m[u]);
-    z[u] = v;
-  }
-#pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) z[u] = wave_sum(z[u]);
-  // Top-K in K rounds of "largest logit not yet taken, lowest expert id among equals" (Eq. 2): a
-  // wavefront maximum, then a ballot of the lanes that hold it; slot k of the token is round k's
-  // winner.  rank = slot of a selected logit, a.K for the others.
-  int rank[kTokPerWave][LPT];
-  bool taken[kTokPerWave][LPT];
-#pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u)
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      rank[u][i] = a.K;
-      taken[u][i] = lane + 64 * i >= a.E;
-    }
-  for (int k = 0; k < a.K; ++k) {
-    float g[kTokPerWave];
-#pragma unroll
-    for (int u = 0; u < kTokPerWave; ++u) {
-      float v = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < LPT; ++i) v = fmaxf(v, taken[u][i] ? -INFINITY : lall[u][i]);
-      g[u] = v;
-    }
-#pragma unroll
-    for (int u = 0; u < kTokPerWave; ++u) g[u] = wave_max(g[u]);
-#pragma unroll
-    for (int u = 0; u < kTokPerWave; ++u) {
-      bool found = false;  // wavefront-uniform
-#pragma unroll
-      for (int i = 0; i < LPT; ++i) {  // expert ids grow with i first, then with the lane
-        const unsigned long long cand = __ballot(!taken[u][i] && lall[u][i] == g[u]);
-        if (!found && cand != 0ull) {
-          found = true;
-          if (lane == (int)__builtin_ctzll(cand)) {
-            rank[u][i] = k;
-            taken[u][i] = true;
-          }
+    for (int c = 0; c < NCH; ++c) {
+      const int e0 = 64 * c + 4 * r;
+      float4 v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (t < t_end) {
+        const float* src = a.logits + (size_t)t * a.E + e0;
+        if (vec) {
+          if (e0 < a.E) v = *(const float4*)src;
+        } else {
+          if (e0 + 0 < a.E) v.x = src[0];
+          if (e0 + 1 < a.E) v.y = src[1];
+          if (e0 + 2 < a.E) v.z = src[2];
+          if (e0 + 3 < a.E) v.w = src[3];
         }
       }
+      // a NaN logit ranks last, so every round below finds a winner
+      l[u][4 * c + 0] = v.x != v.x ? -INFINITY : v.x;
+      l[u][4 * c + 1] = v.y != v.y ? -INFINITY : v.y;
+      l[u][4 * c + 2] = v.z != v.z ? -INFINITY : v.z;
+      l[u][4 * c + 3] = v.w != v.w ? -INFINITY : v.w;
     }
   }
-  float s[kTokPerWave][LPT], ssum[kTokPerWave];
+  float m[U], z[U];
 #pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) {
+  for (int u = 0; u < U; ++u) {
+    float v = l[u][0];
+#pragma unroll
+    for (int j = 1; j < V; ++j) v = fmaxf(v, l[u][j]);
+    m[u] = row_max(v);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
     float v = 0.f;
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const bool selq = (lane + 64 * i < a.E) && rank[u][i] < a.K;
-      s[u][i] = selq ? expf(lall[u][i] - m[u]) / z[u] : 0.f;  // Eq. 1
-      v += s[u][i];
-    }
-    ssum[u] = v;
+    for (int j = 0; j < V; ++j)
+      if (expert(j) < a.E) v += expf(l[u][j] - m[u]);
+    z[u] = row_sum(v);
   }
+  // Top-K in K rounds of "largest logit not yet taken, lowest expert id among equals" (Eq. 2): the
+  // row's maximum, then the row's smallest expert id among the lanes that hold it; slot k of the
+  // token is round k's winner.  rank = slot of a selected logit, a.K for the others.
+  int rank[U][V];
+  uint32_t taken[U];
 #pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) ssum[u] = wave_sum(ssum[u]);
+  for (int u = 0; u < U; ++u) {
+    taken[u] = 0;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      rank[u][j] = a.K;
+      if (expert(j) >= a.E) taken[u] |= 1u << j;
+    }
+  }
+  for (int k = 0; k < a.K; ++k) {
+    float g[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float v = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < V; ++j) v = fmaxf(v, (taken[u] >> j) & 1 ? -INFINITY : l[u][j]);
+      g[u] = row_max(v);
+    }
+    int win[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int cand = 0x7fffffff;
+#pragma unroll
+      for (int j = V - 1; j >= 0; --j)  // expert ids grow with j: the last assignment is the smallest
+        if (!((taken[u] >> j) & 1) && l[u][j] == g[u]) cand = expert(j);
+      win[u] = row_min(cand);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int j = 0; j < V; ++j)
+        if (expert(j) == win[u]) {
+          rank[u][j] = k;
+          taken[u] |= 1u << j;
+        }
+    }
+  }
+  float sc[U][V], ssum[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const bool selq = expert(j) < a.E && rank[u][j] < a.K;
+      sc[u][j] = selq ? expf(l[u][j] - m[u]) / z[u] : 0.f;  // Eq. 1
+      v += sc[u][j];
+    }
+    ssum[u] = row_sum(v);
+  }
   __syncthreads();  // hist is cleared and tau_l is complete
 #pragma unroll
-  for (int u = 0; u < kTokPerWave; ++u) {
-    const int t = blockIdx.x * kWaveTokens + wv + kWaves * u;
+  for (int u = 0; u < U; ++u) {
+    const int t = token(u);
     if (t >= t_end) continue;
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int e = lane + 64 * i;
-      if (e < a.E && rank[u][i] < a.K) {
-        const float n = s[u][i] / ssum[u];  // Sec. 4.1: normalise over the K selected
+    for (int j = 0; j < V; ++j) {
+      const int e = expert(j);
+      if (e < a.E && rank[u][j] < a.K) {
+        const float n = sc[u][j] / ssum[u];  // Sec. 4.1: normalise over the K selected
         const int bits = keep_bits_of(n, e, a, tau_l);
-        const size_t o = (size_t)t * a.K + rank[u][i];
+        const size_t o = (size_t)t * a.K + rank[u][j];
         a.idx[o] = e;
-        a.w[o] = a.renorm ? n : s[u][i];
+        a.w[o] = a.renorm ? n : sc[u][j];
         a.keep[o] = (uint8_t)bits;
         count_pair(hist, bits, e, a);
       }
@@ -278,7 +290,7 @@ __global__ __launch_bounds__(WAVES * 64) void route_wave_kernel(RouteArgs a) {
   }
   __syncthreads();
   const int nb = a.bin_count ? (a.hi - a.lo) * a.nsub : 0;
-  for (int i = threadIdx.x; i < a.nhist; i += kWaveThreads) {
+  for (int i = threadIdx.x; i < a.nhist; i += kThreads) {
     int c = hist[i];
     if (i < nb) a.bin_count[(size_t)blockIdx.x * nb + i] = c;  // this block's row of the histogram: no atomics
     else if (c) atomicAdd(&a.group_count[i - nb], c);
@@ -307,24 +319,24 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
   a.nsub = L.nsub;
   a.nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   a.nhist = (bin_count ? L.nbins : 0) + (group_count ? L.E * L.P : 0);
-  const size_t sh = sizeof(int32_t) * (size_t)(a.nhist + L.E * L.P);  // histogram + (wavefront kernel) threshold table
+  const size_t sh = sizeof(int32_t) * (size_t)(a.nhist + L.E * L.P);  // histogram + (row kernel) threshold table
   if (L.E <= 32) {  // few experts: a lane per token, no cross-lane traffic
     dim3 grid((T + 63) / 64), block(64);
     if (L.E <= 8) route_lane_kernel<8, 8><<<grid, block, sh, s>>>(a);
     else if (L.E <= 16) route_lane_kernel<16, 16><<<grid, block, sh, s>>>(a);
     else route_lane_kernel<32, 16><<<grid, block, sh, s>>>(a);
-  } else if (T > kWaveSmallBatch) {  // many experts: a wavefront per token, 64 tokens per block
-    dim3 grid((T + kRouteBlockTokens - 1) / kRouteBlockTokens), block(1024);
-    if (L.E <= 64) route_wave_kernel<1, 16><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 128) route_wave_kernel<2, 16><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 256) route_wave_kernel<4, 16><<<grid, block, sh, s>>>(a);
-    else route_wave_kernel<8, 16><<<grid, block, sh, s>>>(a);
-  } else {  // small batch: 16 tokens per block
+  } else if (T > kWaveSmallBatch) {  // many experts: sixteen lanes per token, 64 tokens per block
+    dim3 grid((T + kRouteBlockTokens - 1) / kRouteBlockTokens);
+    if (L.E <= 64) route_row_kernel<1, 1, 16><<<grid, dim3(1024), sh, s>>>(a);
+    else if (L.E <= 128) route_row_kernel<2, 1, 16><<<grid, dim3(1024), sh, s>>>(a);
+    else if (L.E <= 256) route_row_kernel<4, 1, 16><<<grid, dim3(1024), sh, s>>>(a);
+    else route_row_kernel<8, 1, 16><<<grid, dim3(1024), sh, s>>>(a);
+  } else {  // small batch: 16 tokens per block, one per row of four wavefronts
     dim3 grid((T + kWaveBlockTokens - 1) / kWaveBlockTokens), block(256);
-    if (L.E <= 64) route_wave_kernel<1, 4><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 128) route_wave_kernel<2, 4><<<grid, block, sh, s>>>(a);
-    else if (L.E <= 256) route_wave_kernel<4, 4><<<grid, block, sh, s>>>(a);
-    else route_wave_kernel<8, 4><<<grid, block, sh, s>>>(a);
+    if (L.E <= 64) route_row_kernel<1, 1, 4><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 128) route_row_kernel<2, 1, 4><<<grid, block, sh, s>>>(a);
+    else if (L.E <= 256) route_row_kernel<4, 1, 4><<<grid, block, sh, s>>>(a);
+    else route_row_kernel<8, 1, 4><<<grid, block, sh, s>>>(a);
   }
   return hipGetLastError();
 }
