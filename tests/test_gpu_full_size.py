@@ -90,3 +90,36 @@ def test_full_size_layer(oracle, name, rate, n_sample):
         assert np.all(y_all[dead] == 0.0)
         assert np.all(np.abs(y_all[~dead]).max(axis=1) > 0)
     layer.close()
+
+
+# decode-sized batches of the full-size layers: the weight-streaming regime (split K in GEMM-2,
+# halved GEMM-1 items, half-empty neuron tiles as first halves), every token against the oracle
+DECODE_CASES = [("C2", 64), ("C2", 16), ("C3", 48), ("C4", 64), ("C5", 32)]
+
+
+@pytest.mark.parametrize("name,T", DECODE_CASES, ids=["%s-%d" % c for c in DECODE_CASES])
+def test_full_size_layer_decode_batch(oracle, name, T):
+    import torch
+    spec = LAYERS[name].with_(T=T)
+    t = make_layer(spec, threads=16)
+    r0 = oracle.route(t["logits"], spec.K, spec.P, np.zeros((spec.E, spec.P), np.float32), spec.lo, spec.hi)
+    res = (r0.idx >= spec.lo) & (r0.idx < spec.hi)
+    ref = tau = None
+    for rate in (0.25, 0.27, 0.23, 0.29, 0.21, 0.31):  # few scores: take the first rate whose thresholds clear the guard band
+        tau = tau_table(spec, pick_tau(r0.n[res], spec.P, rate, window=0.02))
+        ref = oracle.route(t["logits"], spec.K, spec.P, tau, spec.lo, spec.hi)
+        if ref.min_margin > GUARD:
+            break
+    assert ref.min_margin > GUARD, ref.min_margin
+    layer, dev = make_gpu_layer(spec, t)
+    assert layer.uses_mfma
+    tau_dev = to_dev(tau)
+    idx, w, keep, gc = layer.route_and_mask(dev["logits"], tau_dev)
+    y = layer.forward(dev["x"], dev["logits"], tau_dev)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref.idx)
+    np.testing.assert_array_equal(keep.cpu().numpy(), ref.keep_bits)
+    y_ref = oracle.forward(t["x"], t["logits"], t["w1"], t["w3"], t["w2"], tau, spec.K, spec.P, perm=t["perm"],
+                           sh_w1=t.get("sh_w1"), sh_w3=t.get("sh_w3"), sh_w2=t.get("sh_w2"), lo=spec.lo, hi=spec.hi)
+    assert_output_close(to_host64(y, "bf16"), y_ref, "bf16")
+    layer.close()
