@@ -352,8 +352,10 @@ def main():
                  "sample_max_err_over_rms": float(aerr.max() / rms),
                  "sample_max_err_beyond_bf16_output_rounding_over_rms": float((aerr - 2.0 ** -8 * np.abs(y_ref)).max() / rms),
                  "tolerance": 2e-2}
-        log("oracle: %.2f tokens/s on %d threads; GPU vs oracle on the sample: %.4f x RMS" % (cpu["value"], cpu["cores"],
-                                                                                      check["sample_max_err_over_rms"]))
+        log("oracle: %.2f tokens/s on %d threads; GPU vs oracle on the sample: max |err| %.4f x RMS, %.4f x RMS beyond the "
+            "rounding of the bf16 output (bar 0.02), %d elements over the bar" % (
+                cpu["value"], cpu["cores"], check["sample_max_err_over_rms"],
+                check["sample_max_err_beyond_bf16_output_rounding_over_rms"], check["elements_beyond_tolerance"]))
 
     out = {
         "metric": "MoE-layer tokens/s + MFMA TFLOP/s vs bf16 peak at 0/25/50% drop",
