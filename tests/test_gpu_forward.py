@@ -273,6 +273,10 @@ HALF_CASES = [
     ("halved_with_shared", spec_of(T=32, D=128, F=4608, E=8, K=2, P=4, n_shared=1, F_sh=512, seed=52), 0.0, True),
     # the shared experts' row tile has more than 128 rows: their items keep one slot and leave one empty
     ("uncut_shared_items", spec_of(T=200, D=128, F=4480, E=32, K=2, P=1, n_shared=1, F_sh=512, seed=56), 0.0, True),
+    # 65..128 rows per expert (three and four blocks of 32 rows in the half-tile kernel variant)
+    ("halved_100_rows", spec_of(T=200, D=128, F=2304, E=4, K=2, P=2, seed=57), 0.0, True),
+    ("halved_85_rows", spec_of(T=170, D=192, F=2304, E=4, K=2, P=2, seed=58), "rate0.25", None),
+    ("first_halves_100_rows", spec_of(T=200, D=128, F=384, E=4, K=2, P=2, seed=59), 0.0, True),
     # 448 items: the second round is three quarters full and stays as it is
     ("last_round_too_full", spec_of(T=64, D=128, F=7168, E=8, K=2, P=4, seed=53), 0.0, False),
     # more than half a tile of rows per expert: not the streaming regime
