@@ -9,9 +9,15 @@
 // v_mfma_f32_32x32x16_bf16.  A full 256-row tile is split 2 x 2 (each wavefront a 128 x 128 block,
 // 4 x 4 MFMA blocks).  The last tile of an expert's (or sub-expert's) row list is ragged: there the
 // wavefronts split the weight dimension four ways and all walk the same rows, skipping the
-// 32-row blocks past the end, so that a tile with r rows costs about ceil(r/32)/8 of a full one
-// (with drops every sub-expert has its own ragged tail: this is what keeps time proportional to
-// the kept work).
+// 32-row blocks past the end, so that a tile with r rows does ceil(r/32)/8 of a full one's matrix
+// work (with drops every sub-expert has its own ragged tail: this is what keeps time proportional
+// to the kept work); its time does not fall below the arrival of its weight tile, though
+// (measured: 0.7 of a full tile for a handful of rows).
+// Further variants of GEMM-1: a last neuron tile of at most 64 neurons takes only the first 128
+// weight rows, and items of at most 128 rows can be halves of a neuron tile (64 neurons) with a
+// ring twice as deep, for batches so small that the kernel only streams weights.
+// GEMM-2 feeds the weight fragment as the MFMA's A operand, so that a lane ends up with four
+// consecutive output columns of a row.
 //
 // Operand tiles [256][32] bf16 travel HBM/L2 -> LDS by buffer loads that write LDS directly (no
 // registers in between), through a ring of 4 stages (4 x 32 KiB of the CU's 160 KiB LDS), three
