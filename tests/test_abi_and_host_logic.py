@@ -250,3 +250,36 @@ def test_build_refuses_register_spills_in_the_gemm_kernels():
     bad = build._scratch_users(remarks, build.NO_SCRATCH["gemm_mfma.hip"])
     assert len(bad) == 1 and "gemm1_mfma_kernel" in bad[0] and "20" in bad[0]
     assert build._scratch_users(remarks.replace(": 20 ", ": 0 "), build.NO_SCRATCH["gemm_mfma.hip"]) == []
+
+
+def test_header_is_plain_c(lib, tmp_path):
+    """include/dsmoe.h is the boundary: it must compile as C (no C++ or HIP types in the
+    signatures) and a C program must link against the library's entry points."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_dsmoe.c"
+    src.write_text(
+        '#include "dsmoe.h"\n'
+        "#include <stdio.h>\n"
+        "int main(void) {\n"
+        "  dsmoe_config c = {0};\n"
+        "  dsmoe_ctx* ctx = 0;\n"
+        "  int rc = dsmoe_create(&c, &ctx);  /* an all-zero configuration is refused, without a GPU */\n"
+        '  printf("%d %s\\n", rc, dsmoe_strerror(rc));\n'
+        "  return rc == 0;\n"
+        "}\n")
+    inc = os.path.join(ROOT, "include")
+    obj = tmp_path / "use_dsmoe.o"
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-c", str(src), "-o", str(obj)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    exe = tmp_path / "use_dsmoe"
+    libdir = os.path.dirname(LIB)
+    r = subprocess.run([gcc, str(obj), "-o", str(exe), "-L", libdir, "-l:libdsmoe.so", "-Wl,-rpath," + libdir,
+                        "-Wl,--allow-shlib-undefined"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.split()[0] != "0", (r.returncode, r.stdout, r.stderr)
