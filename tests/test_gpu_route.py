@@ -27,6 +27,13 @@ CASES = [
     ("E128K4wave", spec_of(T=700, E=128, K=4, P=2, seed=7), "rate0.25", False),
     ("E300K6wave", spec_of(T=300, E=300, K=6, P=8, seed=8), "rate0.25", True),
     ("E512K16wave", spec_of(T=65, E=512, K=16, P=2, seed=9), "rate0.25", False),
+    # expert counts that are not multiples of 4 (unaligned logit rows: scalar loads), small and large batches
+    ("E50K3rows", spec_of(T=500, E=50, K=3, P=2, seed=13), "rate0.25", False),
+    ("E131K5big", spec_of(T=2500, E=131, K=5, P=2, seed=14), "rate0.25", True),
+    # more than 2048 tokens: 64 tokens per block, 2 / 4 / 8 chunks of 64 experts per lane row
+    ("E128K4big", spec_of(T=2100, E=128, K=4, P=2, seed=15), "rate0.25", False),
+    ("E256K8big", spec_of(T=2100, E=256, K=8, P=4, seed=16), "rate0.25", False),
+    ("E512K6big", spec_of(T=2050, E=512, K=6, P=2, seed=17), "rate0.33", False),
     ("window", spec_of(T=2000, E=8, K=2, P=4, seed=10, resident=(2, 5)), "rate0.25", False),
     ("zipf", LAYERS["C5"].with_(T=2048), "rate0.25", False),
     ("K1", spec_of(T=64, E=5, K=1, P=2, seed=11), 1.0, False),
