@@ -368,7 +368,10 @@ def main():
             round(100 * args.primary_rate), 100 * primary["drop_rate"]),
             "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
-        "sweep": sweep, "proportionality": prop, "kernels": kernels, "reconstruction": reconstruction, "threshold_selection": selection, "decode": decode, "router": router, "complete_transformation": transform,
+        "sweep": sweep, "proportionality": prop, "kernels": kernels,
+        "kernels_note": "HIP-event intervals around each launch of a separate timing pass: every entry carries about 4 us of "
+                        "event-to-event gap (an empty interval reads 4-5 us); kernel durations proper are in profiles/",
+        "reconstruction": reconstruction, "threshold_selection": selection, "decode": decode, "router": router, "complete_transformation": transform,
         "roofline": roofline, "cpu_baseline": cpu, "check": check,
     }
     print(json.dumps(out))
