@@ -82,13 +82,17 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
     if (stage < st13 + sts13) {
       const bool sh = stage >= st13;
       if (sh) stage -= st13;
-      const int ks = (int)(stage % KS1);
-      int64_t r = stage / KS1;
+      // order of the work: expert, K stage, (partition, neuron tile).  The threads at work at one time
+      // then read the same few rows d of W1 / W3 (one 2-byte element per 32-byte sector, in permuted
+      // column order), which stay in L2; the destination index below does not depend on this order.
       const int nt1 = sh ? L.NT1_sh : L.NT1;
-      const int jt = (int)(r % nt1);
-      r /= nt1;
-      const int p = sh ? 0 : (int)(r % L.P);
-      const int e = sh ? 0 : (int)(r / L.P);
+      const int tiles = (sh ? 1 : L.P) * nt1;
+      const int tile = (int)(stage % tiles);
+      int64_t r = stage / tiles;
+      const int ks = (int)(r % KS1);
+      const int e = sh ? 0 : (int)(r / KS1);
+      const int jt = tile % nt1;
+      const int p = sh ? 0 : tile / nt1;
       const int q = row >> 6, gu = (row >> 5) & 1, j = row & 31;
       const int Fp = sh ? L.F_shT : L.Fp;
       const int nin = jt * kMfmaNeur + q * 32 + j;  // neuron inside the partition
