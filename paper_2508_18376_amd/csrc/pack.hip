@@ -64,7 +64,7 @@ __global__ void pack_generic_kernel(Layout L, const T* w1, const T* w3, const T*
 // One thread per 16-byte chunk of the packed MFMA buffers.
 __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w3, const uint16_t* w2,
                                  const uint16_t* sw1, const uint16_t* sw3, const uint16_t* sw2, const int32_t* perm,
-                                 char* packed, int n_shared, int F_sh) {
+                                 char* packed, int n_shared, int F_sh, int skip_routed_w13) {
   const int KS1 = L.D / kBK;
   const int64_t chunks_per_stage = kStageBytes / 16;  // 2048
   const int64_t st13 = (int64_t)L.E_res * L.P * L.NT1 * KS1;
@@ -72,7 +72,8 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
   const int64_t sts13 = (int64_t)(n_shared > 0 ? L.NT1_sh * KS1 : 0);
   const int64_t sts2 = (int64_t)(n_shared > 0 ? L.ND2 * (L.F_shT / kBK) : 0);
   const int64_t total = (st13 + st2 + sts13 + sts2) * chunks_per_stage;
-  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
+  const int64_t first = skip_routed_w13 ? st13 * chunks_per_stage : 0;  // those stages are written by pack_w13_columns_kernel
+  for (int64_t q = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (int64_t)gridDim.x * blockDim.x) {
     int64_t stage = q / chunks_per_stage;
     int c = (int)(q % chunks_per_stage);
     const int row = c / kChunksPerRow, pc = c % kChunksPerRow;
@@ -150,13 +151,95 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
   }
 }
 
+// The routed W1 / W3 stages, walked in SOURCE order: a thread takes one original neuron (column
+// src of W1 and W3) and one K stage, reads its 32 values of d from 32 rows (neighbouring threads read
+// neighbouring columns: whole cache lines, where a walk in destination order fetches a line per
+// 2-byte element of a permuted column) and writes the neuron's two 64-byte image rows at the place
+// the inverse permutation names.  inv == nullptr: identity order.
+__global__ __launch_bounds__(256) void pack_w13_columns_kernel(Layout L, const uint16_t* w1, const uint16_t* w3, const int32_t* inv,
+                                                              char* packed) {
+  const int src = blockIdx.x * 256 + threadIdx.x, ks = blockIdx.y, e = blockIdx.z;
+  if (src >= L.F) return;
+  const int pos = inv ? inv[(size_t)e * L.F + src] : src;
+  const int p = pos / L.Fp, nin = pos % L.Fp;
+  const int jt = nin / kMfmaNeur, q = (nin % kMfmaNeur) >> 5, j = nin & 31;
+  const int KS1 = L.D / kBK;
+  char* stage = packed + L.p_w13 + ((((int64_t)e * L.P + p) * L.NT1 + jt) * KS1 + ks) * kStageBytes;
+#pragma unroll
+  for (int gu = 0; gu < 2; ++gu) {
+    const uint16_t* w = (gu ? w3 : w1) + ((size_t)e * L.D + (size_t)ks * kBK) * L.F + src;
+    uint16_t v[kBK];
+#pragma unroll
+    for (int i = 0; i < kBK; ++i) v[i] = w[(size_t)i * L.F];
+    const int row = q * 64 + gu * 32 + j;
+#pragma unroll
+    for (int lc = 0; lc < kChunksPerRow; ++lc) {
+      uint4 o;
+      o.x = v[8 * lc + 0] | ((uint32_t)v[8 * lc + 1] << 16);
+      o.y = v[8 * lc + 2] | ((uint32_t)v[8 * lc + 3] << 16);
+      o.z = v[8 * lc + 4] | ((uint32_t)v[8 * lc + 5] << 16);
+      o.w = v[8 * lc + 6] | ((uint32_t)v[8 * lc + 7] << 16);
+      *(uint4*)(stage + row * (kBK * 2) + swz_chunk(row, lc) * 16) = o;
+    }
+  }
+}
+
+// image rows of the neurons past the end of a partition (its last neuron tile is not full): zeros
+__global__ __launch_bounds__(256) void pack_w13_padding_kernel(Layout L, char* packed) {
+  const int pad = L.NT1 * kMfmaNeur - L.Fp;  // neurons per (expert, partition) that do not exist
+  const int KS1 = L.D / kBK;
+  const int64_t total = (int64_t)L.E_res * L.P * KS1 * pad * 2 * kChunksPerRow;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= total) return;
+  const int pc = (int)(t % kChunksPerRow);
+  int64_t r = t / kChunksPerRow;
+  const int gu = (int)(r % 2);
+  r /= 2;
+  const int nin = L.Fp + (int)(r % pad);
+  r /= pad;
+  const int ks = (int)(r % KS1);
+  const int64_t ep = r / KS1;  // e * P + p
+  const int jt = nin / kMfmaNeur, q = (nin % kMfmaNeur) >> 5, j = nin & 31;
+  const int row = q * 64 + gu * 32 + j;
+  char* stage = packed + L.p_w13 + ((ep * L.NT1 + jt) * KS1 + ks) * kStageBytes;
+  *(uint4*)(stage + row * (kBK * 2) + pc * 16) = make_uint4(0, 0, 0, 0);
+}
+
+// inv[e][perm[e][pos]] = pos
+__global__ void invert_perm_kernel(const int32_t* perm, int32_t* inv, int F, int64_t n) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  const int64_t e = t / F;
+  const int src = perm[t];
+  if (src >= 0 && src < F) inv[e * F + src] = (int32_t)(t % F);  // a bad perm is refused before this runs; stay in bounds regardless
+}
+
 hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const void* w2, const void* sw1, const void* sw3,
                        const void* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh, hipStream_t s) {
   dim3 block(256), grid(256 * 64);
   if (L.mfma) {
+    // The routed W1 / W3 stages are written in source order (see pack_w13_columns_kernel), which
+    // needs the inverse permutation: it is parked in the W2 region of the packed buffer, which
+    // the last kernel overwrites.  (That region has E_res * F * D * 2 bytes, the table E_res * F * 4.)
+    const bool columns = L.D >= 2 && (int64_t)L.D / kBK <= 65535 && L.E_res <= 65535;
+    if (columns) {
+      int32_t* inv = nullptr;
+      if (perm) {
+        inv = (int32_t*)(packed + L.p_w2);
+        const int64_t n = (int64_t)L.E_res * L.F;
+        invert_perm_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(perm, inv, L.F, n);
+      }
+      pack_w13_columns_kernel<<<dim3((L.F + 255) / 256, L.D / kBK, L.E_res), dim3(256), 0, s>>>(
+          L, (const uint16_t*)w1, (const uint16_t*)w3, inv, packed);
+      const int pad = L.NT1 * kMfmaNeur - L.Fp;
+      if (pad > 0) {
+        const int64_t total = (int64_t)L.E_res * L.P * (L.D / kBK) * pad * 2 * kChunksPerRow;
+        pack_w13_padding_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(L, packed);
+      }
+    }
     pack_mfma_kernel<<<grid, block, 0, s>>>(L, (const uint16_t*)w1, (const uint16_t*)w3, (const uint16_t*)w2,
                                             (const uint16_t*)sw1, (const uint16_t*)sw3, (const uint16_t*)sw2, perm, packed,
-                                            n_shared, F_sh > 0 ? F_sh : 1);
+                                            n_shared, F_sh > 0 ? F_sh : 1, columns ? 1 : 0);
   } else if (L.dtype == DSMOE_F32) {
     pack_generic_kernel<float><<<grid, block, 0, s>>>(L, (const float*)w1, (const float*)w3, (const float*)w2,
                                                       (const float*)sw1, (const float*)sw3, (const float*)sw2, perm, packed,
