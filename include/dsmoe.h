@@ -29,6 +29,8 @@
  *   - A context keeps a little host-side state per call (profiling events, the last plan's row
  *     layout): host threads must not call into the SAME context at the same time.  Several
  *     contexts, each with its own workspace, may run concurrently on different streams.
+ *   - The library reads no environment variable; which kernels a context runs follows from its
+ *     dsmoe_config alone (see dsmoe_uses_mfma).
  */
 #ifndef DSMOE_H
 #define DSMOE_H

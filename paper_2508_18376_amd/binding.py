@@ -9,7 +9,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.environ.get("DSMOE_LIB") or os.path.join(_HERE, "libdsmoe.so")  # DSMOE_LIB: another build of the same ABI
+_LIB_PATH = os.path.join(_HERE, "libdsmoe.so")  # the in-tree build, nothing else
 
 DSMOE_F32, DSMOE_BF16 = 0, 1
 DSMOE_PLAN_FIELDS = 12

@@ -43,9 +43,8 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.dtype = c.dtype;
   L.max_tokens = c.max_tokens;
 
-  const char* force = getenv("DSMOE_FORCE_GENERIC");
   L.mfma = (c.dtype == DSMOE_BF16 && L.D % kBK == 0 && L.Fp % kBK == 0 && (L.n_shared == 0 || L.F_shT % kBK == 0) &&
-            (int64_t)c.max_tokens * L.D * 2 < ((int64_t)1 << 31) && !(force && force[0] == '1'))
+            (int64_t)c.max_tokens * L.D * 2 < ((int64_t)1 << 31))
                ? 1
                : 0;
   const int64_t elem = c.dtype == DSMOE_F32 ? 4 : 2;
@@ -138,7 +137,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   const int64_t need_check = ((int64_t)L.E_res * L.F + 1) * 4;
   if (q < need_check) q = align_up(need_check, 256);
   L.packed_bytes = q;
-  L.router_mfma = (c.dtype == DSMOE_BF16 && L.D % 64 == 0 && !(force && force[0] == '1')) ? 1 : 0;
+  L.router_mfma = (c.dtype == DSMOE_BF16 && L.D % 64 == 0) ? 1 : 0;
   L.router_bytes = L.router_mfma ? (int64_t)L.D * ((L.E + 31) / 32 * 32) * 2 : (int64_t)L.D * L.E * 4;
   return true;
 }
@@ -234,12 +233,12 @@ int moe_route_and_mask(dsmoe_ctx* ctx_, const float* logits, int32_t T, const fl
 
 // The layer's kernel sequence.  router_packed != nullptr: the logits are computed first (into
 // logits_buf) from x and the packed gating weights; otherwise logits_buf holds the caller's logits.
-static int forward_impl(Ctx* ctx, const void* packed, const char* router_packed, const void* x, const float* logits_buf,
-                        const float* tau, int32_t T, void* y, void* workspace, void* stream) {
+static int forward_impl(Ctx* ctx, const Layout& base, const void* packed, const char* router_packed, const void* x,
+                        const float* logits_buf, const float* tau, int32_t T, void* y, void* workspace, void* stream) {
   // The shared experts' rows come first in the row space and the routed rows start at the next
   // tile boundary after the T rows of THIS call (the plan kernel places them there), so the layout
   // every kernel of the call sees carries that boundary, not the one max_tokens would give.
-  Layout L = ctx->L;
+  Layout L = base;
   L.sh_rows = L.n_shared > 0 ? (int)align_up(T, L.BM) : 0;
   ctx->last_sh_rows = L.sh_rows;
   const float* logits = logits_buf;
@@ -287,7 +286,7 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
   if (T > 0 && (!x || !logits || !y)) return DSMOE_EINVAL;
   if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0) return DSMOE_EINVAL;
   if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
-  return forward_impl(ctx, packed, nullptr, x, logits, tau, T, y, workspace, stream);
+  return forward_impl(ctx, ctx->L, packed, nullptr, x, logits, tau, T, y, workspace, stream);
 }
 
 int moe_pack_router(dsmoe_ctx* ctx_, const void* wg, void* router_packed, void* stream) {
@@ -316,7 +315,7 @@ int moe_dualsparse_forward_routed(dsmoe_ctx* ctx_, const void* packed, const voi
   if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0 || ((uintptr_t)router_packed & 15) != 0) return DSMOE_EINVAL;
   if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
   float* lbuf = logits_out ? logits_out : (float*)((char*)workspace + ctx->L.o_logits);
-  return forward_impl(ctx, packed, (const char*)router_packed, x, lbuf, tau, T, y, workspace, stream);
+  return forward_impl(ctx, ctx->L, packed, (const char*)router_packed, x, lbuf, tau, T, y, workspace, stream);
 }
 
 int moe_transform_complete(dsmoe_ctx* ctx_, const void* wg, const void* w1, const void* w3, const void* w2,

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/dsmoe.h"
 
 namespace dsmoe {
@@ -74,6 +76,26 @@ struct Layout {
   // packed weights byte offsets
   int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes, router_bytes;
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
+};
+
+// A set-up step that HIP keeps per device (hipFuncSetAttribute, hipGetSymbolAddress): run once for
+// every device, with that device current, from whichever host thread gets there first.
+constexpr int kMaxDevices = 64;
+struct PerDeviceOnce {
+  std::mutex mu;
+  bool done[kMaxDevices] = {};
+  template <class F>
+  hipError_t run(F&& f) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return f();  // beyond the table: every time
+    std::lock_guard<std::mutex> g(mu);
+    if (done[dev]) return hipSuccess;
+    e = f();
+    if (e == hipSuccess) done[dev] = true;
+    return e;
+  }
 };
 
 constexpr int kNumKernels = 7;  // router (if any), route, plan, scatter, gemm1, gemm2, combine

@@ -560,9 +560,7 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   }
 }
 
-static hipError_t set_lds_attr() {
-  static bool attr_set = false;
-  if (attr_set) return hipSuccess;
+static hipError_t set_lds_attr_now() {
   const struct {
     const void* fn;
     int bytes;
@@ -574,8 +572,11 @@ static hipError_t set_lds_attr() {
     hipError_t e = hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.bytes);
     if (e != hipSuccess) return e;
   }
-  attr_set = true;
   return hipSuccess;
+}
+static hipError_t set_lds_attr() {
+  static PerDeviceOnce once;
+  return once.run(set_lds_attr_now);
 }
 
 // grids are whole chunks of 256 blocks so that the XCD remap is a bijection

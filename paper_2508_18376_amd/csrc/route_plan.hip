@@ -721,12 +721,9 @@ hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
   const int NG = E_tot * L.P;
   size_t sh = sizeof(int32_t) * (size_t)(L.nbins + 4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + kPlanTilesLds + 8);
   if (sh > 48 * 1024) {  // hundreds of experts x 8 parts: up to ~78 KB, above what a launch gets without asking
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)plan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 104 * 1024);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    static PerDeviceOnce once;
+    hipError_t e = once.run([] { return hipFuncSetAttribute((const void*)plan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 104 * 1024); });
+    if (e != hipSuccess) return e;
   }
   plan_kernel<<<dim3(1), dim3(kPlanThreads), sh, s>>>(L, T, ws);
   return hipGetLastError();

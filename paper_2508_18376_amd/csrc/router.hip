@@ -138,12 +138,9 @@ template <int NT, int W>
 static hipError_t launch_router_mfma(const Layout& L, int T, const uint4* wgp, const void* x, float* logits, int NT_all,
                                      hipStream_t s) {
   constexpr int lds = W * NT * 16 * 64 * 4;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)router_mfma_kernel<NT, W>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static PerDeviceOnce once;  // one per instantiation
+  hipError_t e = once.run([] { return hipFuncSetAttribute((const void*)router_mfma_kernel<NT, W>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); });
+  if (e != hipSuccess) return e;
   const dim3 grid((unsigned)((T + kRouterTokens - 1) / kRouterTokens), (unsigned)((NT_all + NT - 1) / NT));
   router_mfma_kernel<NT, W><<<grid, dim3(W * 64), lds, s>>>((const uint16_t*)x, wgp, logits, T, L.D, L.E, NT_all);
   return hipGetLastError();
