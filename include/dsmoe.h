@@ -50,7 +50,7 @@ typedef enum {
   DSMOE_OK = 0,
   DSMOE_EINVAL = -1, /* bad shape, divisibility, limit, NULL pointer, T > max_tokens */
   DSMOE_EPERM = -2,  /* perm is not a permutation of 0..d_ff-1 for some expert */
-  DSMOE_ENOSPC = -3, /* reserved: workspace too small */
+  DSMOE_ENOSPC = -3, /* moe_dualsparse_forward_static: the batch does not fit the static scratch array */
   DSMOE_EHIP = -4    /* a HIP call or kernel launch failed; see dsmoe_last_hip_error */
 } dsmoe_status;
 
@@ -127,6 +127,29 @@ int moe_route_and_mask(dsmoe_ctx* ctx, const float* logits, int32_t T, const flo
  */
 int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, const float* tau,
                            int32_t T, void* y, void* workspace, void* stream);
+
+/*
+ * moe_dualsparse_forward for callers that cannot allocate or hand over device memory for a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and same results as moe_dualsparse_forward, minus the workspace: the
+ * kernels use a static array of DSMOE_STATIC_SCRATCH_BYTES of device memory that is part of the
+ * loaded library (every GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing and does not synchronise.
+ *   - The workspace is laid out for this call's T (not for cfg.max_tokens); a batch that needs more
+ *     than the array returns DSMOE_ENOSPC and launches nothing.  dsmoe_static_workspace_need(ctx, T)
+ *     tells the bytes a batch of T tokens takes (0 for an invalid argument).  Decode-sized batches of
+ *     the large layers fit (a Mixtral-shaped layer up to about a thousand tokens).
+ *   - The first call on a device looks the array's address up (no allocation, but a runtime query):
+ *     make one call with T = 0 before a graph capture starts.
+ *   - Every call on a GPU uses that GPU's one array and overwrites what the last call left: calls
+ *     that overlap in time on one GPU (two streams, two host threads, two contexts) race.  Run them
+ *     one after the other, or give the overlapping ones moe_dualsparse_forward with own workspaces.
+ *   - dsmoe_plan_layout describes the caller's workspace, not this array.
+ */
+#define DSMOE_STATIC_SCRATCH_BYTES (256u << 20)
+int moe_dualsparse_forward_static(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, const float* tau,
+                                  int32_t T, void* y, void* stream);
+size_t dsmoe_static_workspace_need(const dsmoe_ctx* ctx, int32_t T);
 
 /*
  * Gating logits l = x W_g (Sec. 3.1, first equation; the input of Eq. 1).

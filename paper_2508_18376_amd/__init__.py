@@ -23,6 +23,9 @@ _BINDING_NAMES = (
     "moe_partition_weights",
     "moe_route_and_mask",
     "moe_dualsparse_forward",
+    "moe_dualsparse_forward_static",
+    "dsmoe_static_workspace_need",
+    "DSMOE_STATIC_SCRATCH_BYTES",
     "moe_profile_importance",
     "moe_importance_to_perm",
     "moe_select_thresholds",

@@ -57,6 +57,10 @@ def _load() -> ctypes.CDLL:
     L.moe_route_and_mask.restype = ctypes.c_int
     L.moe_dualsparse_forward.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp]
     L.moe_dualsparse_forward.restype = ctypes.c_int
+    L.moe_dualsparse_forward_static.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
+    L.moe_dualsparse_forward_static.restype = ctypes.c_int
+    L.dsmoe_static_workspace_need.argtypes = [vp, i32]
+    L.dsmoe_static_workspace_need.restype = ctypes.c_size_t
     L.moe_profile_importance.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
     L.moe_profile_importance.restype = ctypes.c_int
     L.moe_importance_to_perm.argtypes = [vp, vp, vp, vp]
@@ -177,6 +181,18 @@ def moe_dualsparse_forward(ctx, packed, x, logits, tau, T, y, workspace, stream=
     rc = _lib.moe_dualsparse_forward(ctx, _ptr(packed), _ptr(x), _ptr(logits), _ptr(tau), int(T), _ptr(y), _ptr(workspace),
                                      _stream(stream))
     _check(rc, ctx, "moe_dualsparse_forward")
+
+
+def moe_dualsparse_forward_static(ctx, packed, x, logits, tau, T, y, stream=None) -> None:
+    rc = _lib.moe_dualsparse_forward_static(ctx, _ptr(packed), _ptr(x), _ptr(logits), _ptr(tau), int(T), _ptr(y), _stream(stream))
+    _check(rc, ctx, "moe_dualsparse_forward_static")
+
+
+def dsmoe_static_workspace_need(ctx, T) -> int:
+    return int(_lib.dsmoe_static_workspace_need(ctx, int(T)))
+
+
+DSMOE_STATIC_SCRATCH_BYTES = 256 << 20
 
 
 def moe_profile_importance(ctx, packed, x, logits, T, metric, importance, workspace, stream=None) -> None:

@@ -147,6 +147,36 @@ inline int hip_fail(Ctx* ctx, hipError_t e) {
   return DSMOE_EHIP;
 }
 
+// Workspace of moe_dualsparse_forward_static: device memory that belongs to the loaded library, one
+// copy per GPU, held until the process ends.  In host code the array's name only stands for the
+// symbol; the device address of the current GPU's copy comes from hipGetSymbolAddress and is kept
+// per device in g_scratch_ptr.  Nothing in it has to start at zero: every kernel of the layer
+// writes what a later one reads.
+static __device__ __align__(256) unsigned char scratch[DSMOE_STATIC_SCRATCH_BYTES];
+void* g_scratch_ptr[kMaxDevices] = {};
+PerDeviceOnce g_scratch_once;
+
+// device address of the current GPU's scratch array (looked up on the first call per device)
+hipError_t static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  e = g_scratch_once.run([dev] {
+    void* p = nullptr;
+    hipError_t e2 = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e2 == hipSuccess && p == nullptr) e2 = hipErrorInvalidSymbol;
+    if (e2 == hipSuccess) g_scratch_ptr[dev] = p;
+    return e2;
+  });
+  if (e != hipSuccess) return e;
+  {
+    std::lock_guard<std::mutex> g(g_scratch_once.mu);  // pairs with the write above
+    *out = g_scratch_ptr[dev];
+  }
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -184,7 +214,7 @@ const char* dsmoe_strerror(int status) {
     case DSMOE_OK: return "ok";
     case DSMOE_EINVAL: return "invalid argument (shape, divisibility, limit, null pointer or T > max_tokens)";
     case DSMOE_EPERM: return "perm is not a permutation of the expert's neurons";
-    case DSMOE_ENOSPC: return "workspace too small";
+    case DSMOE_ENOSPC: return "the batch needs more workspace than the library's static scratch array holds";
     case DSMOE_EHIP: return "HIP call or kernel launch failed";
     default: return "unknown dsmoe status";
   }
@@ -287,6 +317,38 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx_, const void* packed, const void* x, c
   if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)packed & 15) != 0) return DSMOE_EINVAL;
   if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
   return forward_impl(ctx, ctx->L, packed, nullptr, x, logits, tau, T, y, workspace, stream);
+}
+
+int moe_dualsparse_forward_static(dsmoe_ctx* ctx_, const void* packed, const void* x, const float* logits, const float* tau,
+                                  int32_t T, void* y, void* stream) {
+  Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
+  if (!ctx || T < 0 || !packed || !tau) return DSMOE_EINVAL;
+  if (T > 0 && (!x || !logits || !y)) return DSMOE_EINVAL;
+  if (((uintptr_t)packed & 15) != 0) return DSMOE_EINVAL;
+  if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
+  // the workspace layout of a context made for exactly this batch: the offsets depend on T, so a
+  // small batch of a large layer fits the array even if the context's own max_tokens would not
+  dsmoe_config c = ctx->cfg;
+  c.max_tokens = T > 0 ? T : 1;
+  Layout L;
+  if (!build_layout(c, L)) return DSMOE_EINVAL;
+  // the packed weights were laid out for the context's own layout: the two must agree on the kernels
+  if (L.mfma != ctx->L.mfma || L.packed_bytes != ctx->L.packed_bytes) return DSMOE_EINVAL;
+  if (L.ws_bytes > (int64_t)DSMOE_STATIC_SCRATCH_BYTES) return DSMOE_ENOSPC;
+  void* ws = nullptr;
+  hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  return forward_impl(ctx, L, packed, nullptr, x, logits, tau, T, y, ws, stream);
+}
+
+size_t dsmoe_static_workspace_need(const dsmoe_ctx* ctx_, int32_t T) {
+  const Ctx* ctx = reinterpret_cast<const Ctx*>(ctx_);
+  if (!ctx || T < 0) return 0;
+  dsmoe_config c = ctx->cfg;
+  c.max_tokens = T > 0 ? T : 1;
+  Layout L;
+  if (!build_layout(c, L)) return 0;
+  return (size_t)L.ws_bytes;
 }
 
 int moe_pack_router(dsmoe_ctx* ctx_, const void* wg, void* router_packed, void* stream) {
