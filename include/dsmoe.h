@@ -67,6 +67,14 @@ typedef struct {
   int32_t renorm_combine; /* 0: combine weight = softmax score (Eq. 2); 1: = normalised score */
   int32_t max_tokens;     /* largest T of any later call; sizes the workspace */
   int32_t dtype;          /* dsmoe_dtype of x, weights and y */
+  int32_t y_fp32;         /* 1: y is float [T][D] although dtype is DSMOE_BF16 (the fp32 sum of Eq. 3 is stored
+                             unrounded); 0: y has the layer's dtype.  No effect on DSMOE_F32 layers. */
+  int32_t h_scale_log2;   /* k in [-40, 40], normally 0.  On the matrix-core path the intermediate activation
+                             h = Swish(x W1) * (x W3) is held in half precision as h * 2^k: full precision for
+                             6.1e-5 <= |h| * 2^k <= 65504, saturation above, an absolute error of 3e-8 below.
+                             Layers whose activations are far from 1 in magnitude choose k to centre them.  The
+                             factor is folded into the packed weights and taken out again exactly: it changes
+                             nothing else and costs nothing per call. */
 } dsmoe_config;
 
 /* Validates cfg and builds the host-side context.  No GPU call is made. */
@@ -119,11 +127,15 @@ int moe_route_and_mask(dsmoe_ctx* ctx, const float* logits, int32_t T, const flo
  * the dropped units of Sec. 4 removed).
  *   packed  device, written by moe_partition_weights for this ctx
  *   x       device [T][D] (cfg.dtype), logits device float [T][E], tau device float [E][P]
- *   y       device [T][D] (cfg.dtype), fully overwritten; a token with every unit dropped gets
- *           exact zeros (plus the shared experts' output)
+ *   y       device [T][D] (cfg.dtype, or float if cfg.y_fp32), fully overwritten; a token with every
+ *           unit dropped gets exact zeros (plus the shared experts' output)
  *   workspace device, >= dsmoe_workspace_bytes(ctx), 256-byte aligned; contents need not be
  *           preserved between calls; two calls that overlap in time need two workspaces
- * bf16 layers accumulate in fp32 and round once (the intermediate activation is stored as bf16).
+ * bf16 layers accumulate in fp32 and round the output once.  On the matrix-core path the
+ * intermediate activation Swish(x W1) * (x W3) is stored in IEEE half precision (values beyond
+ * +-65504 saturate) and multiplied with W2 held as half precision times a per-layer power of two,
+ * which represents every bf16 weight within 2^-29 of the largest exactly; bf16 layers on the generic
+ * path (see dsmoe_uses_mfma) keep the activation in fp32.
  */
 int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, const float* tau,
                            int32_t T, void* y, void* workspace, void* stream);
@@ -197,7 +209,7 @@ int moe_transform_complete(dsmoe_ctx* ctx, const void* wg, const void* w1, const
  *   x, logits   device [T][D] / float [T][E]: the calibration tokens
  *   importance  device float [E_res][F], fully overwritten (0 for an expert no token routes to)
  *   workspace   as for moe_dualsparse_forward (its contents are overwritten)
- * bf16 layers store each term as bf16 before the fp32 row sum.  Asynchronous, no allocation.
+ * bf16 layers on the matrix-core path store each term as bf16 before the fp32 row sum.  Asynchronous, no allocation.
  */
 int moe_profile_importance(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, int32_t T,
                            int32_t metric, float* importance, void* workspace, void* stream);

@@ -24,7 +24,7 @@ class DsmoeError(RuntimeError):
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "d_model", "d_ff", "n_experts", "top_k", "n_part", "n_shared", "d_ff_shared", "expert_lo", "expert_hi",
-        "renorm_combine", "max_tokens", "dtype")]
+        "renorm_combine", "max_tokens", "dtype", "y_fp32", "h_scale_log2")]
 
 
 def lib_path() -> str:
@@ -108,9 +108,10 @@ def dsmoe_strerror(status: int) -> str:
 
 
 def dsmoe_create(*, d_model, d_ff, n_experts, top_k, n_part, max_tokens, dtype, n_shared=0, d_ff_shared=0,
-                 expert_lo=0, expert_hi=None, renorm_combine=0) -> ctypes.c_void_p:
+                 expert_lo=0, expert_hi=None, renorm_combine=0, y_fp32=0, h_scale_log2=0) -> ctypes.c_void_p:
     cfg = _Config(d_model, d_ff, n_experts, top_k, n_part, n_shared, d_ff_shared, expert_lo,
-                  n_experts if expert_hi is None else expert_hi, int(renorm_combine), max_tokens, dtype)
+                  n_experts if expert_hi is None else expert_hi, int(renorm_combine), max_tokens, dtype, int(y_fp32),
+                  int(h_scale_log2))
     out = ctypes.c_void_p()
     rc = _lib.dsmoe_create(ctypes.byref(cfg), ctypes.byref(out))
     if rc != 0:
@@ -247,7 +248,8 @@ class DualSparseLayer:
     """Owns a context plus its packed-weight and workspace buffers (torch allocations)."""
 
     def __init__(self, *, d_model, d_ff, n_experts, top_k, n_part, max_tokens, dtype="bf16", n_shared=0, d_ff_shared=0,
-                 expert_lo=0, expert_hi=None, renorm_combine=False, device="cuda:0"):
+                 expert_lo=0, expert_hi=None, renorm_combine=False, y_fp32=False, h_scale_log2=0,
+                 device="cuda:0"):
         self.device = torch.device(device)
         self.dtype = dtype
         self.D, self.F, self.E, self.K, self.P = d_model, d_ff, n_experts, top_k, n_part
@@ -257,10 +259,12 @@ class DualSparseLayer:
         self.ctx = dsmoe_create(d_model=d_model, d_ff=d_ff, n_experts=n_experts, top_k=top_k, n_part=n_part,
                                 max_tokens=max_tokens, dtype=DSMOE_BF16 if dtype == "bf16" else DSMOE_F32,
                                 n_shared=n_shared, d_ff_shared=d_ff_shared, expert_lo=expert_lo, expert_hi=self.hi,
-                                renorm_combine=int(bool(renorm_combine)))
+                                renorm_combine=int(bool(renorm_combine)), y_fp32=int(bool(y_fp32)),
+                                h_scale_log2=h_scale_log2)
         self.packed = torch.empty(dsmoe_packed_bytes(self.ctx), dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(dsmoe_workspace_bytes(self.ctx), dtype=torch.uint8, device=self.device)
-        self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32  # of x and the weights
+        self.y_dtype = torch.float32 if (y_fp32 or dtype != "bf16") else torch.bfloat16
 
     @property
     def uses_mfma(self) -> bool:
@@ -283,7 +287,8 @@ class DualSparseLayer:
 
     def forward(self, x, logits, tau, out=None):
         T = x.shape[0]
-        y = out if out is not None else torch.empty((T, self.D), dtype=self.torch_dtype, device=self.device)
+        y = out if out is not None else torch.empty((T, self.D), dtype=self.y_dtype, device=self.device)
+        assert y.dtype == self.y_dtype
         with torch.cuda.device(self.device):
             moe_dualsparse_forward(self.ctx, self.packed, x, logits, tau, T, y, self.workspace)
         return y
@@ -315,7 +320,7 @@ class DualSparseLayer:
 
     def forward_routed(self, x, tau, want_logits=False):
         T = x.shape[0]
-        y = torch.empty((T, self.D), dtype=self.torch_dtype, device=self.device)
+        y = torch.empty((T, self.D), dtype=self.y_dtype, device=self.device)
         logits = torch.empty((T, self.E), dtype=torch.float32, device=self.device) if want_logits else None
         with torch.cuda.device(self.device):
             moe_dualsparse_forward_routed(self.ctx, self.packed, self.router_packed, x, tau, T, y, logits, self.workspace)

@@ -25,6 +25,8 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   if (c.max_tokens < 1) return false;
   if (c.dtype != DSMOE_F32 && c.dtype != DSMOE_BF16) return false;
   if (c.renorm_combine != 0 && c.renorm_combine != 1) return false;
+  if (c.y_fp32 != 0 && c.y_fp32 != 1) return false;
+  if (c.h_scale_log2 < -40 || c.h_scale_log2 > 40) return false;
   if ((int64_t)c.max_tokens * c.top_k * c.n_part > (int64_t)1 << 30) return false;
   if ((int64_t)c.n_shared * c.d_ff_shared > (int64_t)1 << 30) return false;
 
@@ -41,12 +43,14 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.F_shT = c.n_shared * c.d_ff_shared;
   L.renorm = c.renorm_combine;
   L.dtype = c.dtype;
+  L.y_f32 = (c.dtype == DSMOE_F32 || c.y_fp32) ? 1 : 0;
   L.max_tokens = c.max_tokens;
 
   L.mfma = (c.dtype == DSMOE_BF16 && L.D % kBK == 0 && L.Fp % kBK == 0 && (L.n_shared == 0 || L.F_shT % kBK == 0) &&
             (int64_t)c.max_tokens * L.D * 2 < ((int64_t)1 << 31))
                ? 1
                : 0;
+  L.h_shift = L.mfma ? c.h_scale_log2 : 0;  // the generic path keeps the activation in fp32: nothing to scale
   const int64_t elem = c.dtype == DSMOE_F32 ? 4 : 2;
   L.BM = L.mfma ? kMfmaBM : kGenBM;
   const int neur = L.mfma ? kMfmaNeur : kGenBN;
@@ -99,8 +103,9 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
     o = align_up(o, 2 << 20);
     return take(bytes);
   };
-  L.o_H = take_big((int64_t)(L.row_cap - L.sh_rows) * L.F * elem);
-  L.o_Hs = take_big((int64_t)L.sh_rows * L.F_shT * elem);
+  const int64_t helem = L.mfma ? 2 : 4;  // H: half precision on the MFMA path, fp32 on the generic path
+  L.o_H = take_big((int64_t)(L.row_cap - L.sh_rows) * L.F * helem);
+  L.o_Hs = take_big((int64_t)L.sh_rows * L.F_shT * helem);
   L.o_Yp = take_big((int64_t)L.row_cap * L.D * 4);
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
   L.o_sel = take((int64_t)(L.E + 1) * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both; row E: resident pairs
@@ -125,6 +130,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
     L.p_w2 = takep(L.w2_expert_bytes * L.E_res);
     L.p_sw13 = takep((int64_t)L.NT1_sh * KS1 * kStageBytes);
     L.p_sw2 = takep(L.n_shared > 0 ? (int64_t)L.ND2 * (L.F_shT / kBK) * kStageBytes : 0);
+    L.p_scale = takep(16);
   } else {
     L.w13_expert_bytes = (int64_t)L.D * L.F * elem;
     L.w2_expert_bytes = (int64_t)L.F * L.D * elem;
@@ -301,7 +307,7 @@ static int forward_impl(Ctx* ctx, const Layout& base, const void* packed, const 
   DSMOE_STEP(4, L.mfma ? launch_gemm1_mfma(L, T, (const char*)packed, x, ws, 0, s)
                        : launch_gemm1_generic(L, T, (const char*)packed, x, ws, 0, s));
   DSMOE_STEP(5, L.mfma ? launch_gemm2_mfma(L, T, (const char*)packed, ws, s) : launch_gemm2_generic(L, T, (const char*)packed, ws, s));
-  DSMOE_STEP(6, launch_combine(L, T, ws, y, s));
+  DSMOE_STEP(6, launch_combine(L, T, (const char*)packed, ws, y, s));
   mark(kNumKernels);
 #undef DSMOE_STEP
   if (err != hipSuccess) return hip_fail(ctx, err);
@@ -493,7 +499,7 @@ int moe_profile_importance(dsmoe_ctx* ctx_, const void* packed, const void* x, c
   if (err == hipSuccess)
     err = L.mfma ? launch_gemm1_mfma(L, T, (const char*)packed, x, ws, 1 + metric, s)
                  : launch_gemm1_generic(L, T, (const char*)packed, x, ws, 1 + metric, s);
-  if (err == hipSuccess) err = launch_colsum(L, ws, importance, s);
+  if (err == hipSuccess) err = launch_colsum(L, ws, metric, importance, s);
   if (err != hipSuccess) return hip_fail(ctx, err);
   return DSMOE_OK;
 }

@@ -57,6 +57,8 @@ struct Layout {
   int32_t lo, hi, E_res;      // resident window
   int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
   int32_t renorm, dtype, mfma, router_mfma;
+  int32_t y_f32;  // 1: y is float even though the layer's tensors are bf16
+  int32_t h_shift;  // MFMA path: the intermediate activation is stored times 2^h_shift (folded into the packed W3)
   int32_t g2_rows_inner;  // GEMM-2 item order: 1 = (expert, column tile, row tile), 0 = (expert, row tile, column tile)
   int32_t split_items;  // kSplitItems if GEMM-2 may split K (MFMA path), else 0
   int32_t max_tokens;
@@ -74,7 +76,7 @@ struct Layout {
   int64_t o_tile_bits, o_act_rank, o_items1, o_items2;
   int64_t o_row_token, o_row_bits, o_H, o_Hs, o_Yp, o_tau0, o_sel, o_logits, o_perm_check, o_pool, o_split_of, ws_bytes;
   // packed weights byte offsets
-  int64_t p_w13, p_w2, p_sw13, p_sw2, packed_bytes, router_bytes;
+  int64_t p_w13, p_w2, p_sw13, p_sw2, p_scale, packed_bytes, router_bytes;  // p_scale: the W2 scale record (MFMA layout)
   int64_t w13_expert_bytes, w2_expert_bytes;  // strides between experts (mfma layout)
 };
 
@@ -140,7 +142,7 @@ hipError_t launch_route(const Layout& L, const float* logits, int T, const float
                         uint8_t* keep, int32_t* bin_count, int32_t* group_count, hipStream_t s, bool whole_router_scores = false);
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s);
 hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s);
-hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s);
+hipError_t launch_combine(const Layout& L, int T, const char* packed, char* ws, void* y, hipStream_t s);
 // epi: what GEMM-1 stores per (row, neuron): 0 = Swish(gate)*up (the layer), 1..4 = the profiling
 // metrics Swish(gate), |Swish(gate)|, Swish(gate)*up, |Swish(gate)*up|
 hipError_t launch_gemm1_generic(const Layout& L, int T, const char* packed, const void* x, char* ws, int epi, hipStream_t s);
@@ -155,7 +157,7 @@ hipError_t launch_transform_complete(const Layout& L, const void* wg, const void
                                      hipStream_t s);
 hipError_t launch_drop_rate_thresholds(const Layout& L, int T, float rate, const int32_t* offset_bins, char* ws, float* tau,
                                        int32_t* stats, hipStream_t s);
-hipError_t launch_colsum(const Layout& L, const char* ws, float* importance, hipStream_t s);
+hipError_t launch_colsum(const Layout& L, const char* ws, int metric, float* importance, hipStream_t s);
 hipError_t launch_perm_from_importance(const Layout& L, const float* importance, int32_t* perm, hipStream_t s);
 hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* ws, hipStream_t s);
 hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const void* w2, const void* sw1, const void* sw3,

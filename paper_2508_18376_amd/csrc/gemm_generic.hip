@@ -1,6 +1,6 @@
 // Generic grouped GEMM path: fp32 accumulation on the vector ALUs, any D and F/P.
 // Used for fp32 layers (where it is the full-precision path) and for bf16 layers whose shape the
-// MFMA kernels do not cover.  Same work lists, same row lists, same math as the MFMA path:
+// MFMA kernels do not cover.  The intermediate activation H is fp32 here whatever the layer's type.  Same work lists, same row lists, same math as the MFMA path:
 //   GEMM-1  H[row][p*Fp + j] = Swish(x_row . W1[:, j]) * (x_row . W3[:, j])      (Eq. 4, gate/up)
 //   GEMM-2  Yp[row][d] = sum over kept partitions p, neurons j of H[row][p*Fp+j] * W2[p*Fp+j][d]
 // with the neurons already in permuted order (Sec. 4.2 b) and split into P slices (Sec. 3.2).
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void gemm1_generic_kernel(Layout L, const char
   const int ncols = min(kGenBN, Fp - it.jt * kGenBN);
   const T* w1 = sh ? (const T*)(packed + L.p_sw13) : (const T*)(packed + L.p_w13) + (size_t)it.e * L.D * L.F;
   const T* w3 = w1 + (sh ? (size_t)L.D * L.F_shT : (size_t)L.E_res * L.D * L.F);
-  T* H = sh ? (T*)(ws + L.o_Hs) : (T*)(ws + L.o_H);
+  float* H = sh ? (float*)(ws + L.o_Hs) : (float*)(ws + L.o_H);
   const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
 
   __shared__ float As[GK][kGenBM + 1];
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void gemm1_generic_kernel(Layout L, const char
       int c = tx * 4 + j;
       if (c >= ncols) continue;
       float h = kept ? epi_value<false>(epi, a1[i][j], a3[i][j]) : 0.f;
-      stf<T>(H, (size_t)(hrow0 + r) * ld + col0 + c, h);
+      H[(size_t)(hrow0 + r) * ld + col0 + c] = h;
     }
   }
 }
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void gemm2_generic_kernel(Layout L, const char
   const int ld = sh ? L.F_shT : L.F;
   const int Fp = sh ? L.F_shT : L.Fp;
   const T* w2 = sh ? (const T*)(packed + L.p_sw2) : (const T*)(packed + L.p_w2) + (size_t)it.e * L.F * L.D;
-  const T* H = sh ? (const T*)(ws + L.o_Hs) : (const T*)(ws + L.o_H);
+  const float* H = sh ? (const float*)(ws + L.o_Hs) : (const float*)(ws + L.o_H);
   const int hrow0 = sh ? it.row0 : it.row0 - L.sh_rows;
   float* Yp = (float*)(ws + L.o_Yp);
   const int d0 = it.jd * kGenBN;
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) void gemm2_generic_kernel(Layout L, const char
         int q = tid + i * 256;
         int r = q / GK, kk = q % GK;
         float v = 0.f;
-        if (r < it.nrows && k0 + kk < Fp) v = ldf<T>(H, (size_t)(hrow0 + r) * ld + p * Fp + k0 + kk);
+        if (r < it.nrows && k0 + kk < Fp) v = H[(size_t)(hrow0 + r) * ld + p * Fp + k0 + kk];
         As[kk][r] = v;
         int kb = q / kGenBN, c = q % kGenBN;
         float b = 0.f;

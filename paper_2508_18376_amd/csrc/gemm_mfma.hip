@@ -18,6 +18,11 @@
 // ring twice as deep, for batches so small that the kernel only streams weights.
 // GEMM-2 feeds the weight fragment as the MFMA's A operand, so that a lane ends up with four
 // consecutive output columns of a row.
+// Number formats: GEMM-1 multiplies bf16 by bf16 (x and W1 / W3 as the caller stores them).  The
+// intermediate activation H is kept as IEEE half precision (11 significant bits; bf16's 8 cost
+// up to 2e-2 of the output RMS on the largest outputs of a batch), so GEMM-2 is the f16 MFMA of
+// the same shape and rate, over W2 converted once, exactly, to half precision times a power of
+// two by moe_partition_weights.  |H| beyond 65504 saturates.
 //
 // Operand tiles [256][32] bf16 travel HBM/L2 -> LDS by buffer loads that write LDS directly (no
 // registers in between), through a ring of 4 stages (4 x 32 KiB of the CU's 160 KiB LDS), three
@@ -33,6 +38,8 @@
 namespace dsmoe {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
@@ -53,6 +60,7 @@ constexpr int64_t kStreamOutBytes = 192ll << 20;    // GEMM-2 outputs larger tha
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
 constexpr int kRowBytes = kBK * 2;                  // one tile row in LDS: 64 bytes
+constexpr float kHalfMax = 65504.f;                 // largest finite half-precision value
 
 __device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t bytes) {
   // buffer descriptor: base address (48 bits), stride 0, size in bytes, format flags
@@ -117,7 +125,9 @@ struct Frags {
 // I+J LDS reads per substep and up to 8 DMA loads.  With one wavefront per SIMD nothing else hides
 // an instruction that stalls the stream, so the reads and loads are threaded between the MFMAs by
 // hand and pinned with scheduling barriers.
-template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false, int NS = kStages, int SB = kStagePair, int BOFF = kStageBytes>
+// F16: the operands are half precision (GEMM-2) instead of bf16; the fragments are 16 bytes either way.
+template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false, int NS = kStages, int SB = kStagePair, int BOFF = kStageBytes,
+          bool F16 = false>
 struct WaveTile {
   static_assert(I * J == 16 || I * J == 8, "256 or 128 accumulator registers");
   static constexpr int M = I * J;  // MFMAs per K substep
@@ -172,9 +182,13 @@ struct WaveTile {
 #pragma unroll
     for (int m = 0; m < M; ++m) {
       const int i = m / J, j = m % J;
-      if (act_i(i) && act_j(j))
-        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j], cur.a[i], acc[i][j], 0, 0, 0)
-                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      if (act_i(i) && act_j(j)) {
+        const bf16x8 fa = SWAP ? cur.b[j] : cur.a[i], fb = SWAP ? cur.a[i] : cur.b[j];
+        if (F16)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa), __builtin_bit_cast(f16x8, fb), acc[i][j], 0, 0, 0);
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[i][j], 0, 0, 0);
+      }
       if (M == 16) {  // a DMA slot after every second MFMA, or after every one of 8
         if (DMA && (m & 1) && (m >> 1) < NLOADS) one(m >> 1);
       } else {
@@ -294,7 +308,8 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   t.mainloop(g.KS1, begin, one, lds);
 
   // epilogue.  acc[i][j][v]: weight row a_row0 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row
-  // b_row0 + j*32 + lane%32.  Swish(gate) * up is rounded to bf16 and parked in LDS as a
+  // b_row0 + j*32 + lane%32.  Swish(gate) * up is rounded to half precision (the profiling
+  // metrics to bf16) and parked in LDS as a
   // [256 rows][128 neurons] tile (rows padded to 272 bytes against bank conflicts), then written
   // out in whole 256-byte row segments: 16 lanes per row, 16 bytes per lane.
   constexpr int kHsRow = kMfmaNeur * 2 + 16;
@@ -309,21 +324,31 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
       char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (lane >> 5) * 4) * 2;
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        bf16x2 lo, hi;
+        float h[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const float gt = t.acc[i][j][vq * 4 + c], up = t.acc[i + 1][j][vq * 4 + c];
-          const float h = kept ? epi_value<true>(PROFILE ? g.epi : 0, gt, up) : 0.f;  // Swish(gate) * up (Eq. 4), or a profiling metric
-          if (c < 2) lo[c] = (__bf16)h;
-          else hi[c - 2] = (__bf16)h;
+          h[c] = kept ? epi_value<true>(PROFILE ? g.epi : 0, gt, up) : 0.f;  // Swish(gate) * up (Eq. 4), or a profiling metric
         }
         uint2 pk;
-        pk.x = __builtin_bit_cast(uint32_t, lo);
-        pk.y = __builtin_bit_cast(uint32_t, hi);
+        if (PROFILE) {
+          bf16x2 lo, hi;
+          lo[0] = (__bf16)h[0], lo[1] = (__bf16)h[1], hi[0] = (__bf16)h[2], hi[1] = (__bf16)h[3];
+          pk.x = __builtin_bit_cast(uint32_t, lo);
+          pk.y = __builtin_bit_cast(uint32_t, hi);
+        } else {
+          // half precision, round to nearest: half a unit of the kept 10 fraction bits is added to the
+          // magnitude (fp32 bit pattern + 2^12), then the packed conversion truncates.  Truncation never
+          // yields infinity, so |h| beyond 65504 saturates.
+#pragma unroll
+          for (int c = 0; c < 4; ++c) h[c] = __uint_as_float(__float_as_uint(h[c]) + 0x1000u);
+          pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1]));
+          pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3]));
+        }
         *(uint2*)(srow + vq * 16) = pk;
       }
+      __builtin_amdgcn_sched_barrier(0);  // one block of rows and 32 neurons at a time: keeps the register pressure of the epilogue low
     }
-    __builtin_amdgcn_sched_barrier(0);  // one block of rows at a time: keeps the register pressure of the epilogue low
   }
   __syncthreads();
   const int n_in = g.it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
@@ -420,12 +445,12 @@ struct G2Args {
   int ldy;    // its row stride: D in Yp, 256 in a pool tile
 };
 
-// MFMA A = pair rows of H, B = output columns of W2.
+// MFMA A = pair rows of H, B = output columns of W2 (both half precision).
 template <int I, int J, int NI, bool NT, class RING = RingWhole>
 __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
   asm volatile("" : "+v"(tid));  // see gemm1_tile
   const int lane = tid & 63;
-  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage), true, RING::NS, RING::SB, RING::BOFF> t;
+  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage), true, RING::NS, RING::SB, RING::BOFF, true> t;
   t.init(a_row0, b_row0, lane);
   // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
   // begin() is called with increasing st, so a running cursor maps st -> K position.

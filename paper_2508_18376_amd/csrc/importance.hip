@@ -17,8 +17,9 @@ __device__ __forceinline__ float ld_h<uint16_t>(const uint16_t* p, size_t i) { r
 
 // importance[e][q] = sum over the rows of expert e of H[row][q] (the packed weights must have been
 // made with the identity permutation, so column q of H is original neuron q)
+// unscale: 2^-h_shift for the metrics that contain the up projection (the packed W3 carries 2^h_shift), else 1
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(Layout L, const char* ws, float* importance) {
+__global__ __launch_bounds__(256) void colsum_kernel(Layout L, const char* ws, float* importance, float unscale) {
   const int e = blockIdx.y;
   const int q = blockIdx.x * 256 + threadIdx.x;
   if (q >= L.F) return;
@@ -38,13 +39,14 @@ __global__ __launch_bounds__(256) void colsum_kernel(Layout L, const char* ws, f
     for (int u = 0; u < 8; ++u) acc += v[u];
   }
   for (; r < n; ++r) acc += ld_h<T>(H, (r0 + r) * L.F + q);
-  importance[(size_t)e * L.F + q] = acc;
+  importance[(size_t)e * L.F + q] = acc * unscale;
 }
 
-hipError_t launch_colsum(const Layout& L, const char* ws, float* importance, hipStream_t s) {
+hipError_t launch_colsum(const Layout& L, const char* ws, int metric, float* importance, hipStream_t s) {
   dim3 grid((L.F + 255) / 256, L.E_res), block(256);
-  if (L.dtype == DSMOE_F32) colsum_kernel<float><<<grid, block, 0, s>>>(L, ws, importance);
-  else colsum_kernel<uint16_t><<<grid, block, 0, s>>>(L, ws, importance);
+  const float unscale = metric >= 2 ? ldexpf(1.f, -L.h_shift) : 1.f;
+  if (!L.mfma) colsum_kernel<float><<<grid, block, 0, s>>>(L, ws, importance, unscale);  // the generic path keeps H in fp32
+  else colsum_kernel<uint16_t><<<grid, block, 0, s>>>(L, ws, importance, unscale);
   return hipGetLastError();
 }
 

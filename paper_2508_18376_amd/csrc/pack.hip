@@ -9,7 +9,15 @@
 //   W13  stage ((e*P + p)*NT1 + jt)*(D/32) + ks : 256 weight rows x 32 values of d; weight row
 //        q*64 + gu*32 + j  is neuron  p*Fp + jt*128 + q*32 + j  of W1 (gu=0) or W3 (gu=1): every 64
 //        weight rows hold the gate and the up projection of the same 32 neurons
-//   W2   stage (e*ND2 + jd)*(F/32) + kt : 256 output columns x 32 neurons (positions kt*32..)
+//   W2   stage (e*ND2 + jd)*(F/32) + kt : 256 output columns x 32 neurons (positions kt*32..),
+//        as IEEE half precision times 2^s (GEMM-2 multiplies half-precision operands: its left
+//        operand, the intermediate activation, needs more significant bits than bf16 has).  s is
+//        chosen per layer so that the largest |W2| lands in [2^14, 2^15): every bf16 value within a
+//        factor 2^-29 of the largest is then exactly representable (smaller ones round to the
+//        subnormal grid, 2^-39 of the largest); the combine kernel multiplies by 2^-s, exactly.
+//        The scale record sits at p_scale: uint32 largest |W2| bits, float 2^s, float 2^-(s+k), int32 s.
+//   W3 carries the factor 2^k of cfg.h_scale_log2 (exact in bf16), so that the intermediate activation
+//        comes out of GEMM-1 times 2^k, in the range half precision resolves best, at no run-time cost.
 //   neurons / columns past the end are zero.
 #include "common.h"
 
@@ -61,6 +69,51 @@ __global__ void pack_generic_kernel(Layout L, const T* w1, const T* w3, const T*
   }
 }
 
+// largest finite |w| of a bf16 tensor, as its bit pattern (monotone in the value), into *out
+__global__ __launch_bounds__(256) void absmax_bf16_kernel(const uint16_t* w, int64_t n, uint32_t* out) {
+  uint32_t m = 0;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += (int64_t)gridDim.x * 256 * 8) {
+    if (i + 8 <= n && (((uintptr_t)(w + i)) & 15) == 0) {
+      const uint4 v = *(const uint4*)(w + i);
+      const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t a = u[k] & 0x7fffu, b = (u[k] >> 16) & 0x7fffu;
+        if (a < 0x7f80u && a > m) m = a;
+        if (b < 0x7f80u && b > m) m = b;
+      }
+    } else {
+      for (int64_t k = i; k < n && k < i + 8; ++k) {
+        const uint32_t a = w[k] & 0x7fffu;
+        if (a < 0x7f80u && a > m) m = a;
+      }
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, o, 64));
+  if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
+}
+
+// rec[0] = largest |W2| bits  ->  rec[1] = 2^s, rec[2] = 2^-(s + h_shift), rec[3] = s, with largest * 2^s in
+// [2^14, 2^15).  rec[2] undoes both powers of two the packed weights carry: 2^s in W2 and 2^h_shift in W3.
+__global__ void w2_scale_kernel(uint32_t* rec, int h_shift) {
+  const int e = (int)(rec[0] >> 7);  // biased exponent of the largest value (0: zero or subnormal)
+  int s = e == 0 ? 0 : 14 - (e - 127);
+  s = s < -80 ? -80 : s > 80 ? 80 : s;
+  rec[1] = (uint32_t)(127 + s) << 23;
+  rec[2] = (uint32_t)(127 - s - h_shift) << 23;
+  rec[3] = (uint32_t)s;
+}
+
+// a bf16 value times 2^k (k = L.h_shift), exact unless it leaves bf16's exponent range
+__device__ __forceinline__ uint16_t bf16_shift(uint16_t b, int k) {
+  return k == 0 ? b : f32_to_bf16(ldexpf(bf16_to_f32(b), k));
+}
+
+__device__ __forceinline__ uint16_t bf16_to_scaled_half(uint16_t b, float scale) {
+  const _Float16 h = (_Float16)(bf16_to_f32(b) * scale);  // the product is exact; one rounding (none for values in range)
+  return __builtin_bit_cast(uint16_t, h);
+}
+
 // One thread per 16-byte chunk of the packed MFMA buffers.
 __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w3, const uint16_t* w2,
                                  const uint16_t* sw1, const uint16_t* sw3, const uint16_t* sw2, const int32_t* perm,
@@ -103,11 +156,11 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
           const int pos = p * Fp + nin;
           const int src = perm ? perm[(size_t)e * L.F + pos] : pos;
           const uint16_t* w = gu ? w3 : w1;
-          for (int i = 0; i < 8; ++i) v[i] = w[((size_t)e * L.D + d0 + i) * L.F + src];
+          for (int i = 0; i < 8; ++i) v[i] = bf16_shift(w[((size_t)e * L.D + d0 + i) * L.F + src], gu ? L.h_shift : 0);
         } else {
           const int s = nin / F_sh, n = nin % F_sh;
           const uint16_t* w = gu ? sw3 : sw1;
-          for (int i = 0; i < 8; ++i) v[i] = w[((size_t)s * L.D + d0 + i) * F_sh + n];
+          for (int i = 0; i < 8; ++i) v[i] = bf16_shift(w[((size_t)s * L.D + d0 + i) * F_sh + n], gu ? L.h_shift : 0);
         }
       } else {
         for (int i = 0; i < 8; ++i) v[i] = 0;
@@ -125,15 +178,16 @@ __global__ void pack_mfma_kernel(Layout L, const uint16_t* w1, const uint16_t* w
       const int e = sh ? 0 : (int)(r / L.ND2);
       const int d = jd * kMfmaBN2 + row;
       const int pos0 = kt * kBK + lc * 8;
+      const float w2_scale = ((const float*)(packed + L.p_scale))[1];
       if (d < L.D) {
         for (int i = 0; i < 8; ++i) {
           const int pos = pos0 + i;
           if (!sh) {
             const int src = perm ? perm[(size_t)e * L.F + pos] : pos;
-            v[i] = w2[((size_t)e * L.F + src) * L.D + d];
+            v[i] = bf16_to_scaled_half(w2[((size_t)e * L.F + src) * L.D + d], w2_scale);
           } else {
             const int s = pos / F_sh, n = pos % F_sh;
-            v[i] = sw2[((size_t)s * F_sh + n) * L.D + d];
+            v[i] = bf16_to_scaled_half(sw2[((size_t)s * F_sh + n) * L.D + d], w2_scale);
           }
         }
       } else {
@@ -170,7 +224,7 @@ __global__ __launch_bounds__(256) void pack_w13_columns_kernel(Layout L, const u
     const uint16_t* w = (gu ? w3 : w1) + ((size_t)e * L.D + (size_t)ks * kBK) * L.F + src;
     uint16_t v[kBK];
 #pragma unroll
-    for (int i = 0; i < kBK; ++i) v[i] = w[(size_t)i * L.F];
+    for (int i = 0; i < kBK; ++i) v[i] = bf16_shift(w[(size_t)i * L.F], gu ? L.h_shift : 0);
     const int row = q * 64 + gu * 32 + j;
 #pragma unroll
     for (int lc = 0; lc < kChunksPerRow; ++lc) {
@@ -218,6 +272,13 @@ hipError_t launch_pack(const Layout& L, const void* w1, const void* w3, const vo
                        const void* sw2, const int32_t* perm, char* packed, int n_shared, int F_sh, hipStream_t s) {
   dim3 block(256), grid(256 * 64);
   if (L.mfma) {
+    // the layer's W2 scale (see the layout comment at the top), from the largest |W2| of routed and shared experts
+    uint32_t* rec = (uint32_t*)(packed + L.p_scale);
+    hipError_t e0 = launch_fill_i32((int32_t*)rec, 4, 0, s);
+    if (e0 != hipSuccess) return e0;
+    absmax_bf16_kernel<<<dim3(2048), dim3(256), 0, s>>>((const uint16_t*)w2, (int64_t)L.E_res * L.F * L.D, rec);
+    if (n_shared > 0) absmax_bf16_kernel<<<dim3(512), dim3(256), 0, s>>>((const uint16_t*)sw2, (int64_t)L.F_shT * L.D, rec);
+    w2_scale_kernel<<<dim3(1), dim3(1), 0, s>>>(rec, L.h_shift);
     // The routed W1 / W3 stages are written in source order (see pack_w13_columns_kernel), which
     // needs the inverse permutation: it is parked in the W2 region of the packed buffer, which
     // the last kernel overwrites.  (That region has E_res * F * D * 2 bytes, the table E_res * F * 4.)

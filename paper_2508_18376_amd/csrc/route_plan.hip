@@ -810,8 +810,11 @@ hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s) {
 // ------------------------------------------------------------------------------------- combine
 // y[t] = sum_k g[t][k] * Yp[row(t,k)] (+ Yp[shared row t]); Eq. 3 restricted to the kept units.
 // One writer per output element, slots added in slot order: no atomics.
+// w2_inv: 2^-s, the inverse of the power of two the packed W2 carries (1 on the generic path); the
+// products with it are exact, so the result is the one an unscaled W2 would give.
 template <typename OutT, int KB>
-__global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const char* ws, OutT* y) {
+__global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const char* ws, OutT* y, const float* w2_inv_p) {
+  const float w2_inv = w2_inv_p ? *w2_inv_p : 1.f;
   const float* Yp = (const float*)(ws + L.o_Yp);
   const float* w = (const float*)(ws + L.o_w);
   const int32_t* pair_row = (const int32_t*)(ws + L.o_pair_row);
@@ -826,7 +829,7 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
 #pragma unroll
   for (int k = 0; k < KB; ++k) {
     row[k] = k < L.K ? pair_row[(size_t)t * L.K + k] : -1;
-    g[k] = k < L.K ? w[(size_t)t * L.K + k] : 0.f;
+    g[k] = k < L.K ? w[(size_t)t * L.K + k] * w2_inv : 0.f;
   }
   float4 v[KB];
 #pragma unroll
@@ -859,6 +862,7 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
       if (row[k] >= 0) add_extra(row[k], v[k]);
     if (L.n_shared > 0) add_extra(t, acc);
   }
+  acc.x *= w2_inv, acc.y *= w2_inv, acc.z *= w2_inv, acc.w *= w2_inv;  // the shared experts' rows (weight 1)
 #pragma unroll
   for (int k = 0; k < KB; ++k) {
     if (row[k] >= 0) {
@@ -900,15 +904,16 @@ __global__ __launch_bounds__(256) void combine_scalar_kernel(Layout L, int T, co
   else ((uint16_t*)y)[q] = f32_to_bf16(acc);
 }
 
-hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t s) {
+hipError_t launch_combine(const Layout& L, int T, const char* packed, char* ws, void* y, hipStream_t s) {
   if (T <= 0) return hipSuccess;
+  const float* w2_inv = L.mfma ? (const float*)(packed + L.p_scale) + 2 : nullptr;
   if (L.D % 4 == 0) {
     int64_t n = (int64_t)T * (L.D / 4);
     dim3 grid((unsigned)((n + 255) / 256)), block(256);
 #define DSMOE_COMBINE(KB)                                                                      \
   do {                                                                                          \
-    if (L.dtype == DSMOE_F32) combine_kernel<float, KB><<<grid, block, 0, s>>>(L, T, ws, (float*)y); \
-    else combine_kernel<uint16_t, KB><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y);             \
+    if (L.y_f32) combine_kernel<float, KB><<<grid, block, 0, s>>>(L, T, ws, (float*)y, w2_inv); \
+    else combine_kernel<uint16_t, KB><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y, w2_inv);             \
   } while (0)
     if (L.K <= 2) DSMOE_COMBINE(2);
     else if (L.K <= 4) DSMOE_COMBINE(4);
@@ -918,7 +923,7 @@ hipError_t launch_combine(const Layout& L, int T, char* ws, void* y, hipStream_t
   } else {
     int64_t n = (int64_t)T * L.D;
     dim3 grid((unsigned)((n + 255) / 256)), block(256);
-    if (L.dtype == DSMOE_F32) combine_scalar_kernel<float><<<grid, block, 0, s>>>(L, T, ws, (float*)y);
+    if (L.y_f32) combine_scalar_kernel<float><<<grid, block, 0, s>>>(L, T, ws, (float*)y);
     else combine_scalar_kernel<uint16_t><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y);
   }
   return hipGetLastError();

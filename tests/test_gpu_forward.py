@@ -131,6 +131,36 @@ def test_bf16_layers(oracle, name, spec, tau_kind, mfma):
         assert np.all(y == 0.0)
 
 
+# The matrix-core path keeps the intermediate activation in half precision and W2 as half precision
+# times a power of two chosen from the largest |W2|: layers whose weights or activations are far from
+# the synthetic layers' scale must come out as exactly as those.
+SCALE_CASES = [
+    # (name, weight std, activation std, cfg.h_scale_log2)
+    ("large_weights", 0.6, 1.0, 0),        # |W2| up to ~3; activations of a few hundred
+    ("tiny_weights", 2e-3, 1.0, 0),        # |W2| ~ 1e-2 at most, far below half precision's normal range unscaled
+    ("tiny_activations", 0.02, 0.02, 14),  # h ~ 1e-5: below half precision's normal range unless centred by 2^14
+    ("huge_activations", 0.5, 40.0, -12),  # h up to ~1e6: beyond 65504 unless scaled down
+]
+
+
+@pytest.mark.parametrize("name,w_std,x_std,k", SCALE_CASES, ids=[c[0] for c in SCALE_CASES])
+def test_weight_and_activation_scales_far_from_one(oracle, name, w_std, x_std, k):
+    import torch
+    spec = spec_of(T=600, D=256, F=512, E=4, K=2, P=2, seed=31, w_std=w_std, x_std=x_std)
+    t = make_layer(spec)
+    tau = resolve_tau(oracle, spec, t, "rate0.25")
+    y_ref = oracle_forward(oracle, spec, t, tau)
+    for y_fp32 in (True, False):
+        layer, dev = make_gpu_layer(spec, t, y_fp32=y_fp32, h_scale_log2=k)
+        assert layer.uses_mfma
+        y = layer.forward(dev["x"], dev["logits"], to_dev(tau))
+        torch.cuda.synchronize()
+        err = assert_output_close(to_host64(y, "f32" if y_fp32 else "bf16"), y_ref, "bf16", y_fp32=y_fp32)
+        if y_fp32:
+            assert err < 5e-3, err  # the computation itself is an order of magnitude inside the bar
+        layer.close()
+
+
 def test_partition_and_reorder_invariance_on_gpu(oracle):
     """No drop: the output must not depend on P or on the neuron order (paper Sec. 3.2 identity);
     checked GPU-against-oracle for each variant, and the oracle outputs agree among themselves."""
