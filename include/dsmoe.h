@@ -249,12 +249,13 @@ int moe_select_thresholds(dsmoe_ctx* ctx, const float* logits, int32_t T, const 
  *   Thresholds live on the grid of multiples of 2^-12: tau[e][p] = (b + offset_bins[p]) / 4096, the
  *   same row for every expert.  b is the smallest integer for which at least rate * (resident pairs
  *   * P) units of the pairs routed to the resident experts fall below their threshold.
- *   logits device float [T][E]; rate in [0, 1]; offset_bins HOST int32 [P], each in [-4096, 4096]
+ *   logits device float [T][E]; rate in [0, 1] (the count rate * units is formed in double precision);
+ *   offset_bins HOST int32 [P], each in [-4096, 4096]
  *   (0.01 is 41 grid steps); tau device float [E][P] (output);
  *   stats device int32 [2] (output, may be NULL): dropped units, resident pairs * P.
  *   workspace as for moe_dualsparse_forward (overwritten).  Asynchronous, no allocation.
  */
-int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx, const float* logits, int32_t T, float rate, const int32_t* offset_bins,
+int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx, const float* logits, int32_t T, double rate, const int32_t* offset_bins,
                                  float* tau, int32_t* stats, void* workspace, void* stream);
 
 /*

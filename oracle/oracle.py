@@ -294,7 +294,7 @@ def thresholds_for_drop_rate(logits: np.ndarray, K: int, P: int, rate: float, of
     r = route(logits, K, P, np.zeros((E, P), np.float32))
     n = r.n.astype(np.float32)[(r.idx >= lo) & (r.idx < hi)]
     total = int(n.size) * P
-    need = float(f32(rate)) * total      # the rate is a single-precision argument of the entry point
+    need = rate * total
 
     def dropped(b):
         return sum(int((n < f32(b + k) / f32(n_bins)).sum()) for k in off)

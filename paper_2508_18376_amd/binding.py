@@ -75,7 +75,7 @@ def _load() -> ctypes.CDLL:
     L.moe_dualsparse_forward_routed.restype = ctypes.c_int
     L.moe_transform_complete.argtypes = [vp] * 12
     L.moe_transform_complete.restype = ctypes.c_int
-    L.moe_thresholds_for_drop_rate.argtypes = [vp, vp, i32, ctypes.c_float, ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp]
+    L.moe_thresholds_for_drop_rate.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp]
     L.moe_thresholds_for_drop_rate.restype = ctypes.c_int
     L.moe_select_thresholds.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
     L.moe_select_thresholds.restype = ctypes.c_int
@@ -233,7 +233,7 @@ def moe_transform_complete(ctx, wg, w1, w3, w2, perm, wg_out, w1_out, w3_out, w2
 
 def moe_thresholds_for_drop_rate(ctx, logits, T, rate, offset_bins, tau, stats, workspace, stream=None) -> None:
     off = (ctypes.c_int32 * len(offset_bins))(*[int(v) for v in offset_bins])
-    rc = _lib.moe_thresholds_for_drop_rate(ctx, _ptr(logits), int(T), ctypes.c_float(rate), off, _ptr(tau), _ptr(stats),
+    rc = _lib.moe_thresholds_for_drop_rate(ctx, _ptr(logits), int(T), ctypes.c_double(rate), off, _ptr(tau), _ptr(stats),
                                            _ptr(workspace), _stream(stream))
     _check(rc, ctx, "moe_thresholds_for_drop_rate")
 
@@ -339,8 +339,9 @@ class DualSparseLayer:
 
     def thresholds_for_drop_rate(self, logits, rate, offset_bins=None):
         """tau [E][P] that drops at least `rate` of this batch's resident units, and (dropped, total) units."""
-        if offset_bins is None:  # -0.01 .. +0.01 around the centre, evenly spread (41 grid steps = 0.01)
-            offset_bins = [0] if self.P == 1 else [round(41 * (2 * p - (self.P - 1)) / (self.P - 1)) for p in range(self.P)]
+        if offset_bins is None:  # the policy's default: -0.01 .. +0.01 around the centre (Sec. 4.2 c)
+            from .thresholds import offset_bins as default_offset_bins
+            offset_bins = default_offset_bins(self.P)
         assert len(offset_bins) == self.P
         tau = torch.empty((self.E, self.P), dtype=torch.float32, device=self.device)
         stats = torch.empty((2,), dtype=torch.int32, device=self.device)

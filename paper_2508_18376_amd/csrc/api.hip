@@ -533,10 +533,10 @@ int moe_select_thresholds(dsmoe_ctx* ctx_, const float* logits, int32_t T, const
   return DSMOE_OK;
 }
 
-int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx_, const float* logits, int32_t T, float rate, const int32_t* offset_bins,
+int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx_, const float* logits, int32_t T, double rate, const int32_t* offset_bins,
                                  float* tau, int32_t* stats, void* workspace, void* stream) {
   Ctx* ctx = reinterpret_cast<Ctx*>(ctx_);
-  if (!ctx || T < 0 || !offset_bins || !tau || !workspace || !(rate >= 0.f && rate <= 1.f)) return DSMOE_EINVAL;
+  if (!ctx || T < 0 || !offset_bins || !tau || !workspace || !(rate >= 0.0 && rate <= 1.0)) return DSMOE_EINVAL;
   if (T > 0 && !logits) return DSMOE_EINVAL;
   if (((uintptr_t)workspace & 255) != 0) return DSMOE_EINVAL;
   const Layout& L = ctx->L;

@@ -155,7 +155,7 @@ hipError_t launch_router(const Layout& L, int T, const char* router_packed, cons
 hipError_t launch_transform_complete(const Layout& L, const void* wg, const void* w1, const void* w3, const void* w2,
                                      const int32_t* perm, void* wg_out, void* w1_out, void* w3_out, void* w2_out,
                                      hipStream_t s);
-hipError_t launch_drop_rate_thresholds(const Layout& L, int T, float rate, const int32_t* offset_bins, char* ws, float* tau,
+hipError_t launch_drop_rate_thresholds(const Layout& L, int T, double rate, const int32_t* offset_bins, char* ws, float* tau,
                                        int32_t* stats, hipStream_t s);
 hipError_t launch_colsum(const Layout& L, const char* ws, int metric, float* importance, hipStream_t s);
 hipError_t launch_perm_from_importance(const Layout& L, const float* importance, int32_t* perm, hipStream_t s);

@@ -111,7 +111,7 @@ hipError_t launch_select_thresholds(const Layout& L, int T, const float* tau_max
 struct DropRateArgs {
   int32_t off[kMaxPart];
   int P, E;
-  float rate;
+  double rate;
 };
 __global__ __launch_bounds__(1024) void drop_rate_pick_kernel(const int32_t* __restrict__ h, DropRateArgs a,
                                                               float* __restrict__ tau, int32_t* __restrict__ stats) {
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(1024) void drop_rate_pick_kernel(const int32_t* __r
       omax = max(omax, a.off[p]);
       omin = min(omin, a.off[p]);
     }
-    const double need = (double)a.rate * ((double)pairs * a.P);
+    const double need = a.rate * ((double)pairs * a.P);
     int lo_b = -omax, hi_b = kSelBins + 1 - omin;  // nothing dropped .. everything dropped
     while (lo_b < hi_b) {                          // smallest b with dropped(b) >= need
       const int mid = lo_b + ((hi_b - lo_b) >> 1);
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(1024) void drop_rate_pick_kernel(const int32_t* __r
   }
 }
 
-hipError_t launch_drop_rate_thresholds(const Layout& L, int T, float rate, const int32_t* offset_bins, char* ws, float* tau,
+hipError_t launch_drop_rate_thresholds(const Layout& L, int T, double rate, const int32_t* offset_bins, char* ws, float* tau,
                                        int32_t* stats, hipStream_t s) {
   int32_t* sel = (int32_t*)(ws + L.o_sel);
   const int64_t npairs = (int64_t)T * L.K;

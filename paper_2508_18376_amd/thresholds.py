@@ -20,6 +20,15 @@ def dual_thresholds(tau: float, P: int, delta: float = 0.01) -> np.ndarray:
     return (tau + delta * (2 * p - (P - 1)) / (P - 1)).astype(np.float32)
 
 
+GRID = 4096  # the library's on-device threshold selection works on multiples of 2^-12
+
+
+def offset_bins(P: int, delta: float = 0.01) -> list:
+    """dual_thresholds' offsets around the centre in steps of the library's threshold grid (0.01 = 41
+    steps): the `offset_bins` argument of moe_thresholds_for_drop_rate."""
+    return [int(round(float(v) * GRID)) for v in dual_thresholds(0.0, P, delta).astype(np.float64)]
+
+
 def tau_for_drop_rate(n: np.ndarray, P: int, rate: float, window: float = 0.005, delta: float = 0.01) -> np.ndarray:
     """Per-partition thresholds dropping about `rate` of the (pair, partition) units.
 

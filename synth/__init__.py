@@ -13,6 +13,5 @@ from .layers import (  # noqa: F401
     make_router,
     f32_to_bf16_bits,
     bf16_bits_to_f32,
-    spread_thresholds,
     zipf_logit_bias,
 )

@@ -173,23 +173,6 @@ def make_layer(spec: LayerSpec, weights: bool = True, threads: int = 8) -> Dict[
     return t
 
 
-def spread_thresholds(tau: float, P: int, delta: float = 0.01) -> np.ndarray:
-    """Per-partition thresholds around one drop threshold.
-
-    P=2 gives (tau - delta, tau + delta): the major partition gets the lower threshold and the
-    minor one the higher.  More partitions are spaced evenly between those two ends; P=1 is tau.
-    """
-    if P == 1:
-        return np.array([tau], dtype=np.float32)
-    p = np.arange(P, dtype=np.float64)
-    return (tau + delta * (2 * p - (P - 1)) / (P - 1)).astype(np.float32)
-
-
-def flops_per_unit(spec: LayerSpec) -> float:
-    """Multiply-add flops of one kept (token, expert, partition) unit: three D x Fp products."""
-    return 6.0 * spec.D * (spec.F // spec.P)
-
-
 def _selfcheck() -> None:
     a = np.array([1.0, 1.00390625, 1.01171875, -2.5, 0.0], dtype=np.float32)
     b = bf16_bits_to_f32(f32_to_bf16_bits(a))

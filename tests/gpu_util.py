@@ -4,7 +4,8 @@ from __future__ import annotations
 
 import numpy as np
 
-from synth import LayerSpec, spread_thresholds
+from synth import LayerSpec
+from threshold_util import pick_tau, spread_thresholds  # noqa: F401  (re-exported for the GPU tests)
 
 
 def to_dev(a, device="cuda:0"):
@@ -45,26 +46,6 @@ def tau_table(spec: LayerSpec, v) -> np.ndarray:
 
 
 GUARD = 1e-6  # |n - tau| every test input must keep: ~20x the fp32 evaluation error of n (<= 5e-8 for n <= 1)
-
-
-def pick_tau(n: np.ndarray, P: int, rate: float, window: float = 0.01, delta: float = 0.01) -> np.ndarray:
-    """Thresholds (spread over the P partitions) that drop about `rate` of the units, placed where
-    every partition's threshold is as far as possible from any normalised score in `n`."""
-    if rate <= 0:
-        return np.zeros(P, dtype=np.float32)
-    flat = np.sort(np.asarray(n, dtype=np.float64).ravel())
-    m = flat.size
-    lo = max(int((rate - window) * m), 1)
-    hi = min(int((rate + window) * m), m - 1)
-    cand = 0.5 * (flat[lo - 1:hi] + flat[lo:hi + 1])                     # gap midpoints around the quantile
-    off = (spread_thresholds(0.0, P, delta).astype(np.float64))[None, :]   # per-partition offsets
-    th = (cand[:, None] + off).astype(np.float32).astype(np.float64)       # thresholds as the GPU will see them
-    pos = np.searchsorted(flat, th.ravel()).reshape(th.shape)
-    up = np.abs(flat[np.clip(pos, 0, m - 1)] - th)
-    dn = np.abs(flat[np.clip(pos - 1, 0, m - 1)] - th)
-    margin = np.minimum(up, dn).min(axis=1)
-    best = int(np.argmax(margin))
-    return th[best].astype(np.float32)
 
 
 def rel_err(y_gpu: np.ndarray, y_ref: np.ndarray) -> float:

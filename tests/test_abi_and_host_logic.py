@@ -190,7 +190,7 @@ def test_later_entry_points_validate_before_touching_the_gpu(lib):
     assert lib.moe_select_thresholds(ctx, fake, 4, None, 1, 0, fake, None, fake, None) == -1   # tau_max missing
     assert lib.moe_select_thresholds(ctx, fake, 65, fake, 1, 0, fake, None, fake, None) == -1
     lib.moe_thresholds_for_drop_rate.restype = ctypes.c_int
-    lib.moe_thresholds_for_drop_rate.argtypes = [vp, vp, i32, ctypes.c_float, ctypes.POINTER(i32), vp, vp, vp, vp]
+    lib.moe_thresholds_for_drop_rate.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.POINTER(i32), vp, vp, vp, vp]
     offs = (i32 * 2)(-41, 41)
     assert lib.moe_thresholds_for_drop_rate(ctx, fake, 4, 1.5, offs, fake, None, fake, None) == -1             # rate in [0, 1]
     assert lib.moe_thresholds_for_drop_rate(ctx, fake, 4, float("nan"), offs, fake, None, fake, None) == -1

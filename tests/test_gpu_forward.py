@@ -7,7 +7,8 @@ Tolerances (relative to the RMS of the oracle output): fp32 layers 1e-5, bf16 la
 import numpy as np
 import pytest
 
-from synth import LayerSpec, LAYERS, make_layer, spread_thresholds
+from synth import LayerSpec, LAYERS, make_layer
+from threshold_util import spread_thresholds
 from gpu_util import GUARD, make_gpu_layer, to_dev, to_host64, pick_tau, tau_table, rel_err, assert_output_close, TOL
 
 pytestmark = pytest.mark.gpu

@@ -12,7 +12,8 @@ import numpy as np
 import pytest
 import scipy.special
 
-from synth import LayerSpec, make_layer, f32_to_bf16_bits, bf16_bits_to_f32, spread_thresholds
+from synth import LayerSpec, make_layer, f32_to_bf16_bits, bf16_bits_to_f32
+from threshold_util import spread_thresholds
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -165,9 +166,13 @@ def test_group_counts_recount(oracle):
 
 def test_golden_two_threshold_cases(oracle):
     gold = json.load(open(os.path.join(GOLD, "two_threshold_cases.json")))
+    from paper_2508_18376_amd.thresholds import dual_thresholds, offset_bins
     for pr in gold["printed_pairs"]:
-        th = spread_thresholds(pr["T1"], 2)
-        np.testing.assert_allclose(th, [pr["T_major"], pr["T_minor"]], atol=1e-7)
+        # the tests' own spread rule and the product's policy both reproduce the printed pairs
+        for th in (spread_thresholds(pr["T1"], 2), dual_thresholds(pr["T1"], 2)):
+            np.testing.assert_allclose(th, [pr["T_major"], pr["T_minor"]], atol=1e-7)
+        # and so do the product's grid offsets (multiples of 2^-12) to within half a grid step
+        np.testing.assert_allclose(pr["T1"] + np.array(offset_bins(2)) / 4096.0, [pr["T_major"], pr["T_minor"]], atol=0.5 / 4096)
     for c in gold["cases"]:
         n2 = c["n"]
         logits = np.array([[0.0, math.log(n2 / (1.0 - n2))]], np.float32)  # E = K = 2: scores (1-n2, n2)
@@ -672,7 +677,7 @@ def test_drop_rate_thresholds_follow_the_order_statistics(oracle):
     n32 = np.sort(r.n.astype(np.float32).ravel())
     for rate in (0.1, 0.25, 0.5, 0.9):
         res = oracle.thresholds_for_drop_rate(logits, K, 1, rate, [0], n_bins=B)
-        need = int(np.ceil(float(np.float32(rate)) * n32.size))  # the rate is a single-precision argument
+        need = int(np.ceil(rate * n32.size))
         v = float(n32[need - 1])
         assert res.centre_bin == int(np.floor(v * B)) + 1
         assert res.total_units == n32.size and res.dropped_units >= need
@@ -694,9 +699,9 @@ def test_drop_rate_thresholds_with_partition_offsets_and_window(oracle):
     resident = (rr.idx >= 2) & (rr.idx < 6)
     assert res.total_units == int(resident.sum()) * P
     dropped = int((rr.keep[resident] == 0).sum())
-    assert dropped == res.dropped_units and dropped >= float(np.float32(0.3)) * res.total_units
+    assert dropped == res.dropped_units and dropped >= 0.3 * res.total_units
     one_less = oracle.route(logits, K, P, res.tau - np.float32(1.0 / B), lo=2, hi=6)
-    assert int((one_less.keep[resident] == 0).sum()) < float(np.float32(0.3)) * res.total_units
+    assert int((one_less.keep[resident] == 0).sum()) < 0.3 * res.total_units
     # extremes: rate 0 drops nothing (thresholds <= 0), rate 1 drops everything (thresholds > 1)
     r0 = oracle.thresholds_for_drop_rate(logits, K, P, 0.0, [-41, 41], n_bins=B)
     assert r0.dropped_units == 0 and np.all(r0.tau <= 0)
