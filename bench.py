@@ -1,14 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the DualSparse-MoE layer forward on one MI355X.
 
-One "step" = one moe_dualsparse_forward call (route+mask, row lists, GEMM-1, GEMM-2, combine) on
-the Mixtral-8x7B-shaped synthetic layer (T=4096, D=4096, E=8, F=14336, top-2, P=4) with the inputs
-and packed weights already resident in HBM.  The headline value is tokens/s at about 25 % unit
-drop; the same line carries the 0 / 25 / 50 % sweep (tokens/s, algorithmic TFLOP/s, fraction of the
-bf16 MFMA peak), the roofline of the dominant kernel and the fp64 CPU oracle timed on a token
-sample of the same workload.
+One "step" = one moe_dualsparse_forward call (route+mask, row lists, GEMM-1, GEMM-2, combine) with the
+inputs and packed weights already resident in HBM.  The headline is the Mixtral-8x7B-shaped synthetic
+layer (C2: T=4096, D=4096, E=8, F=14336, top-2, P=4): tokens/s at about 25 % unit drop, the 0 / 25 / 50 %
+sweep (tokens/s, algorithmic TFLOP/s, fraction of the bf16 MFMA peak), the roofline of the dominant
+kernel and the fp64 CPU oracle timed on a token sample of the same workload.  The same JSON line
+carries, under "workloads", the fine-grained layer (C3: 0 / 12.5 / 25 / 50 %), the shared-plus-routed
+layer (C4: about 25 % by the paper's definition) and the skewed expert-parallel share (C5: load-aware
+thresholds with a row cap), each with its per-kernel split.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--sample S] [--no-cpu] [--core-only] [--tokens T]
+Every threshold table that is timed is chosen by the library itself on the device
+(moe_thresholds_for_drop_rate, moe_select_thresholds) from the batch's own scores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--core-only]
+                    [--tokens T] [--rates 0,0.25,0.5] [--no-others]
 """
 import argparse
 import json
@@ -20,7 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor figure
+BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA, vendor figure
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, vendor figure
 
 
@@ -29,7 +35,8 @@ def log(msg):
 
 
 def read_traffic(workload):
-    """HBM bytes per GEMM-1 launch from the committed rocprofv3 counter summary, if there is one."""
+    """HBM-side bytes per GEMM-1 launch from the committed rocprofv3 counter summary of this workload
+    (profiles/), or None: counters cannot be read from inside the timed run."""
     path = os.path.join(ROOT, "profiles", "gemm1_mfma_kernel_%s_hbm_traffic.txt" % workload)
     try:
         for line in open(path):
@@ -38,6 +45,195 @@ def read_traffic(workload):
     except OSError:
         pass
     return None
+
+
+class Workload:
+    """One synthetic layer on the GPU: packed weights, inputs, a routing-only context for counting."""
+
+    def __init__(self, name, tokens, np, torch, ds, keep_host=False):
+        from synth import LAYERS, make_layer
+        self.np, self.torch, self.ds = np, torch, ds
+        self.dev = torch.device("cuda:0")
+        spec = LAYERS[name]
+        if tokens:
+            spec = spec.with_(T=tokens)  # same layer, another batch size (decode-sized batches: 16..256)
+        self.spec = spec
+        t0 = time.time()
+        host = make_layer(spec, threads=16)
+        log("generated %s on the host in %.1f s" % (spec.name, time.time() - t0))
+        self.layer = ds.DualSparseLayer(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P,
+                                        max_tokens=spec.T, dtype=spec.dtype, n_shared=spec.n_shared, d_ff_shared=spec.F_sh,
+                                        expert_lo=spec.lo, expert_hi=spec.hi)
+        assert self.layer.uses_mfma, "the benchmark layers run on the MFMA path"
+        self.x, self.logits = self.up(host["x"]), self.up(host["logits"])
+        wdev = {k: self.up(host.get(k)) for k in ("w1", "w3", "w2", "sh_w1", "sh_w3", "sh_w2", "perm")}
+        t0 = time.time()
+        self.layer.partition_weights(wdev["w1"], wdev["w3"], wdev["w2"], perm=wdev["perm"], sh_w1=wdev["sh_w1"],
+                                     sh_w3=wdev["sh_w3"], sh_w2=wdev["sh_w2"])
+        torch.cuda.synchronize()
+        log("moe_partition_weights (%s): %.3f s" % (spec.name, time.time() - t0))
+        del wdev
+        torch.cuda.empty_cache()
+        self.host = host if keep_host else None
+        # a second context that only routes (normalised scores as weights), for unit counts
+        self.rctx = ds.dsmoe_create(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P,
+                                    max_tokens=spec.T, dtype=1, expert_lo=spec.lo, expert_hi=spec.hi, renorm_combine=1)
+        n_pairs = spec.T * spec.K
+        self.r_idx = torch.empty(n_pairs, dtype=torch.int32, device=self.dev)
+        self.r_w = torch.empty(n_pairs, dtype=torch.float32, device=self.dev)
+        self.r_keep = torch.empty(n_pairs, dtype=torch.uint8, device=self.dev)
+        self.r_gc = torch.empty(spec.E * spec.P, dtype=torch.int32, device=self.dev)
+        self.y = torch.empty((spec.T, spec.D), dtype=torch.bfloat16, device=self.dev)
+        self.stream = torch.cuda.current_stream()
+        tau0 = torch.zeros((spec.E, spec.P), dtype=torch.float32, device=self.dev)
+        self.total_units = self.kept_units(tau0)  # resident routed units with nothing dropped
+        self.Fp = spec.F // spec.P
+        self.unit_flops = 6.0 * spec.D * self.Fp
+        self.shared_flops = 6.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
+        # with shared experts the paper counts them in the denominator of the drop rate (Sec. 5.1)
+        self.shared_units = spec.T * spec.n_shared * spec.P * (spec.F_sh / spec.F) if spec.n_shared else 0.0
+
+    def up(self, a):
+        np, torch = self.np, self.torch
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(self.dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(self.dev)
+
+    def kept_units(self, tau_dev, T=None, logits=None):
+        T = self.spec.T if T is None else T
+        self.ds.moe_route_and_mask(self.rctx, self.logits if logits is None else logits, T, tau_dev, self.r_idx, self.r_w,
+                                   self.r_keep, self.r_gc)
+        self.torch.cuda.synchronize()
+        return int(self.r_gc.sum().item())
+
+    def tau_for_rate(self, rate, T=None, logits=None):
+        """Threshold table for a target drop rate of the resident units, chosen on the device."""
+        spec, torch = self.spec, self.torch
+        if rate <= 0:
+            return torch.zeros((spec.E, spec.P), dtype=torch.float32, device=self.dev)
+        lg = self.logits if logits is None else logits
+        tau, _ = self.layer.thresholds_for_drop_rate(lg if T is None else lg[:T].contiguous(), rate)
+        return tau
+
+    def tau_load_aware(self, tau_max_row, row_cap):
+        """Sec. 4.3 on the device: thresholds scaled by the load ratio of each expert, and lifted where an
+        expert would still keep more than row_cap pairs."""
+        tau, pairs = self.layer.select_thresholds(self.logits, tau_max_row, group_size=1, row_cap=row_cap)
+        return tau
+
+    def run(self, tau_dev, n):
+        for _ in range(n):
+            self.ds.moe_dualsparse_forward(self.layer.ctx, self.layer.packed, self.x, self.logits, tau_dev, self.spec.T, self.y,
+                                           self.layer.workspace, self.stream)
+
+    def timed(self, tau_dev, K, W, profile_level=0):
+        ds, torch = self.ds, self.torch
+        self.run(tau_dev, W)
+        torch.cuda.synchronize()
+        if profile_level:
+            ds.dsmoe_profile_begin(self.layer.ctx, profile_level, K)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        self.run(tau_dev, K)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t_start
+        kms = None
+        if profile_level:
+            kms, calls = ds.dsmoe_profile_end(self.layer.ctx)
+            assert calls == K
+        return dt / K * 1e3, kms
+
+    def record(self, label, tau_dev, K, W, profile_level=0):
+        spec = self.spec
+        units = self.kept_units(tau_dev)
+        ms, kms = self.timed(tau_dev, K, W, profile_level)
+        flops = self.unit_flops * units + self.shared_flops
+        rec = {"case": label, "drop_rate": 1.0 - units / max(self.total_units, 1), "kept_units": units,
+               "drop_rate_incl_shared": (self.total_units - units) / max(self.total_units + self.shared_units, 1),
+               "ms_per_step": ms, "tokens_per_s": spec.T / (ms * 1e-3), "tflops": flops / (ms * 1e-3) / 1e12,
+               "frac_bf16_peak": flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "flops": flops,
+               "tau": [float(v) for v in tau_dev[spec.lo].cpu().numpy()]}
+        log("%s %s: %.3f ms/step, %.0f tokens/s, %.1f TFLOP/s (%.1f %% of bf16 peak), realised drop %.3f"
+            % (spec.name, label, ms, rec["tokens_per_s"], rec["tflops"], 100 * rec["frac_bf16_peak"], rec["drop_rate"]))
+        return rec, kms
+
+    def kernel_table(self, tau_dev, K, W):
+        """Per-kernel split from HIP events between all launches (its own timing pass)."""
+        spec = self.spec
+        units = self.kept_units(tau_dev)
+        _, kms = self.timed(tau_dev, K, W, 2)
+        plan = self.layer.plan(spec.T)
+        pairs_kept = int((plan["pair_row"] >= 0).sum().item())
+        bytes_route = spec.T * spec.E * 4 + spec.T * spec.K * 9
+        bytes_scatter = spec.T * spec.K * 9 + pairs_kept * 5
+        bytes_combine = pairs_kept * spec.D * 4 + spec.T * spec.D * 2 + spec.T * spec.K * 8 \
+            + (spec.T * spec.D * 4 if spec.n_shared else 0)
+        g1_flops = 4.0 * spec.D * self.Fp * units + 4.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
+        g2_flops = 2.0 * spec.D * self.Fp * units + 2.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
+        kernels = {k: {"ms": v} for k, v in kms.items()}
+        kernels["route_mask"]["GBps"] = bytes_route / (kms["route_mask"] * 1e-3) / 1e9
+        kernels["scatter"]["GBps"] = bytes_scatter / (kms["scatter"] * 1e-3) / 1e9
+        kernels["combine"]["GBps"] = bytes_combine / (kms["combine"] * 1e-3) / 1e9
+        kernels["gemm1"]["tflops"] = g1_flops / (kms["gemm1"] * 1e-3) / 1e12
+        kernels["gemm2"]["tflops"] = g2_flops / (kms["gemm2"] * 1e-3) / 1e12
+        return kernels, g1_flops
+
+    def close(self):
+        self.ds.dsmoe_destroy(self.rctx)
+        self.layer.close()
+        del self.layer, self.x, self.logits, self.y
+        self.torch.cuda.empty_cache()
+
+
+def proportionality(zero, rec):
+    """Time saved against the work removed, both relative to the run with nothing dropped."""
+    saved = (zero["ms_per_step"] - rec["ms_per_step"]) / zero["ms_per_step"]
+    removed = 1.0 - rec["flops"] / zero["flops"]
+    return {"time_reduction": saved, "work_reduction": removed, "drop_rate": rec["drop_rate"],
+            "frac_of_proportional": saved / max(removed, 1e-9)}
+
+
+def other_workload(name, np, torch, ds, K, W):
+    """The fine-grained (C3), shared-plus-routed (C4) and skewed expert-parallel (C5) layers."""
+    w = Workload(name, 0, np, torch, ds)
+    spec = w.spec
+    cases = []
+    zero, _ = w.record("0%", w.tau_for_rate(0.0), K, W)
+    cases.append(zero)
+    primary_tau = None
+    if name == "C3":
+        for rate in (0.125, 0.25, 0.5):
+            tau = w.tau_for_rate(rate)
+            rec, _ = w.record("%g%%" % (100 * rate), tau, K, W)
+            rec["proportionality"] = proportionality(zero, rec)
+            cases.append(rec)
+            if rate == 0.25:
+                primary_tau = tau
+    elif name == "C4":
+        # "about 25 %" by the paper's definition (shared experts in the denominator) = a third of the routed units
+        routed_rate = 0.25 * (w.total_units + w.shared_units) / w.total_units
+        primary_tau = w.tau_for_rate(routed_rate)
+        rec, _ = w.record("25% incl. shared", primary_tau, K, W)
+        rec["proportionality"] = proportionality(zero, rec)
+        cases.append(rec)
+    else:  # C5: load-aware thresholds (Sec. 4.3) with the hot expert capped at 1.25 x the balanced share of rows
+        cap = int(1.25 * spec.T * spec.K / spec.E)
+        base = w.tau_for_rate(0.25)
+        primary_tau = w.tau_load_aware(base[spec.lo].contiguous(), cap)
+        rec, _ = w.record("load-aware (25%% thresholds as the maximum, row cap %d)" % cap, primary_tau, K, W)
+        rec["proportionality"] = proportionality(zero, rec)
+        rec["tau_per_resident_expert"] = [[float(v) for v in primary_tau[e].cpu().numpy()] for e in range(spec.lo, spec.hi)]
+        cases.append(rec)
+    kernels, _ = w.kernel_table(primary_tau, K, W)
+    out = {"workload": "%s: T=%d D=%d E=%d F=%d top-%d P=%d%s%s" % (
+        spec.name, spec.T, spec.D, spec.E, spec.F, spec.K, spec.P,
+        (" + %d shared x %d" % (spec.n_shared, spec.F_sh)) if spec.n_shared else "",
+        (" resident experts [%d, %d)" % (spec.lo, spec.hi)) if spec.E_res != spec.E else ""),
+        "cases": [{k: v for k, v in c.items() if k != "flops"} for c in cases], "kernels_at_primary": kernels}
+    w.close()
+    return out
 
 
 def main():
@@ -50,8 +246,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--tokens", type=int, default=0, help="batch size instead of the workload's own (e.g. 64: a decode step)")
     ap.add_argument("--core-only", action="store_true",
-                    help="only the layer's forward pass (no reconstruction / threshold selection / decode / router / "
-                         "transformation timings): what the rocprofv3 summaries are taken from")
+                    help="only the layer's forward pass of --workload (no reconstruction / threshold selection / decode / "
+                         "router / transformation timings, no other workloads): what the rocprofv3 summaries are taken from")
+    ap.add_argument("--no-others", action="store_true", help="skip the C3 / C4 / C5 records")
     ap.add_argument("--rates", default="0,0.25,0.5")
     ap.add_argument("--primary-rate", type=float, default=0.25)
     args = ap.parse_args()
@@ -61,100 +258,24 @@ def main():
 
     import numpy as np
     import torch
-    from synth import LAYERS, make_layer
     import paper_2508_18376_amd as ds
-    from paper_2508_18376_amd.thresholds import tau_for_drop_rate, tau_capping_rows
+    from paper_2508_18376_amd.thresholds import offset_bins
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    spec = LAYERS[args.workload]
-    if args.tokens:
-        spec = spec.with_(T=args.tokens)  # same layer, another batch size (decode-sized batches: 16..256)
     K, W = args.steps, args.warmup
 
-    t0 = time.time()
-    host = make_layer(spec, threads=16)
-    log("generated %s on the host in %.1f s" % (spec.name, time.time() - t0))
-
-    def up(a):
-        if a is None:
-            return None
-        if a.dtype == np.uint16:
-            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
-        return torch.from_numpy(a).to(dev)
-
-    layer = ds.DualSparseLayer(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P,
-                               max_tokens=spec.T, dtype=spec.dtype, n_shared=spec.n_shared, d_ff_shared=spec.F_sh,
-                               expert_lo=spec.lo, expert_hi=spec.hi)
-    assert layer.uses_mfma, "the benchmark layer must run on the MFMA path"
-    x, logits = up(host["x"]), up(host["logits"])
-    wdev = {k: up(host.get(k)) for k in ("w1", "w3", "w2", "sh_w1", "sh_w3", "sh_w2", "perm")}
-    t0 = time.time()
-    layer.partition_weights(wdev["w1"], wdev["w3"], wdev["w2"], perm=wdev["perm"], sh_w1=wdev["sh_w1"], sh_w3=wdev["sh_w3"],
-                            sh_w2=wdev["sh_w2"])
-    torch.cuda.synchronize()
-    log("moe_partition_weights: %.3f s" % (time.time() - t0))
-    del wdev
-    torch.cuda.empty_cache()
-
-    # normalised scores from the GPU's own routing (renorm context, tau = 0) -> thresholds per rate
-    rctx = ds.dsmoe_create(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P, max_tokens=spec.T,
-                           dtype=1, expert_lo=spec.lo, expert_hi=spec.hi, renorm_combine=1)
-    n_pairs = spec.T * spec.K
-    r_idx = torch.empty(n_pairs, dtype=torch.int32, device=dev)
-    r_w = torch.empty(n_pairs, dtype=torch.float32, device=dev)
-    r_keep = torch.empty(n_pairs, dtype=torch.uint8, device=dev)
-    r_gc = torch.empty(spec.E * spec.P, dtype=torch.int32, device=dev)
-    tau0 = torch.zeros((spec.E, spec.P), dtype=torch.float32, device=dev)
-    ds.moe_route_and_mask(rctx, logits, spec.T, tau0, r_idx, r_w, r_keep, r_gc)
-    torch.cuda.synchronize()
-    n_all = r_w.cpu().numpy().reshape(spec.T, spec.K)
-    idx_all = r_idx.cpu().numpy().reshape(spec.T, spec.K)
-    resident = (idx_all >= spec.lo) & (idx_all < spec.hi)
-    n_res = n_all[resident]
+    w = Workload(args.workload, args.tokens, np, torch, ds, keep_host=True)
+    spec, layer, x, logits, stream = w.spec, w.layer, w.x, w.logits, w.stream
+    host = w.host
+    Fp = w.Fp
 
     def tau_for(rate):
-        tab = np.tile(tau_for_drop_rate(n_res, spec.P, rate)[None, :], (spec.E, 1)).astype(np.float32)
-        if spec.name == "C5":  # load-aware cap: the hot expert keeps at most 1.25 x the balanced share of rows
-            cap = int(1.25 * spec.T * spec.K / spec.E)
-            for e in range(spec.lo, spec.hi):
-                ne = n_all[idx_all == e]
-                if ne.size > cap:
-                    tab[e] = np.maximum(tab[e], tau_capping_rows(ne, spec.P, cap))
-        return tab
-
-    def kept_units(tau_dev):
-        ds.moe_route_and_mask(rctx, logits, spec.T, tau_dev, r_idx, r_w, r_keep, r_gc)
-        torch.cuda.synchronize()
-        return int(r_gc.sum().item())
-
-    Fp = spec.F // spec.P
-    unit_flops = 6.0 * spec.D * Fp
-    shared_flops = 6.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
-    total_units = int(resident.sum()) * spec.P
-    y = torch.empty((spec.T, spec.D), dtype=torch.bfloat16, device=dev)
-    stream = torch.cuda.current_stream()
-
-    def run_steps(tau_dev, n):
-        for _ in range(n):
-            ds.moe_dualsparse_forward(layer.ctx, layer.packed, x, logits, tau_dev, spec.T, y, layer.workspace, stream)
-
-    def timed(tau_dev, profile_level):
-        run_steps(tau_dev, W)
-        torch.cuda.synchronize()
-        if profile_level:
-            ds.dsmoe_profile_begin(layer.ctx, profile_level, K)
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        run_steps(tau_dev, K)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t_start
-        kms = None
-        if profile_level:
-            kms, calls = ds.dsmoe_profile_end(layer.ctx)
-            assert calls == K
-        return dt / K * 1e3, kms
+        tau = w.tau_for_rate(rate)
+        if spec.name == "C5" and rate > 0:  # the skewed share is run with the load-aware rule on top
+            tau = w.tau_load_aware(tau[spec.lo].contiguous(), int(1.25 * spec.T * spec.K / spec.E))
+        return tau
 
     rates = [float(r) for r in args.rates.split(",")]
     if args.primary_rate not in rates:
@@ -162,49 +283,29 @@ def main():
     sweep = []
     primary = None
     for rate in rates:
-        tab = tau_for(rate)
-        tau_dev = torch.from_numpy(tab).to(dev)
-        units = kept_units(tau_dev)
+        tau_dev = tau_for(rate)
         is_primary = abs(rate - args.primary_rate) < 1e-9
-        ms, kms = timed(tau_dev, 1 if is_primary else 0)
-        flops = unit_flops * units + shared_flops
-        # with shared experts the paper counts them in the denominator (Sec. 5.1): dropped / (routed + shared)
-        shared_units = spec.T * spec.n_shared * spec.P * (spec.F_sh / spec.F) if spec.n_shared else 0.0
-        rec = {"target_drop": rate, "drop_rate": 1.0 - units / max(total_units, 1), "kept_units": units,
-               "drop_rate_incl_shared": (total_units - units) / max(total_units + shared_units, 1),
-               "ms_per_step": ms, "tokens_per_s": spec.T / (ms * 1e-3), "tflops": flops / (ms * 1e-3) / 1e12,
-               "frac_bf16_peak": flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "tau": [float(v) for v in tab[spec.lo]]}
+        rec, kms = w.record("%g%%" % (100 * rate), tau_dev, K, W, 1 if is_primary else 0)
+        rec["target_drop"] = rate
         sweep.append(rec)
-        log("rate %.3f: %.3f ms/step, %.0f tokens/s, %.1f TFLOP/s (%.1f %% of bf16 peak), realised drop %.3f"
-            % (rate, ms, rec["tokens_per_s"], rec["tflops"], 100 * rec["frac_bf16_peak"], rec["drop_rate"]))
         if is_primary:
             primary = dict(rec)
             primary["gemm1_ms"] = kms["gemm1"]
-            primary["tau_table"] = tab
             primary["tau_dev"] = tau_dev
-    # per-kernel table (separate pass with events between all kernels)
-    _, kms_all = timed(primary["tau_dev"], 2)
-    units = primary["kept_units"]
-    pairs_kept = None
-    plan = layer.plan(spec.T)
-    pairs_kept = int((plan["pair_row"] >= 0).sum().item())
-    bytes_route = spec.T * spec.E * 4 + spec.T * spec.K * 9
-    bytes_scatter = spec.T * spec.K * 9 + pairs_kept * 5
-    bytes_combine = pairs_kept * spec.D * 4 + spec.T * spec.D * 2 + spec.T * spec.K * 8 \
-        + (spec.T * spec.D * 4 if spec.n_shared else 0)
-    g1_flops = 4.0 * spec.D * Fp * units + 4.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
-    g2_flops = 2.0 * spec.D * Fp * units + 2.0 * spec.D * spec.F_sh * spec.n_shared * spec.T
-    kernels = {k: {"ms": v} for k, v in kms_all.items()}
-    kernels["route_mask"]["GBps"] = bytes_route / (kms_all["route_mask"] * 1e-3) / 1e9
-    kernels["scatter"]["GBps"] = bytes_scatter / (kms_all["scatter"] * 1e-3) / 1e9
-    kernels["combine"]["GBps"] = bytes_combine / (kms_all["combine"] * 1e-3) / 1e9
-    kernels["gemm1"]["tflops"] = g1_flops / (kms_all["gemm1"] * 1e-3) / 1e12
-    kernels["gemm2"]["tflops"] = g2_flops / (kms_all["gemm2"] * 1e-3) / 1e12
+            primary["tau_table"] = tau_dev.cpu().numpy()
+    kernels, g1_flops = w.kernel_table(primary["tau_dev"], K, W)
 
     g1_ach = g1_flops / (primary["gemm1_ms"] * 1e-3) / 1e12
+    traffic = read_traffic(spec.name) if not args.tokens else None
     roofline = {"kernel": "gemm1_mfma_kernel", "bound": "mfma", "achieved": g1_ach, "peak": BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": g1_ach / BF16_PEAK_TFLOPS, "traffic": read_traffic(spec.name),
+                "unit": "TFLOP/s", "frac": g1_ach / BF16_PEAK_TFLOPS, "traffic": traffic,
+                "traffic_source": ("profiles/gemm1_mfma_kernel_%s_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier "
+                                   "run of this command; counters are not readable from inside the run)" % spec.name)
+                if traffic is not None else None,
                 "avg_launch_ms": primary["gemm1_ms"], "flops_per_launch": g1_flops}
+
+    zero = next((r for r in sweep if r["target_drop"] == 0.0), None)
+    prop = proportionality(zero, primary) if zero else None
 
     reconstruction = selection = router = transform = None
     decode = []
@@ -227,23 +328,22 @@ def main():
         rec_ms = ev_ms(lambda: ds.moe_profile_importance(layer.ctx, layer.packed, x, logits, spec.T, 3, imp, layer.workspace,
                                                          stream), n_rec)
         perm_ms = ev_ms(lambda: ds.moe_importance_to_perm(layer.ctx, imp, perm_out, stream), n_rec)
-        rec_flops = 4.0 * spec.D * spec.F * int(resident.sum())
+        rec_flops = 4.0 * spec.D * Fp * w.total_units
         reconstruction = {"profile_importance_ms": rec_ms, "profile_importance_tflops": rec_flops / (rec_ms * 1e-3) / 1e12,
                           "importance_to_perm_ms": perm_ms, "calibration_tokens": spec.T, "metric": 3}
         log("reconstruction: importance of %d tokens %.3f ms (%.0f TFLOP/s), order %.3f ms"
             % (spec.T, rec_ms, reconstruction["profile_importance_tflops"], perm_ms))
 
-        # load-aware threshold selection on the device (Sec. 4.3): the step that can feed `tau` every batch
+        # threshold selection on the device (Sec. 4.3, Sec. 5.3.3): the steps that feed `tau` every batch
         tau_sel = torch.empty((spec.E, spec.P), dtype=torch.float32, device=dev)
         pairs_sel = torch.empty((spec.E,), dtype=torch.int32, device=dev)
-        tau_max_dev = torch.from_numpy(np.ascontiguousarray(primary["tau_table"][spec.lo])).to(dev)
+        tau_max_dev = primary["tau_dev"][spec.lo].contiguous()
         cap_rows = int(1.25 * spec.T * spec.K / spec.E)
         sel_ms = ev_ms(lambda: ds.moe_select_thresholds(layer.ctx, logits, spec.T, tau_max_dev, 1, cap_rows, tau_sel, pairs_sel,
                                                         layer.workspace, stream), max(10, K))
-        off_bins = [0] if spec.P == 1 else [round(41 * (2 * p - (spec.P - 1)) / (spec.P - 1)) for p in range(spec.P)]
         stats_sel = torch.empty((2,), dtype=torch.int32, device=dev)
-        rate_ms = ev_ms(lambda: ds.moe_thresholds_for_drop_rate(layer.ctx, logits, spec.T, args.primary_rate, off_bins, tau_sel,
-                                                                stats_sel, layer.workspace, stream), max(10, K))
+        rate_ms = ev_ms(lambda: ds.moe_thresholds_for_drop_rate(layer.ctx, logits, spec.T, args.primary_rate, offset_bins(spec.P),
+                                                                tau_sel, stats_sel, layer.workspace, stream), max(10, K))
         st = stats_sel.cpu().numpy()
         selection = {"select_thresholds_ms": sel_ms, "group_size": 1, "row_cap": cap_rows,
                      "thresholds_for_drop_rate_ms": rate_ms, "target_drop": args.primary_rate,
@@ -255,21 +355,21 @@ def main():
         from synth import make_router
         wg_host = make_router(spec)
         router_packed = torch.empty(max(ds.dsmoe_router_packed_bytes(layer.ctx), 16), dtype=torch.uint8, device=dev)
-        ds.moe_pack_router(layer.ctx, up(wg_host), router_packed, stream)
+        ds.moe_pack_router(layer.ctx, w.up(wg_host), router_packed, stream)
         lg_out = torch.empty((spec.T, spec.E), dtype=torch.float32, device=dev)
         router_ms = ev_ms(lambda: ds.moe_router_logits(layer.ctx, router_packed, x, spec.T, lg_out, stream), max(10, K))
         routed_ms = ev_ms(lambda: ds.moe_dualsparse_forward_routed(layer.ctx, layer.packed, router_packed, x, primary["tau_dev"],
-                                                                   spec.T, y, None, layer.workspace, stream), max(5, K // 2))
+                                                                   spec.T, w.y, None, layer.workspace, stream), max(5, K // 2))
         router_bytes = spec.T * spec.D * 2 + spec.T * spec.E * 4
         router = {"router_logits_ms": router_ms, "GBps": router_bytes / (router_ms * 1e-3) / 1e9,
                   "forward_routed_ms": routed_ms}
         log("router x W_g: %.4f ms (%.0f GB/s of x); layer driven by those logits (another routing, same tau table) %.3f ms"
             % (router_ms, router["GBps"], routed_ms))
         del lg_out
-        w_dev = {k: up(host[k]) for k in ("w1", "w3", "w2")}
+        w_dev = {k: w.up(host[k]) for k in ("w1", "w3", "w2")}
         w_out = {k: torch.empty_like(v) for k, v in w_dev.items()}
-        wg_dev, wg_out = up(wg_host), torch.empty((spec.D, spec.E * spec.P), dtype=torch.bfloat16, device=dev)
-        perm_dev = up(host["perm"])
+        wg_dev, wg_out = w.up(wg_host), torch.empty((spec.D, spec.E * spec.P), dtype=torch.bfloat16, device=dev)
+        perm_dev = w.up(host["perm"])
         tr_ms = ev_ms(lambda: ds.moe_transform_complete(layer.ctx, wg_dev, w_dev["w1"], w_dev["w3"], w_dev["w2"], perm_dev, wg_out,
                                                         w_out["w1"], w_out["w3"], w_out["w2"], layer.workspace, stream), 2)
         w_bytes = sum(v.numel() * 2 for v in w_dev.values())
@@ -278,18 +378,14 @@ def main():
         del w_dev, w_out
 
         # decode-sized batches of the same layer (weight streaming regime): the first T tokens of the batch
-        decode = []
         w_unit_bytes = 3 * spec.D * Fp * 2
         for Td in (16, 64, 256):
             if Td > spec.T:
                 continue
             xd, ld = x[:Td].contiguous(), logits[:Td].contiguous()
-            res_d = resident[:Td]
-            tab = np.tile(tau_for_drop_rate(n_all[:Td][res_d], spec.P, args.primary_rate)[None, :], (spec.E, 1)).astype(np.float32)
-            tau_d = torch.from_numpy(tab).to(dev)
-            ds.moe_route_and_mask(rctx, ld, Td, tau_d, r_idx, r_w, r_keep, r_gc)
-            torch.cuda.synchronize()
-            gc = r_gc.cpu().numpy()
+            tau_d = w.tau_for_rate(args.primary_rate, T=Td)
+            w.kept_units(tau_d, T=Td, logits=ld)
+            gc = w.r_gc.cpu().numpy()
             active = int((gc > 0).sum())
             wbytes = active * w_unit_bytes + 3 * spec.D * spec.F_sh * spec.n_shared * 2
             yd = torch.empty((Td, spec.D), dtype=torch.bfloat16, device=dev)
@@ -304,16 +400,9 @@ def main():
             ms_d = (time.perf_counter() - t_start) / K * 1e3
             decode.append({"tokens": Td, "ms_per_step": ms_d, "tokens_per_s": Td / (ms_d * 1e-3), "active_sub_experts": active,
                            "kept_units": int(gc.sum()), "weight_bytes": wbytes, "GBps": wbytes / (ms_d * 1e-3) / 1e9,
-                           "frac_hbm_peak": wbytes / (ms_d * 1e-3) / 1e9 / 8000.0})
+                           "frac_hbm_peak": wbytes / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBS})
             log("decode T=%d: %.3f ms/step, weights of %d active sub-experts %.2f GB -> %.0f GB/s (%.0f %% of 8 TB/s)"
                 % (Td, ms_d, active, wbytes / 1e9, decode[-1]["GBps"], 100 * decode[-1]["frac_hbm_peak"]))
-
-    # proportionality of the time saved at the primary rate, against the 0 % run
-    t_zero = next((r["ms_per_step"] for r in sweep if r["target_drop"] == 0.0), None)
-    prop = None
-    if t_zero:
-        prop = {"time_reduction": (t_zero - primary["ms_per_step"]) / t_zero, "drop_rate": primary["drop_rate"]}
-        prop["frac_of_proportional"] = prop["time_reduction"] / max(primary["drop_rate"], 1e-9)
 
     # CPU oracle leg: the same layer and thresholds on a seeded token sample, all host cores
     cpu = None
@@ -323,8 +412,9 @@ def main():
         S = args.sample or {"C2": 1536, "C3": 8192, "C4": 6144, "C5": 2048}[spec.name]  # about 10 s of oracle time each
         S = min(S, spec.T)
         tok = np.sort(np.random.default_rng(12345).choice(spec.T, size=S, replace=False)).astype(np.int32)
+        tau_host = primary["tau_table"]
         t0 = time.time()
-        y_ref = oracle.forward(host["x"], host["logits"], host["w1"], host["w3"], host["w2"], primary["tau_table"], spec.K,
+        y_ref = oracle.forward(host["x"], host["logits"], host["w1"], host["w3"], host["w2"], tau_host, spec.K,
                                spec.P, perm=host["perm"], sh_w1=host.get("sh_w1"), sh_w3=host.get("sh_w3"),
                                sh_w2=host.get("sh_w2"), lo=spec.lo, hi=spec.hi, tokens=tok)
         dt = time.time() - t0
@@ -340,38 +430,72 @@ def main():
                "host": {"nproc": os.cpu_count(), "cpu": cpu_model},
                "note": "the oracle as it stands, untuned: a reported baseline, not a competitor",
                "sample": "%d of %d tokens (seeded), whole layer per token, %.1f s" % (S, spec.T, dt)}
-        run_steps(primary["tau_dev"], 1)
+        # the thresholds sit on the device's grid, not in a gap between scores: tokens whose fp32 and fp64
+        # keep decisions could differ (|n - tau| <= 1e-6) are left out of the comparison, and counted
+        margin = oracle.route(host["logits"], spec.K, spec.P, tau_host, spec.lo, spec.hi)
+        n64 = margin.n
+        near = np.zeros(spec.T, dtype=bool)
+        for p in range(spec.P):
+            near |= (np.abs(n64 - tau_host[margin.idx, p].astype(np.float64)) <= 1e-6).any(axis=1)
+        ok_rows = ~near[tok]
+        # the timed output (bf16) and, from the same packed weights, the fp32 output that carries no output rounding
+        w.run(primary["tau_dev"], 1)
+        ctx32 = ds.dsmoe_create(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P, max_tokens=spec.T,
+                                dtype=1, n_shared=spec.n_shared, d_ff_shared=spec.F_sh, expert_lo=spec.lo, expert_hi=spec.hi,
+                                y_fp32=1)
+        y32 = torch.empty((spec.T, spec.D), dtype=torch.float32, device=dev)
+        ds.moe_dualsparse_forward(ctx32, layer.packed, x, logits, primary["tau_dev"], spec.T, y32, layer.workspace, stream)
         torch.cuda.synchronize()
-        y_s = y[torch.from_numpy(tok.astype(np.int64)).to(dev)].to(torch.float32).cpu().numpy().astype(np.float64)
-        rms = float(np.sqrt(np.mean(y_ref ** 2)))
-        aerr = np.abs(y_s - y_ref)
-        # the bf16 output format costs up to 2^-8 |y| by itself; the rest is the computation's error
-        beyond = aerr - 2.0 ** -8 * np.abs(y_ref)
-        check = {"elements": int(aerr.size), "rms_err_over_rms": float(np.sqrt(np.mean(aerr ** 2)) / rms),
-                 "elements_beyond_tolerance": int((beyond > 2e-2 * rms).sum()),
-                 "sample_max_err_over_rms": float(aerr.max() / rms),
-                 "sample_max_err_beyond_bf16_output_rounding_over_rms": float((aerr - 2.0 ** -8 * np.abs(y_ref)).max() / rms),
-                 "tolerance": 2e-2}
-        log("oracle: %.2f tokens/s on %d threads; GPU vs oracle on the sample: max |err| %.4f x RMS, %.4f x RMS beyond the "
-            "rounding of the bf16 output (bar 0.02), %d elements over the bar" % (
-                cpu["value"], cpu["cores"], check["sample_max_err_over_rms"],
-                check["sample_max_err_beyond_bf16_output_rounding_over_rms"], check["elements_beyond_tolerance"]))
+        ds.dsmoe_destroy(ctx32)
+        sel = torch.from_numpy(tok.astype(np.int64)).to(dev)
+        a16 = w.y[sel].to(torch.float32).cpu().numpy().astype(np.float64)[ok_rows]
+        a32 = y32[sel].cpu().numpy().astype(np.float64)[ok_rows]
+        ref = y_ref[ok_rows]
+        rms = float(np.sqrt(np.mean(ref ** 2)))
+        e16, e32 = np.abs(a16 - ref), np.abs(a32 - ref)
+        beyond16 = e16 - 2.0 ** -8 * np.abs(ref)  # the bf16 output format costs up to 2^-8 |y| by itself
+        check = {"elements": int(ref.size), "tolerance": 2e-2, "tokens_left_out_near_a_threshold": int((~ok_rows).sum()),
+                 "fp32_output": {"max_err_over_rms": float(e32.max() / rms), "rms_err_over_rms": float(np.sqrt(np.mean(e32 ** 2)) / rms),
+                                 "elements_beyond_tolerance": int((e32 > 2e-2 * rms).sum())},
+                 "bf16_output": {"max_err_over_rms": float(e16.max() / rms),
+                                 "max_err_beyond_output_rounding_over_rms": float(beyond16.max() / rms),
+                                 "elements_beyond_tolerance_plus_output_rounding": int((beyond16 > 2e-2 * rms).sum())}}
+        log("oracle: %.2f tokens/s on %d threads; GPU vs oracle on the sample: fp32 output max |err| %.4f x RMS (bar 0.02, %d "
+            "elements over); bf16 output %.4f x RMS, %.4f x RMS beyond its own rounding" % (
+                cpu["value"], cpu["cores"], check["fp32_output"]["max_err_over_rms"],
+                check["fp32_output"]["elements_beyond_tolerance"], check["bf16_output"]["max_err_over_rms"],
+                check["bf16_output"]["max_err_beyond_output_rounding_over_rms"]))
+
+    workload_line = "%s: T=%d D=%d E=%d F=%d top-%d P=%d%s, tau for ~%d%% unit drop (realised %.1f%%)" % (
+        spec.name, spec.T, spec.D, spec.E, spec.F, spec.K, spec.P,
+        (" + %d shared x %d" % (spec.n_shared, spec.F_sh)) if spec.n_shared else "",
+        round(100 * args.primary_rate), 100 * primary["drop_rate"])
+    resident = [spec.lo, spec.hi]
+    w.close()
+    del w, layer, x, logits, host
+
+    workloads = {}
+    if not args.core_only and not args.no_others and not args.tokens and args.workload == "C2":
+        for name in ("C3", "C4", "C5"):
+            workloads[name] = other_workload(name, np, torch, ds, K, W)
+
+    def strip(r):
+        return {k: v for k, v in r.items() if k not in ("flops", "tau_dev", "tau_table", "gemm1_ms")}
 
     out = {
         "metric": "MoE-layer tokens/s + MFMA TFLOP/s vs bf16 peak at 0/25/50% drop",
         "value": primary["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": primary["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: T=%d D=%d E=%d F=%d top-%d P=%d%s, tau for ~%d%% unit drop (realised %.1f%%)" % (
-            spec.name, spec.T, spec.D, spec.E, spec.F, spec.K, spec.P,
-            (" + %d shared x %d" % (spec.n_shared, spec.F_sh)) if spec.n_shared else "",
-            round(100 * args.primary_rate), 100 * primary["drop_rate"]),
-            "resident_experts": [spec.lo, spec.hi], "tokens": spec.T},
+        "config": {"workload": workload_line, "resident_experts": resident, "tokens": spec.T,
+                   "thresholds": "chosen on the device by moe_thresholds_for_drop_rate from the batch's scores"},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
-        "sweep": sweep, "proportionality": prop, "kernels": kernels,
+        "sweep": [strip(r) for r in sweep], "proportionality": prop, "kernels": kernels,
         "kernels_note": "HIP-event intervals around each launch of a separate timing pass: every entry carries about 4 us of "
                         "event-to-event gap (an empty interval reads 4-5 us); kernel durations proper are in profiles/",
-        "reconstruction": reconstruction, "threshold_selection": selection, "decode": decode, "router": router, "complete_transformation": transform,
+        "workloads": workloads,
+        "reconstruction": reconstruction, "threshold_selection": selection, "decode": decode, "router": router,
+        "complete_transformation": transform,
         "roofline": roofline, "cpu_baseline": cpu, "check": check,
     }
     print(json.dumps(out))
