@@ -145,19 +145,35 @@ class Workload:
             assert calls == K
         return dt / K * 1e3, kms
 
-    def record(self, label, tau_dev, K, W, profile_level=0):
+    def sweep(self, cases, K, W, reps=3, profile_label=None):
+        """Times every (label, tau) of `cases`: `reps` passes over the list, each pass W warm-up + K timed steps
+        per case, so that the cases see the same clock and temperature drift; a case's figure is the median of
+        its passes.  The case named profile_label also gets its GEMM-1 launches timed with HIP events (last pass)."""
         spec = self.spec
-        units = self.kept_units(tau_dev)
-        ms, kms = self.timed(tau_dev, K, W, profile_level)
-        flops = self.unit_flops * units + self.shared_flops
-        rec = {"case": label, "drop_rate": 1.0 - units / max(self.total_units, 1), "kept_units": units,
-               "drop_rate_incl_shared": (self.total_units - units) / max(self.total_units + self.shared_units, 1),
-               "ms_per_step": ms, "tokens_per_s": spec.T / (ms * 1e-3), "tflops": flops / (ms * 1e-3) / 1e12,
-               "frac_bf16_peak": flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "flops": flops,
-               "tau": [float(v) for v in tau_dev[spec.lo].cpu().numpy()]}
-        log("%s %s: %.3f ms/step, %.0f tokens/s, %.1f TFLOP/s (%.1f %% of bf16 peak), realised drop %.3f"
-            % (spec.name, label, ms, rec["tokens_per_s"], rec["tflops"], 100 * rec["frac_bf16_peak"], rec["drop_rate"]))
-        return rec, kms
+        units = [self.kept_units(tau) for _, tau in cases]
+        samples = [[] for _ in cases]
+        g1_ms = None
+        for rep in range(reps):
+            for i, (label, tau) in enumerate(cases):
+                prof = 1 if (label == profile_label and rep == reps - 1) else 0
+                ms, kms = self.timed(tau, K, W, prof)
+                samples[i].append(ms)
+                if prof:
+                    g1_ms = kms["gemm1"]
+        recs = []
+        for i, (label, tau) in enumerate(cases):
+            ms = sorted(samples[i])[len(samples[i]) // 2]
+            flops = self.unit_flops * units[i] + self.shared_flops
+            rec = {"case": label, "drop_rate": 1.0 - units[i] / max(self.total_units, 1), "kept_units": units[i],
+                   "drop_rate_incl_shared": (self.total_units - units[i]) / max(self.total_units + self.shared_units, 1),
+                   "ms_per_step": ms, "ms_per_step_passes": samples[i], "tokens_per_s": spec.T / (ms * 1e-3),
+                   "tflops": flops / (ms * 1e-3) / 1e12, "frac_bf16_peak": flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS,
+                   "flops": flops, "tau": [float(v) for v in tau[spec.lo].cpu().numpy()]}
+            log("%s %s: %.3f ms/step (passes %s), %.0f tokens/s, %.1f TFLOP/s (%.1f %% of bf16 peak), realised drop %.3f"
+                % (spec.name, label, ms, " ".join("%.3f" % v for v in samples[i]), rec["tokens_per_s"], rec["tflops"],
+                   100 * rec["frac_bf16_peak"], rec["drop_rate"]))
+            recs.append(rec)
+        return recs, g1_ms
 
     def kernel_table(self, tau_dev, K, W):
         """Per-kernel split from HIP events between all launches (its own timing pass)."""
@@ -199,33 +215,26 @@ def other_workload(name, np, torch, ds, K, W):
     """The fine-grained (C3), shared-plus-routed (C4) and skewed expert-parallel (C5) layers."""
     w = Workload(name, 0, np, torch, ds)
     spec = w.spec
-    cases = []
-    zero, _ = w.record("0%", w.tau_for_rate(0.0), K, W)
-    cases.append(zero)
-    primary_tau = None
+    todo = [("0%", w.tau_for_rate(0.0))]
     if name == "C3":
         for rate in (0.125, 0.25, 0.5):
-            tau = w.tau_for_rate(rate)
-            rec, _ = w.record("%g%%" % (100 * rate), tau, K, W)
-            rec["proportionality"] = proportionality(zero, rec)
-            cases.append(rec)
-            if rate == 0.25:
-                primary_tau = tau
+            todo.append(("%g%%" % (100 * rate), w.tau_for_rate(rate)))
+        primary_tau = todo[2][1]
     elif name == "C4":
         # "about 25 %" by the paper's definition (shared experts in the denominator) = a third of the routed units
         routed_rate = 0.25 * (w.total_units + w.shared_units) / w.total_units
         primary_tau = w.tau_for_rate(routed_rate)
-        rec, _ = w.record("25% incl. shared", primary_tau, K, W)
-        rec["proportionality"] = proportionality(zero, rec)
-        cases.append(rec)
+        todo.append(("25% incl. shared", primary_tau))
     else:  # C5: load-aware thresholds (Sec. 4.3) with the hot expert capped at 1.25 x the balanced share of rows
         cap = int(1.25 * spec.T * spec.K / spec.E)
         base = w.tau_for_rate(0.25)
         primary_tau = w.tau_load_aware(base[spec.lo].contiguous(), cap)
-        rec, _ = w.record("load-aware (25%% thresholds as the maximum, row cap %d)" % cap, primary_tau, K, W)
-        rec["proportionality"] = proportionality(zero, rec)
-        rec["tau_per_resident_expert"] = [[float(v) for v in primary_tau[e].cpu().numpy()] for e in range(spec.lo, spec.hi)]
-        cases.append(rec)
+        todo.append(("load-aware (25%% thresholds as the maximum, row cap %d)" % cap, primary_tau))
+    cases, _ = w.sweep(todo, K, W)
+    for rec in cases[1:]:
+        rec["proportionality"] = proportionality(cases[0], rec)
+    if name == "C5":
+        cases[1]["tau_per_resident_expert"] = [[float(v) for v in primary_tau[e].cpu().numpy()] for e in range(spec.lo, spec.hi)]
     kernels, _ = w.kernel_table(primary_tau, K, W)
     out = {"workload": "%s: T=%d D=%d E=%d F=%d top-%d P=%d%s%s" % (
         spec.name, spec.T, spec.D, spec.E, spec.F, spec.K, spec.P,
@@ -280,17 +289,15 @@ def main():
     rates = [float(r) for r in args.rates.split(",")]
     if args.primary_rate not in rates:
         rates.append(args.primary_rate)
-    sweep = []
+    todo = [("%g%%" % (100 * rate), tau_for(rate)) for rate in rates]
+    primary_label = "%g%%" % (100 * args.primary_rate)
+    sweep, g1_ms = w.sweep(todo, K, W, profile_label=primary_label)
     primary = None
-    for rate in rates:
-        tau_dev = tau_for(rate)
-        is_primary = abs(rate - args.primary_rate) < 1e-9
-        rec, kms = w.record("%g%%" % (100 * rate), tau_dev, K, W, 1 if is_primary else 0)
+    for rate, rec, (_, tau_dev) in zip(rates, sweep, todo):
         rec["target_drop"] = rate
-        sweep.append(rec)
-        if is_primary:
+        if abs(rate - args.primary_rate) < 1e-9:
             primary = dict(rec)
-            primary["gemm1_ms"] = kms["gemm1"]
+            primary["gemm1_ms"] = g1_ms
             primary["tau_dev"] = tau_dev
             primary["tau_table"] = tau_dev.cpu().numpy()
     kernels, g1_flops = w.kernel_table(primary["tau_dev"], K, W)
@@ -488,7 +495,9 @@ def main():
         "ms_per_step": primary["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": workload_line, "resident_experts": resident, "tokens": spec.T,
-                   "thresholds": "chosen on the device by moe_thresholds_for_drop_rate from the batch's scores"},
+                   "thresholds": "chosen on the device by moe_thresholds_for_drop_rate from the batch's scores",
+                   "timing": "every case: median of 3 passes of `steps` timed steps after `warmup` steps, the cases of a sweep "
+                             "interleaved pass by pass"},
         "tflops": primary["tflops"], "frac_bf16_peak": primary["frac_bf16_peak"],
         "sweep": [strip(r) for r in sweep], "proportionality": prop, "kernels": kernels,
         "kernels_note": "HIP-event intervals around each launch of a separate timing pass: every entry carries about 4 us of "

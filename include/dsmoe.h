@@ -209,7 +209,9 @@ int moe_transform_complete(dsmoe_ctx* ctx, const void* wg, const void* w1, const
  *   x, logits   device [T][D] / float [T][E]: the calibration tokens
  *   importance  device float [E_res][F], fully overwritten (0 for an expert no token routes to)
  *   workspace   as for moe_dualsparse_forward (its contents are overwritten)
- * bf16 layers on the matrix-core path store each term as bf16 before the fp32 row sum.  Asynchronous, no allocation.
+ * Terms and sums are fp32.  The rows of a tile are summed in the order the row list holds them, which
+ * can differ between runs (see moe_dualsparse_forward's row lists): the last bits of a sum may too.
+ * Asynchronous, no allocation.
  */
 int moe_profile_importance(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, int32_t T,
                            int32_t metric, float* importance, void* workspace, void* stream);

@@ -187,6 +187,28 @@ __device__ __forceinline__ float epi_value(int epi, float g, float u) {
   }
 }
 
+// All-reductions inside a row of sixteen lanes: four data-parallel steps (mirror, half mirror, two
+// quad permutations) leave the result in every lane of the row, with no LDS or scalar round trip.
+constexpr int kRowMirror = 0x140, kRowHalfMirror = 0x141, kQuadSwap2 = 0x4E, kQuadSwap1 = 0xB1;
+template <int CTRL>
+__device__ __forceinline__ int dpp_all(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ float row_max(float v) {
+  v = fmaxf(v, __int_as_float(dpp_all<kRowMirror>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_all<kRowHalfMirror>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_all<kQuadSwap2>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_all<kQuadSwap1>(__float_as_int(v))));
+  return v;
+}
+__device__ __forceinline__ float row_sum(float v) {  // every step adds two partners' values: the same bits in every lane
+  v += __int_as_float(dpp_all<kRowMirror>(__float_as_int(v)));
+  v += __int_as_float(dpp_all<kRowHalfMirror>(__float_as_int(v)));
+  v += __int_as_float(dpp_all<kQuadSwap2>(__float_as_int(v)));
+  v += __int_as_float(dpp_all<kQuadSwap1>(__float_as_int(v)));
+  return v;
+}
+
 // Position of the 16-byte chunk `chunk` (0..3) of row `row` inside a [rows][32] bf16 LDS tile
 // (64-byte rows).  The chunks of a row are XOR-rotated by bits 2..3 of the row so that an MFMA
 // operand read (consecutive rows, same logical chunk) touches every LDS bank once per 16 lanes.

@@ -307,9 +307,64 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   };
   t.mainloop(g.KS1, begin, one, lds);
 
+  if constexpr (PROFILE) {
+    // Importance profiling (Sec. 4.2 b): the metric of every (row, neuron) of the tile is summed over
+    // the rows right here, in fp32: over the wavefront's row blocks in registers, over the 32 lanes
+    // that hold different rows of the same neurons by a fixed exchange pattern, over the two
+    // wavefronts that split the rows through LDS.  The tile's 128 sums go to row (row tile) of a
+    // [row tiles][F] table that colsum_tiles_kernel adds up per expert, in tile order.  Nothing is
+    // rounded to 16 bits and no per-row intermediate is written.
+    float* part = (float*)lds;  // [2 row groups][128 neurons]
+    const bool with_up = g.epi >= 3, magnitude = g.epi == 2 || g.epi == 4;  // the four metrics, see epi_value
+    block_barrier();            // every wave is done reading the last stage
+    if (tid < 256) part[tid] = 0.f;
+    uint32_t keptmask = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int r = b_row0 + j * 32 + (lane & 31);
+      const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
+      keptmask |= (kept ? 1u : 0u) << j;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < I; i += 2) {
+      float sum[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum[v] = 0.f;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const bool kept = (keptmask >> j) & 1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float sg = silu_fast(t.acc[i][j][v]);
+          float m = with_up ? sg * t.acc[i + 1][j][v] : sg;  // uniform selects, no branch per value
+          m = magnitude ? fabsf(m) : m;
+          sum[v] += kept ? m : 0.f;
+        }
+      }
+      if (NJ > 0) {
+        const int nb = (a_row0 >> 5) + i + 4 * half;  // weight block index; neurons of the tile: (nb/2)*32 ..
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float x = row_sum(sum[v]);   // over the sixteen lanes of a row, then the two rows of this half of the wavefront
+          x += __shfl_xor(x, 16, 64);  // (a + b in one lane, b + a in the other: the same bits)
+          if ((lane & 31) == 0) part[(b_row0 ? 128 : 0) + (nb >> 1) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = x;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    const int n_lo = HALF ? 64 * half : 0, n_hi = HALF ? n_lo + 64 : kMfmaNeur;
+    if (tid >= n_lo && tid < n_hi && g.it.jt * kMfmaNeur + tid < g.Fp) {
+      float* table = (float*)g.H;  // the profiling pass keeps its per-tile sums where the layer keeps H
+      const size_t tile = (size_t)(g.hrow0 / kMfmaBM);
+      table[tile * g.ld + (size_t)g.it.p * g.Fp + g.it.jt * kMfmaNeur + tid] = part[tid] + part[128 + tid];
+    }
+    return;
+  }
+
   // epilogue.  acc[i][j][v]: weight row a_row0 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row
-  // b_row0 + j*32 + lane%32.  Swish(gate) * up is rounded to half precision (the profiling
-  // metrics to bf16) and parked in LDS as a
+  // b_row0 + j*32 + lane%32.  Swish(gate) * up is rounded to half precision and parked in LDS as a
   // [256 rows][128 neurons] tile (rows padded to 272 bytes against bank conflicts), then written
   // out in whole 256-byte row segments: 16 lanes per row, 16 bytes per lane.
   constexpr int kHsRow = kMfmaNeur * 2 + 16;
@@ -328,15 +383,10 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const float gt = t.acc[i][j][vq * 4 + c], up = t.acc[i + 1][j][vq * 4 + c];
-          h[c] = kept ? epi_value<true>(PROFILE ? g.epi : 0, gt, up) : 0.f;  // Swish(gate) * up (Eq. 4), or a profiling metric
+          h[c] = kept ? epi_value<true>(0, gt, up) : 0.f;  // Swish(gate) * up (Eq. 4)
         }
         uint2 pk;
-        if (PROFILE) {
-          bf16x2 lo, hi;
-          lo[0] = (__bf16)h[0], lo[1] = (__bf16)h[1], hi[0] = (__bf16)h[2], hi[1] = (__bf16)h[3];
-          pk.x = __builtin_bit_cast(uint32_t, lo);
-          pk.y = __builtin_bit_cast(uint32_t, hi);
-        } else {
+        {
           // half precision, round to nearest: half a unit of the kept 10 fraction bits is added to the
           // magnitude (fp32 bit pattern + 2^12), then the packed conversion truncates.  Truncation never
           // yields infinity, so |h| beyond 65504 saturates.
@@ -394,8 +444,9 @@ __device__ __forceinline__ void gemm1_setup(G1Args& g, int item_id, const Layout
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
 }
 
-// PROFILE = false is the layer's kernel (epilogue fixed at compile time); PROFILE = true picks the
-// importance metric of the epilogue at run time (epi 1..4), which costs a few per cent.
+// PROFILE = false is the layer's kernel: it stores Swish(gate) * up.  PROFILE = true is the importance
+// profiling pass: it picks the metric at run time (epi 1..4), sums it over the rows of the tile and
+// stores 128 column sums per item instead of the activation.
 template <bool PROFILE>
 __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const char* packed, const uint16_t* x, char* ws, int epi) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -404,6 +455,7 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   G1Args g;
   gemm1_setup<4>(g, item_id, L, T, packed, x, ws, epi, lds, tid, w);
+  if (PROFILE && g.sh) return;  // importance is profiled for the routed experts only
 
   if (g.it.half) {  // at most 128 rows (the plan guarantees it): wavefronts 0 and 1 multiply, 64 weight rows each
     if (w < 2) {

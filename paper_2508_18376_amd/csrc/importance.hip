@@ -1,9 +1,11 @@
 // Neuron importance profiling and reconstruction order (paper Sec. 4.2 b).
 //
-// GEMM-1 is run over the calibration tokens with every routed pair kept and stores, instead of
-// Swish(gate)*up, the chosen metric per (row, neuron).  Here the rows of each expert are summed
-// per neuron (one thread per neuron, rows in order: deterministic), and an importance vector is
-// turned into the permutation "neurons by descending importance, equal values by ascending id".
+// GEMM-1 is run over the calibration tokens with every routed pair kept.  On the matrix-core path
+// its epilogue sums the chosen metric over the rows of each tile and this file adds the tiles of an
+// expert; on the generic path GEMM-1 stores the metric per (row, neuron) in fp32 and the rows of each
+// expert are summed here (one thread per neuron, rows in order).  Both are deterministic.  An
+// importance vector is turned into the permutation "neurons by descending importance, equal values
+// by ascending id".
 #include "common.h"
 
 namespace dsmoe {
@@ -42,11 +44,27 @@ __global__ __launch_bounds__(256) void colsum_kernel(Layout L, const char* ws, f
   importance[(size_t)e * L.F + q] = acc * unscale;
 }
 
+// MFMA path: the GEMM-1 profiling pass has left one row of F column sums per row tile where the layer
+// keeps H; importance[e][q] = the sum of the rows of expert e's tiles, in tile order (deterministic).
+__global__ __launch_bounds__(256) void colsum_tiles_kernel(Layout L, const char* ws, float* importance, float unscale) {
+  const int e = blockIdx.y;
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= L.F) return;
+  const int32_t* exp_nrows = (const int32_t*)(ws + L.o_exp_nrows);
+  const int32_t* exp_row0 = (const int32_t*)(ws + L.o_exp_row0);
+  const float* table = (const float*)(ws + L.o_H);
+  const int nt = (exp_nrows[e] + L.BM - 1) / L.BM;
+  const size_t t0 = (size_t)((exp_row0[e] - L.sh_rows) / L.BM);
+  float acc = 0.f;
+  for (int i = 0; i < nt; ++i) acc += table[(t0 + i) * L.F + q];
+  importance[(size_t)e * L.F + q] = acc * unscale;
+}
+
 hipError_t launch_colsum(const Layout& L, const char* ws, int metric, float* importance, hipStream_t s) {
   dim3 grid((L.F + 255) / 256, L.E_res), block(256);
   const float unscale = metric >= 2 ? ldexpf(1.f, -L.h_shift) : 1.f;
   if (!L.mfma) colsum_kernel<float><<<grid, block, 0, s>>>(L, ws, importance, unscale);  // the generic path keeps H in fp32
-  else colsum_kernel<uint16_t><<<grid, block, 0, s>>>(L, ws, importance, unscale);
+  else colsum_tiles_kernel<<<grid, block, 0, s>>>(L, ws, importance, unscale);
   return hipGetLastError();
 }
 

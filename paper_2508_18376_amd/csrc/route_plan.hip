@@ -132,25 +132,6 @@ __global__ __launch_bounds__(64) void route_lane_kernel(RouteArgs a) {
 // scalar round trip, and the four rows of a wavefront work on four tokens at once.  U tokens per
 // row are carried through every step together so that their dependency chains overlap.
 // A block is WV wavefronts = WV * 4 * U tokens.
-constexpr int kRowMirror = 0x140, kRowHalfMirror = 0x141, kQuadSwap2 = 0x4E, kQuadSwap1 = 0xB1;
-template <int CTRL>
-__device__ __forceinline__ int dpp_all(int v) {
-  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
-}
-__device__ __forceinline__ float row_max(float v) {
-  v = fmaxf(v, __int_as_float(dpp_all<kRowMirror>(__float_as_int(v))));
-  v = fmaxf(v, __int_as_float(dpp_all<kRowHalfMirror>(__float_as_int(v))));
-  v = fmaxf(v, __int_as_float(dpp_all<kQuadSwap2>(__float_as_int(v))));
-  v = fmaxf(v, __int_as_float(dpp_all<kQuadSwap1>(__float_as_int(v))));
-  return v;
-}
-__device__ __forceinline__ float row_sum(float v) {  // every step adds two partners' values: the same bits in every lane
-  v += __int_as_float(dpp_all<kRowMirror>(__float_as_int(v)));
-  v += __int_as_float(dpp_all<kRowHalfMirror>(__float_as_int(v)));
-  v += __int_as_float(dpp_all<kQuadSwap2>(__float_as_int(v)));
-  v += __int_as_float(dpp_all<kQuadSwap1>(__float_as_int(v)));
-  return v;
-}
 __device__ __forceinline__ int row_min(int v) {
   v = min(v, dpp_all<kRowMirror>(v));
   v = min(v, dpp_all<kRowHalfMirror>(v));
