@@ -75,6 +75,12 @@ typedef struct {
                              Layers whose activations are far from 1 in magnitude choose k to centre them.  The
                              factor is folded into the packed weights and taken out again exactly: it changes
                              nothing else and costs nothing per call. */
+  int32_t partial_fp32;   /* 0 (normal): on the matrix-core path the per-(token, expert) partial outputs that the
+                             combine step adds up are stored in half precision (11 significant bits each), scaled
+                             relative to the largest |W2| and to h * 2^k of h_scale_log2: full precision over some
+                             seven decades below their typical size, saturation a factor 60 and more above it.
+                             They are the largest memory stream of layers with many experts per token.
+                             1: they are kept in fp32.  Sums are fp32 either way. */
 } dsmoe_config;
 
 /* Validates cfg and builds the host-side context.  No GPU call is made. */
@@ -134,8 +140,9 @@ int moe_route_and_mask(dsmoe_ctx* ctx, const float* logits, int32_t T, const flo
  * bf16 layers accumulate in fp32 and round the output once.  On the matrix-core path the
  * intermediate activation Swish(x W1) * (x W3) is stored in IEEE half precision (values beyond
  * +-65504 saturate) and multiplied with W2 held as half precision times a per-layer power of two,
- * which represents every bf16 weight within 2^-29 of the largest exactly; bf16 layers on the generic
- * path (see dsmoe_uses_mfma) keep the activation in fp32.
+ * which represents every bf16 weight within 2^-29 of the largest exactly, and the per-pair partial
+ * outputs are stored in half precision unless cfg.partial_fp32 is set; bf16 layers on the generic path
+ * (see dsmoe_uses_mfma) keep both in fp32.
  */
 int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, const float* logits, const float* tau,
                            int32_t T, void* y, void* workspace, void* stream);

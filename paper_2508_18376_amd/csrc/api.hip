@@ -27,6 +27,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   if (c.renorm_combine != 0 && c.renorm_combine != 1) return false;
   if (c.y_fp32 != 0 && c.y_fp32 != 1) return false;
   if (c.h_scale_log2 < -40 || c.h_scale_log2 > 40) return false;
+  if (c.partial_fp32 != 0 && c.partial_fp32 != 1) return false;
   if ((int64_t)c.max_tokens * c.top_k * c.n_part > (int64_t)1 << 30) return false;
   if ((int64_t)c.n_shared * c.d_ff_shared > (int64_t)1 << 30) return false;
 
@@ -50,6 +51,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
             (int64_t)c.max_tokens * L.D * 2 < ((int64_t)1 << 31))
                ? 1
                : 0;
+  L.yp_half = (L.mfma && !c.partial_fp32) ? 1 : 0;
   L.h_shift = L.mfma ? c.h_scale_log2 : 0;  // the generic path keeps the activation in fp32: nothing to scale
   const int64_t elem = c.dtype == DSMOE_F32 ? 4 : 2;
   L.BM = L.mfma ? kMfmaBM : kGenBM;

@@ -17,6 +17,12 @@ constexpr int kSplitItems = 256;  // one GEMM-2 item per compute unit: the granu
 constexpr int kMaxSplit = 8;      // most K ranges an item is split into when there are few row tiles (decode-sized batches)
 constexpr int kMaxTailSplit = 4;  // most K ranges an item of the last, partly filled round of items is split into
 constexpr int kPoolTiles = 256;   // partial-output tiles (256 x 256 fp32) the extra K ranges can need at most
+// Half-precision partial outputs hold the GEMM-2 accumulators times 2^-10.  The accumulators are sums
+// over the kept neurons of (activation x 2^k) x (W2 x 2^s) with the largest |W2 x 2^s| in [2^14, 2^15):
+// for activations of order one they are of order sqrt(neurons) x 5000, i.e. 1e2 .. 1e3 after the
+// scaling, with a factor 60 and more up to half precision's largest value and seven decades down to its
+// smallest normal one, whatever the scale of the weights (and, through cfg.h_scale_log2, of the activations).
+constexpr float kYpHalfScale = 1.0f / 1024.0f;
 constexpr int kSelBins = 4096;  // grid of the row-budget thresholds: multiples of 2^-12 (a power of two keeps n * kSelBins exact)
 constexpr int kRouteBlockTokens = 64;  // tokens per block of the route kernels, one histogram row each ...
 constexpr int kWaveBlockTokens = 16;   // ... except the sixteen-lanes-per-token kernel (E > 32) on small batches: 4 wavefronts x 4 tokens
@@ -58,6 +64,7 @@ struct Layout {
   int32_t n_shared, F_shT;    // shared experts fused into one pseudo-expert of F_shT neurons (id E_res)
   int32_t renorm, dtype, mfma, router_mfma;
   int32_t y_f32;  // 1: y is float even though the layer's tensors are bf16
+  int32_t yp_half;  // MFMA path: GEMM-2 stores its per-pair partial outputs (Yp, pool tiles) in half precision (times kYpHalfScale)
   int32_t h_shift;  // MFMA path: the intermediate activation is stored times 2^h_shift (folded into the packed W3)
   int32_t g2_rows_inner;  // GEMM-2 item order: 1 = (expert, column tile, row tile), 0 = (expert, row tile, column tile)
   int32_t split_items;  // kSplitItems if GEMM-2 may split K (MFMA path), else 0

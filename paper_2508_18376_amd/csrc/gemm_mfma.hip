@@ -18,6 +18,9 @@
 // ring twice as deep, for batches so small that the kernel only streams weights.
 // GEMM-2 feeds the weight fragment as the MFMA's A operand, so that a lane ends up with four
 // consecutive output columns of a row.
+// The per-pair partial outputs of GEMM-2 (fp32 accumulators) are stored in half precision too unless
+// the context asks for fp32 partials: they are the largest stream of the fine-grained layers (K
+// partial rows of D values per token, written here and read once by the combine kernel).
 // Number formats: GEMM-1 multiplies bf16 by bf16 (x and W1 / W3 as the caller stores them).  The
 // intermediate activation H is kept as IEEE half precision (11 significant bits; bf16's 8 cost
 // up to 2e-2 of the output RMS on the largest outputs of a batch), so GEMM-2 is the f16 MFMA of
@@ -493,12 +496,14 @@ struct G2Args {
   int np, KSp, nstages, D;
   i32x4 rsW, rsH;
   uint32_t hoff[4], woff, lds_w;
-  float* Y;   // where row 0, column 0 of this item's output tile goes
-  int ldy;    // its row stride: D in Yp, 256 in a pool tile
+  char* Y;       // where row 0, column 0 of this item's output tile goes (float, or half precision: YH)
+  int ldy;       // its row stride in elements: D in Yp, 256 in a pool tile
+  float yscale;  // YH: the accumulators are stored times this power of two (see kYpHalfScale)
 };
 
 // MFMA A = pair rows of H, B = output columns of W2 (both half precision).
-template <int I, int J, int NI, bool NT, class RING = RingWhole>
+// YH: the partial outputs are stored in half precision (see launch_gemm2_mfma)
+template <int I, int J, int NI, bool NT, bool YH, class RING = RingWhole>
 __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
   asm volatile("" : "+v"(tid));  // see gemm1_tile
   const int lane = tid & 63;
@@ -531,26 +536,41 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   // turns one block of 32 rows at a time around in its own quarter of the (now idle) ring and
   // writes it out as whole row segments of J*128 bytes, 16 bytes per lane.
   typedef float f32x4_t __attribute__((ext_vector_type(4)));
-  constexpr int kYsRow = J * 128 + 16;           // bytes; the pad spreads the rows over the banks
-  constexpr int kLanesRow = J * 8;               // lanes that share a row in the write-out
+  constexpr int kEl = YH ? 2 : 4;                // bytes of one stored value
+  constexpr int kYsRow = J * 32 * kEl + 16;      // bytes; the pad spreads the rows over the banks
+  constexpr int kLanesRow = J * 2 * kEl;         // lanes that share a row in the write-out (16 bytes each)
+  constexpr int kColsLane = 16 / kEl;            // columns a lane writes out
   constexpr int kRowsPass = 64 / kLanesRow;      // rows per store instruction
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   char* mine = lds + w * (RING::BYTES / 4);
   static_assert(32 * kYsRow <= RING::BYTES / 4, "a block of 32 rows fits a wavefront's quarter of the ring");
   block_barrier();  // every wave is done reading the last stage
-  const int cw = g.it.jd * kMfmaBN2 + b_row0 + (lane % kLanesRow) * 4;  // first of this lane's 4 columns in the write-out
+  const int cw = g.it.jd * kMfmaBN2 + b_row0 + (lane % kLanesRow) * kColsLane;  // first of this lane's columns in the write-out
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
 #pragma unroll
     for (int j = 0; j < J; ++j)
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        f32x4_t o;
-        o.x = t.acc[i][j][vq * 4 + 0];
-        o.y = t.acc[i][j][vq * 4 + 1];
-        o.z = t.acc[i][j][vq * 4 + 2];
-        o.w = t.acc[i][j][vq * 4 + 3];
-        *(f32x4_t*)(mine + (lane & 31) * kYsRow + (j * 32 + vq * 8 + (lane >> 5) * 4) * 4) = o;
+        char* at = mine + (lane & 31) * kYsRow + (j * 32 + vq * 8 + (lane >> 5) * 4) * kEl;
+        if constexpr (YH) {  // times 2^-10, saturating, round to nearest even
+          float v[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_fmed3f(t.acc[i][j][vq * 4 + c] * g.yscale, -kHalfMax, kHalfMax);
+          f16x2 lo, hi;
+          lo[0] = (_Float16)v[0], lo[1] = (_Float16)v[1], hi[0] = (_Float16)v[2], hi[1] = (_Float16)v[3];
+          uint2 pk;
+          pk.x = __builtin_bit_cast(uint32_t, lo);
+          pk.y = __builtin_bit_cast(uint32_t, hi);
+          *(uint2*)at = pk;
+        } else {
+          f32x4_t o;
+          o.x = t.acc[i][j][vq * 4 + 0];
+          o.y = t.acc[i][j][vq * 4 + 1];
+          o.z = t.acc[i][j][vq * 4 + 2];
+          o.w = t.acc[i][j][vq * 4 + 3];
+          *(f32x4_t*)at = o;
+        }
       }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -559,9 +579,9 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
     for (int k = 0; k < 32 / kRowsPass; ++k) {
       const int rl = k * kRowsPass + lane / kLanesRow;
       const int r = a_row0 + i * 32 + rl;
-      const f32x4_t o = *(const f32x4_t*)(mine + rl * kYsRow + (lane % kLanesRow) * 16);
+      const f32x4_t o = *(const f32x4_t*)(mine + rl * kYsRow + (lane % kLanesRow) * 16);  // 16 bytes: 4 floats or 8 halves
       if (r < g.it.nrows && cw < g.D) {
-        f32x4_t* dst = (f32x4_t*)(g.Y + (size_t)r * g.ldy + b_row0 + (lane % kLanesRow) * 4);
+        f32x4_t* dst = (f32x4_t*)(g.Y + ((size_t)r * g.ldy + b_row0 + (lane % kLanesRow) * kColsLane) * kEl);
         if (NT) __builtin_nontemporal_store(o, dst);
         else *dst = o;
       }
@@ -591,13 +611,15 @@ __device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout
   const char* hbase = (const char*)(H + (size_t)hrow0 * ld);
   g.rsW = make_rsrc(wbase, (uint32_t)((int64_t)KT * kStageBytes));
   g.rsH = make_rsrc(hbase, (uint32_t)((int64_t)g.it.nrows * ld * 2));
+  const size_t yel = L.yp_half ? 2 : 4;
   if (g.it.split == 0) {  // the item's rows of Yp
-    g.Y = (float*)(ws + L.o_Yp) + (size_t)g.it.row0 * L.D + g.it.jd * kMfmaBN2;
+    g.Y = ws + L.o_Yp + ((size_t)g.it.row0 * L.D + g.it.jd * kMfmaBN2) * yel;
     g.ldy = L.D;
   } else {  // an extra K range of a split item: a partial-output tile of the pool
-    g.Y = (float*)(ws + L.o_pool) + (size_t)(g.it.split - 1) * kMfmaBM * kMfmaBN2;
+    g.Y = ws + L.o_pool + (size_t)(g.it.split - 1) * kMfmaBM * kMfmaBN2 * yel;
     g.ldy = kMfmaBN2;
   }
+  g.yscale = kYpHalfScale;
 #pragma unroll
   for (int i = 0; i < SLABS; ++i) {
     const int r = i * 64 + (tid >> 2);
@@ -612,7 +634,7 @@ __device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout
 
 // NT: the output leaves with non-temporal stores (for outputs far larger than the caches: the
 // combine step reads them from HBM anyway, and the weight and activation tiles keep their place in L2)
-template <bool NT>
+template <bool NT, bool YH>
 __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const char* packed, char* ws) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int item_id = xcd_remap(blockIdx.x);
@@ -622,17 +644,17 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   gemm2_setup<4>(g, item_id, L, packed, ws, lds, tid, w);
 
   if (g.it.nrows == kMfmaBM) {
-    gemm2_tile<4, 4, 4, NT>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
+    gemm2_tile<4, 4, 4, NT, YH>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
   } else {  // 1 x 4: the ceil(nrows/32) blocks of pair rows that exist x 64 columns
     switch ((g.it.nrows + 31) >> 5) {
-      case 1: gemm2_tile<8, 2, 1, NT>(g, lds, 0, w * 64, tid); break;
-      case 2: gemm2_tile<8, 2, 2, NT>(g, lds, 0, w * 64, tid); break;
-      case 3: gemm2_tile<8, 2, 3, NT>(g, lds, 0, w * 64, tid); break;
-      case 4: gemm2_tile<8, 2, 4, NT>(g, lds, 0, w * 64, tid); break;
-      case 5: gemm2_tile<8, 2, 5, NT>(g, lds, 0, w * 64, tid); break;
-      case 6: gemm2_tile<8, 2, 6, NT>(g, lds, 0, w * 64, tid); break;
-      case 7: gemm2_tile<8, 2, 7, NT>(g, lds, 0, w * 64, tid); break;
-      default: gemm2_tile<8, 2, 8, NT>(g, lds, 0, w * 64, tid); break;
+      case 1: gemm2_tile<8, 2, 1, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 2: gemm2_tile<8, 2, 2, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 3: gemm2_tile<8, 2, 3, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 4: gemm2_tile<8, 2, 4, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 5: gemm2_tile<8, 2, 5, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 6: gemm2_tile<8, 2, 6, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 7: gemm2_tile<8, 2, 7, NT, YH>(g, lds, 0, w * 64, tid); break;
+      default: gemm2_tile<8, 2, 8, NT, YH>(g, lds, 0, w * 64, tid); break;
     }
   }
 }
@@ -643,7 +665,8 @@ static hipError_t set_lds_attr_now() {
     int bytes;
   } kernels[] = {
       {(const void*)gemm1_mfma_kernel<false>, kLdsBytes},       {(const void*)gemm1_mfma_kernel<true>, kLdsBytes},
-      {(const void*)gemm2_mfma_kernel<false>, kLdsBytes},       {(const void*)gemm2_mfma_kernel<true>, kLdsBytes},
+      {(const void*)gemm2_mfma_kernel<false, false>, kLdsBytes}, {(const void*)gemm2_mfma_kernel<true, false>, kLdsBytes},
+      {(const void*)gemm2_mfma_kernel<false, true>, kLdsBytes},  {(const void*)gemm2_mfma_kernel<true, true>, kLdsBytes},
   };
   for (const auto& k : kernels) {
     hipError_t e = hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.bytes);
@@ -674,9 +697,16 @@ hipError_t launch_gemm2_mfma(const Layout& L, int T, const char* packed, char* w
   if (e != hipSuccess) return e;
   const int g2 = (items2_bound(L, T) + 255) & ~255;
   // per-pair outputs of this batch, at most; beyond the size of the last-level cache they stream
-  const int64_t out_bytes = (int64_t)T * (L.K + (L.n_shared > 0 ? 1 : 0)) * L.D * 4;
-  if (out_bytes > kStreamOutBytes) gemm2_mfma_kernel<true><<<dim3(g2), dim3(256), kLdsBytes, s>>>(L, T, packed, ws);
-  else gemm2_mfma_kernel<false><<<dim3(g2), dim3(256), kLdsBytes, s>>>(L, T, packed, ws);
+  const int64_t out_bytes = (int64_t)T * (L.K + (L.n_shared > 0 ? 1 : 0)) * L.D * (L.yp_half ? 2 : 4);
+  const bool nt = out_bytes > kStreamOutBytes;
+  const dim3 grid(g2), block(256);
+  if (L.yp_half) {
+    if (nt) gemm2_mfma_kernel<true, true><<<grid, block, kLdsBytes, s>>>(L, T, packed, ws);
+    else gemm2_mfma_kernel<false, true><<<grid, block, kLdsBytes, s>>>(L, T, packed, ws);
+  } else {
+    if (nt) gemm2_mfma_kernel<true, false><<<grid, block, kLdsBytes, s>>>(L, T, packed, ws);
+    else gemm2_mfma_kernel<false, false><<<grid, block, kLdsBytes, s>>>(L, T, packed, ws);
+  }
   return hipGetLastError();
 }
 

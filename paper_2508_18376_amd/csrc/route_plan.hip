@@ -791,19 +791,43 @@ hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s) {
 // ------------------------------------------------------------------------------------- combine
 // y[t] = sum_k g[t][k] * Yp[row(t,k)] (+ Yp[shared row t]); Eq. 3 restricted to the kept units.
 // One writer per output element, slots added in slot order: no atomics.
-// w2_inv: 2^-s, the inverse of the power of two the packed W2 carries (1 on the generic path); the
-// products with it are exact, so the result is the one an unscaled W2 would give.
-template <typename OutT, int KB>
+// Partial outputs still carry the powers of two of the packed weights; w2_inv = 2^-(s+k) takes them
+// out here (exact, so the result is the one unscaled weights would give; 1 on the generic path).
+// They are fp32, or (HALF) half precision times kYpHalfScale, which is taken out here as well.
+// 16 bytes of partial outputs from element idx: VEC = 4 floats, or 8 half-precision values
+template <bool HALF>
+struct Partials {
+  static constexpr int VEC = HALF ? 8 : 4;
+  float v[VEC];
+  __device__ __forceinline__ void load(const char* base, size_t idx) {
+    if constexpr (HALF) {
+      typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+      const h8 h = *(const h8*)(base + idx * 2);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = (float)h[i];
+    } else {
+      const float4 f = *(const float4*)(base + idx * 4);
+      v[0] = f.x, v[1] = f.y, v[2] = f.z, v[3] = f.w;
+    }
+  }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+  }
+};
+
+template <typename OutT, int KB, bool HALF>
 __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const char* ws, OutT* y, const float* w2_inv_p) {
-  const float w2_inv = w2_inv_p ? *w2_inv_p : 1.f;
-  const float* Yp = (const float*)(ws + L.o_Yp);
+  constexpr int VEC = Partials<HALF>::VEC;  // columns per thread (D % 8 == 0 where HALF is used: the matrix-core path)
+  const float w2_inv = (w2_inv_p ? *w2_inv_p : 1.f) * (HALF ? 1.0f / kYpHalfScale : 1.f);
+  const char* Yp = ws + L.o_Yp;
   const float* w = (const float*)(ws + L.o_w);
   const int32_t* pair_row = (const int32_t*)(ws + L.o_pair_row);
-  const int D4 = L.D >> 2;  // D % 4 == 0 on this path
+  const int DV = L.D / VEC;
   const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (q >= (int64_t)T * D4) return;
-  const int t = (int)(q / D4);
-  const int d = (int)(q % D4) * 4;
+  if (q >= (int64_t)T * DV) return;
+  const int t = (int)(q / DV);
+  const int d = (int)(q % DV) * VEC;
   // all row indices first, then all row loads in flight together, then the sum in slot order
   int row[KB];
   float g[KB];
@@ -812,29 +836,31 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
     row[k] = k < L.K ? pair_row[(size_t)t * L.K + k] : -1;
     g[k] = k < L.K ? w[(size_t)t * L.K + k] * w2_inv : 0.f;
   }
-  float4 v[KB];
+  Partials<HALF> v[KB];
 #pragma unroll
-  for (int k = 0; k < KB; ++k)
-    v[k] = row[k] >= 0 ? *(const float4*)(Yp + (size_t)row[k] * L.D + d) : make_float4(0.f, 0.f, 0.f, 0.f);
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (L.n_shared > 0) acc = *(const float4*)(Yp + (size_t)t * L.D + d);  // shared rows sit first in the row space
+  for (int k = 0; k < KB; ++k) {
+    if (row[k] >= 0) v[k].load(Yp, (size_t)row[k] * L.D + d);
+    else v[k].zero();
+  }
+  Partials<HALF> acc;
+  acc.zero();
+  if (L.n_shared > 0) acc.load(Yp, (size_t)t * L.D + d);  // shared rows sit first in the row space
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   const int nsplit = counters[3];
   if (nsplit > 1) {  // GEMM-2 split K: add the partial-output tiles of the extra K ranges, in range order
     const int32_t* split_of = (const int32_t*)(ws + L.o_split_of);
-    const float* pool = (const float*)(ws + L.o_pool);
+    const char* pool = ws + L.o_pool;
     const int jd = d / kMfmaBN2, dc = d - jd * kMfmaBN2;
-    auto add_extra = [&](int r, float4& into) {  // r: a row of the row space
+    auto add_extra = [&](int r, Partials<HALF>& into) {  // r: a row of the row space
       const int tile = r / L.BM;
       const int first = split_of[(size_t)tile * L.ND2 + jd];
       if (first < 0) return;
-      const float* src = pool + ((size_t)first * L.BM + (r - tile * L.BM)) * kMfmaBN2 + dc;
+      size_t src = ((size_t)first * L.BM + (r - tile * L.BM)) * kMfmaBN2 + dc;
       for (int sp = 1; sp < nsplit; ++sp) {
-        const float4 u = *(const float4*)src;
-        into.x += u.x;
-        into.y += u.y;
-        into.z += u.z;
-        into.w += u.w;
+        Partials<HALF> u;
+        u.load(pool, src);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) into.v[i] += u.v[i];
         src += (size_t)L.BM * kMfmaBN2;
       }
     };
@@ -843,25 +869,30 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
       if (row[k] >= 0) add_extra(row[k], v[k]);
     if (L.n_shared > 0) add_extra(t, acc);
   }
-  acc.x *= w2_inv, acc.y *= w2_inv, acc.z *= w2_inv, acc.w *= w2_inv;  // the shared experts' rows (weight 1)
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc.v[i] *= w2_inv;  // the shared experts' rows (weight 1)
 #pragma unroll
   for (int k = 0; k < KB; ++k) {
     if (row[k] >= 0) {
-      acc.x += g[k] * v[k].x;
-      acc.y += g[k] * v[k].y;
-      acc.z += g[k] * v[k].z;
-      acc.w += g[k] * v[k].w;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc.v[i] += g[k] * v[k].v[i];
     }
   }
   if constexpr (sizeof(OutT) == 4) {
-    *(float4*)((float*)y + (size_t)t * L.D + d) = acc;
+    float* dst = (float*)y + (size_t)t * L.D + d;
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) *(float4*)(dst + i) = make_float4(acc.v[i], acc.v[i + 1], acc.v[i + 2], acc.v[i + 3]);
   } else {
-    ushort4 o;
-    o.x = f32_to_bf16(acc.x);
-    o.y = f32_to_bf16(acc.y);
-    o.z = f32_to_bf16(acc.z);
-    o.w = f32_to_bf16(acc.w);
-    *(ushort4*)((uint16_t*)y + (size_t)t * L.D + d) = o;
+    uint16_t* dst = (uint16_t*)y + (size_t)t * L.D + d;
+    uint16_t o[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] = f32_to_bf16(acc.v[i]);
+    if constexpr (VEC == 8) {
+      *(uint4*)dst = make_uint4(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16), o[4] | ((uint32_t)o[5] << 16),
+                                o[6] | ((uint32_t)o[7] << 16));
+    } else {
+      *(uint2*)dst = make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
+    }
   }
 }
 
@@ -889,12 +920,17 @@ hipError_t launch_combine(const Layout& L, int T, const char* packed, char* ws, 
   if (T <= 0) return hipSuccess;
   const float* w2_inv = L.mfma ? (const float*)(packed + L.p_scale) + 2 : nullptr;
   if (L.D % 4 == 0) {
-    int64_t n = (int64_t)T * (L.D / 4);
+    int64_t n = (int64_t)T * (L.D / (L.yp_half ? 8 : 4));
     dim3 grid((unsigned)((n + 255) / 256)), block(256);
 #define DSMOE_COMBINE(KB)                                                                      \
   do {                                                                                          \
-    if (L.y_f32) combine_kernel<float, KB><<<grid, block, 0, s>>>(L, T, ws, (float*)y, w2_inv); \
-    else combine_kernel<uint16_t, KB><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y, w2_inv);             \
+    if (L.yp_half) {                                                                              \
+      if (L.y_f32) combine_kernel<float, KB, true><<<grid, block, 0, s>>>(L, T, ws, (float*)y, w2_inv); \
+      else combine_kernel<uint16_t, KB, true><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y, w2_inv);  \
+    } else {                                                                                      \
+      if (L.y_f32) combine_kernel<float, KB, false><<<grid, block, 0, s>>>(L, T, ws, (float*)y, w2_inv); \
+      else combine_kernel<uint16_t, KB, false><<<grid, block, 0, s>>>(L, T, ws, (uint16_t*)y, w2_inv);  \
+    }                                                                                             \
   } while (0)
     if (L.K <= 2) DSMOE_COMBINE(2);
     else if (L.K <= 4) DSMOE_COMBINE(4);

@@ -162,6 +162,29 @@ def test_weight_and_activation_scales_far_from_one(oracle, name, w_std, x_std, k
         layer.close()
 
 
+@pytest.mark.parametrize("name", ["fine_grained_K8", "shared_split_k"])
+def test_partial_outputs_in_fp32_and_in_half_precision(oracle, name):
+    """cfg.partial_fp32: both settings meet the bar (the fp32 output shows the computation's own error),
+    and fp32 partials are at least as close to the oracle as half-precision ones."""
+    import torch
+    spec = (spec_of(T=900, D=256, F=256, E=16, K=8, P=2, seed=41) if name == "fine_grained_K8"
+            else spec_of(T=40, D=512, F=2048, E=4, K=2, P=2, n_shared=1, F_sh=512, seed=42))  # few row tiles: K split in GEMM-2
+    t = make_layer(spec)
+    tau = resolve_tau(oracle, spec, t, "rate0.25")
+    y_ref = oracle_forward(oracle, spec, t, tau)
+    err = {}
+    for partial_fp32 in (False, True):
+        layer, dev = make_gpu_layer(spec, t, y_fp32=True, partial_fp32=partial_fp32)
+        assert layer.uses_mfma
+        y = layer.forward(dev["x"], dev["logits"], to_dev(tau))
+        torch.cuda.synchronize()
+        err[partial_fp32] = assert_output_close(to_host64(y, "f32"), y_ref, "bf16", y_fp32=True)
+        if name == "shared_split_k":
+            assert int(layer.plan(spec.T)["counters"][3]) > 1
+        layer.close()
+    assert err[False] < 5e-3 and err[True] <= err[False] * 1.05, err
+
+
 def test_partition_and_reorder_invariance_on_gpu(oracle):
     """No drop: the output must not depend on P or on the neuron order (paper Sec. 3.2 identity);
     checked GPU-against-oracle for each variant, and the oracle outputs agree among themselves."""
