@@ -794,31 +794,29 @@ hipError_t launch_scatter(const Layout& L, int T, char* ws, hipStream_t s) {
 // Partial outputs still carry the powers of two of the packed weights; w2_inv = 2^-(s+k) takes them
 // out here (exact, so the result is the one unscaled weights would give; 1 on the generic path).
 // They are fp32, or (HALF) half precision times kYpHalfScale, which is taken out here as well.
-// 16 bytes of partial outputs from element idx: VEC = 4 floats, or 8 half-precision values
+// 16 bytes of partial outputs: VEC = 4 floats, or 8 half-precision values.  The rows of a token are
+// loaded as raw 16-byte vectors (all in flight together) and widened one row at a time, so that the
+// kernel stays within the registers of full occupancy.
 template <bool HALF>
 struct Partials {
   static constexpr int VEC = HALF ? 8 : 4;
-  float v[VEC];
-  __device__ __forceinline__ void load(const char* base, size_t idx) {
+  static __device__ __forceinline__ uint4 load(const char* base, size_t idx) { return *(const uint4*)(base + idx * (HALF ? 2 : 4)); }
+  static __device__ __forceinline__ void widen(const uint4& r, float (&v)[VEC]) {
     if constexpr (HALF) {
       typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-      const h8 h = *(const h8*)(base + idx * 2);
+      const h8 h = __builtin_bit_cast(h8, r);
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[i] = (float)h[i];
     } else {
-      const float4 f = *(const float4*)(base + idx * 4);
-      v[0] = f.x, v[1] = f.y, v[2] = f.z, v[3] = f.w;
+      v[0] = __uint_as_float(r.x), v[1] = __uint_as_float(r.y), v[2] = __uint_as_float(r.z), v[3] = __uint_as_float(r.w);
     }
-  }
-  __device__ __forceinline__ void zero() {
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) v[i] = 0.f;
   }
 };
 
 template <typename OutT, int KB, bool HALF>
 __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const char* ws, OutT* y, const float* w2_inv_p) {
-  constexpr int VEC = Partials<HALF>::VEC;  // columns per thread (D % 8 == 0 where HALF is used: the matrix-core path)
+  using PT = Partials<HALF>;
+  constexpr int VEC = PT::VEC;  // columns per thread (D % 8 == 0 where HALF is used: the matrix-core path)
   const float w2_inv = (w2_inv_p ? *w2_inv_p : 1.f) * (HALF ? 1.0f / kYpHalfScale : 1.f);
   const char* Yp = ws + L.o_Yp;
   const float* w = (const float*)(ws + L.o_w);
@@ -836,57 +834,56 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
     row[k] = k < L.K ? pair_row[(size_t)t * L.K + k] : -1;
     g[k] = k < L.K ? w[(size_t)t * L.K + k] * w2_inv : 0.f;
   }
-  Partials<HALF> v[KB];
+  uint4 raw[KB];
 #pragma unroll
-  for (int k = 0; k < KB; ++k) {
-    if (row[k] >= 0) v[k].load(Yp, (size_t)row[k] * L.D + d);
-    else v[k].zero();
-  }
-  Partials<HALF> acc;
-  acc.zero();
-  if (L.n_shared > 0) acc.load(Yp, (size_t)t * L.D + d);  // shared rows sit first in the row space
+  for (int k = 0; k < KB; ++k) raw[k] = row[k] >= 0 ? PT::load(Yp, (size_t)row[k] * L.D + d) : make_uint4(0, 0, 0, 0);
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   const int nsplit = counters[3];
-  if (nsplit > 1) {  // GEMM-2 split K: add the partial-output tiles of the extra K ranges, in range order
-    const int32_t* split_of = (const int32_t*)(ws + L.o_split_of);
-    const char* pool = ws + L.o_pool;
-    const int jd = d / kMfmaBN2, dc = d - jd * kMfmaBN2;
-    auto add_extra = [&](int r, Partials<HALF>& into) {  // r: a row of the row space
-      const int tile = r / L.BM;
-      const int first = split_of[(size_t)tile * L.ND2 + jd];
-      if (first < 0) return;
-      size_t src = ((size_t)first * L.BM + (r - tile * L.BM)) * kMfmaBN2 + dc;
-      for (int sp = 1; sp < nsplit; ++sp) {
-        Partials<HALF> u;
-        u.load(pool, src);
+  const int32_t* split_of = (const int32_t*)(ws + L.o_split_of);
+  const char* pool = ws + L.o_pool;
+  const int jd = d / kMfmaBN2, dc = d - jd * kMfmaBN2;
+  // GEMM-2 split K: the partial-output tiles of the extra K ranges of row r are added in range order
+  auto add_extra = [&](int r, float (&into)[VEC]) {
+    const int tile = r / L.BM;
+    const int first = split_of[(size_t)tile * L.ND2 + jd];
+    if (first < 0) return;
+    size_t src = ((size_t)first * L.BM + (r - tile * L.BM)) * kMfmaBN2 + dc;
+    for (int sp = 1; sp < nsplit; ++sp) {
+      float u[VEC];
+      PT::widen(PT::load(pool, src), u);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) into.v[i] += u.v[i];
-        src += (size_t)L.BM * kMfmaBN2;
-      }
-    };
+      for (int i = 0; i < VEC; ++i) into[i] += u[i];
+      src += (size_t)L.BM * kMfmaBN2;
+    }
+  };
+  if (L.n_shared > 0) {  // the shared experts' rows sit first in the row space (weight 1)
+    PT::widen(PT::load(Yp, (size_t)t * L.D + d), acc);
+    if (nsplit > 1) add_extra(t, acc);
 #pragma unroll
-    for (int k = 0; k < KB; ++k)
-      if (row[k] >= 0) add_extra(row[k], v[k]);
-    if (L.n_shared > 0) add_extra(t, acc);
+    for (int i = 0; i < VEC; ++i) acc[i] *= w2_inv;
   }
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) acc.v[i] *= w2_inv;  // the shared experts' rows (weight 1)
 #pragma unroll
   for (int k = 0; k < KB; ++k) {
     if (row[k] >= 0) {
+      float v[VEC];
+      PT::widen(raw[k], v);
+      if (nsplit > 1) add_extra(row[k], v);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) acc.v[i] += g[k] * v[k].v[i];
+      for (int i = 0; i < VEC; ++i) acc[i] += g[k] * v[i];
     }
   }
   if constexpr (sizeof(OutT) == 4) {
     float* dst = (float*)y + (size_t)t * L.D + d;
 #pragma unroll
-    for (int i = 0; i < VEC; i += 4) *(float4*)(dst + i) = make_float4(acc.v[i], acc.v[i + 1], acc.v[i + 2], acc.v[i + 3]);
+    for (int i = 0; i < VEC; i += 4) *(float4*)(dst + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
   } else {
     uint16_t* dst = (uint16_t*)y + (size_t)t * L.D + d;
     uint16_t o[VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) o[i] = f32_to_bf16(acc.v[i]);
+    for (int i = 0; i < VEC; ++i) o[i] = f32_to_bf16(acc[i]);
     if constexpr (VEC == 8) {
       *(uint4*)dst = make_uint4(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16), o[4] | ((uint32_t)o[5] << 16),
                                 o[6] | ((uint32_t)o[7] << 16));
