@@ -227,7 +227,7 @@ int moe_profile_importance(dsmoe_ctx* ctx, const void* packed, const void* x, co
  * Reconstruction order from an importance table (Sec. 4.2 b: the major sub-expert takes the most
  * important neurons): perm[e][j] = neuron with the j-th largest importance[e][.], equal values by
  * ascending neuron id.  importance device float [E_res][F], perm device int32 [E_res][F].  The
- * result is what moe_partition_weights takes as perm.  NaN importances give an unspecified order.
+ * result is what moe_partition_weights takes as perm.  A NaN importance ranks as minus infinity (last).
  */
 int moe_importance_to_perm(dsmoe_ctx* ctx, const float* importance, int32_t* perm, void* stream);
 

@@ -15,8 +15,8 @@ constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
 constexpr int kSplitItems = 256;  // one GEMM-2 item per compute unit: the granularity K splits aim at (measured best)
 constexpr int kMaxSplit = 8;      // most K ranges an item is split into when there are few row tiles (decode-sized batches)
-constexpr int kMaxTailSplit = 4;  // most K ranges an item of the last, partly filled round of items is split into
-constexpr int kPoolTiles = 256;   // partial-output tiles (256 x 256 fp32) the extra K ranges can need at most
+constexpr int kMaxTailSplit = 8;  // most K ranges an item of the last, partly filled round of items is split into
+constexpr int kPoolTiles = 768;   // partial-output tiles (256 x 256) the extra K ranges can need at most
 // Half-precision partial outputs hold the GEMM-2 accumulators times 2^-10.  The accumulators are sums
 // over the kept neurons of (activation x 2^k) x (W2 x 2^s) with the largest |W2 x 2^s| in [2^14, 2^15):
 // for activations of order one they are of order sqrt(neurons) x 5000, i.e. 1e2 .. 1e3 after the

@@ -68,18 +68,20 @@ hipError_t launch_colsum(const Layout& L, const char* ws, int metric, float* imp
   return hipGetLastError();
 }
 
-// perm[e][rank(q)] = q with rank(q) = #{q' : imp[q'] > imp[q], or equal and q' < q}
+// perm[e][rank(q)] = q with rank(q) = #{q' : imp[q'] > imp[q], or equal and q' < q}.  A NaN importance
+// counts as minus infinity (such neurons come last, by id), so the result is a permutation whatever the input.
 constexpr int kRankTile = 1024;
 __global__ __launch_bounds__(256) void perm_rank_kernel(int F, const float* importance, int32_t* perm) {
   __shared__ float tile[kRankTile];
   const int e = blockIdx.y;
   const float* imp = importance + (size_t)e * F;
   const int q = blockIdx.x * 256 + threadIdx.x;
-  const float mine = q < F ? imp[q] : 0.f;
+  auto key = [](float v) { return v != v ? -INFINITY : v; };
+  const float mine = q < F ? key(imp[q]) : 0.f;
   int rank = 0;
   for (int base = 0; base < F; base += kRankTile) {
     __syncthreads();
-    for (int i = threadIdx.x; i < kRankTile; i += 256) tile[i] = base + i < F ? imp[base + i] : 0.f;
+    for (int i = threadIdx.x; i < kRankTile; i += 256) tile[i] = base + i < F ? key(imp[base + i]) : 0.f;
     __syncthreads();
     const int n = min(kRankTile, F - base);
     for (int i = 0; i < n; ++i) {

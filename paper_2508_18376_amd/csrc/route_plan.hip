@@ -524,8 +524,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   //    (a) few row tiles (decode-sized batches): fewer items than units, each streaming a whole
   //        column tile of W2 alone -> all items are split, into as many ranges as keep the list
   //        within one item per unit;
-  //    (b) the last round of a longer list is less than half full -> its items are split so that
-  //        the round is about full.
+  //    (b) the last round of a longer list is only partly full -> its items are split where the shorter
+  //        pieces fill the units better (see below).
   const int W2n = total_tiles * L.ND2;
   int nsplit = 1, first_split = W2n;  // items first_split .. W2n-1 (in list order) are split nsplit ways
   if (L.split_items > 0 && W2n > 0) {
@@ -535,10 +535,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       while (nsplit < kMaxSplit && W2n * nsplit * 2 <= L.split_items && nsplit * 2 <= ksp) nsplit *= 2;
       first_split = 0;
     } else {
+      // The last round holds `rest` items for split_items compute units.  Cut n ways they are rest * n
+      // shorter items, which take ceil(rest * n / units) turns of 1/n of a round each (plus a fill and a
+      // write-out per piece, worth about eight K stages): 192 items cut in four are three turns of a
+      // quarter instead of a whole round at three quarters of the units.  The cheapest n that the pool
+      // of partial tiles can hold wins; n = 1 (cost: one round) if none is cheaper.
       const int rest = W2n % L.split_items;
-      if (rest > 0 && rest * 2 <= L.split_items) {
-        nsplit = min(min(L.split_items / rest, kMaxTailSplit), ksp);
-        first_split = W2n - rest;
+      if (rest > 0) {
+        float best = 1.0f;
+        const int item_stages = E_res > 0 ? L.P * (L.Fp / kBK) : L.F_shT / kBK;  // K stages of a long item
+        const float piece = 8.0f / (float)max(item_stages, 1);                  // per-piece overhead in units of such an item
+        for (int n = 2; n <= kMaxTailSplit && n <= ksp; ++n) {
+          if (rest * (n - 1) > kPoolTiles) break;
+          const int turns = (rest * n + L.split_items - 1) / L.split_items;
+          const float cost = (float)turns * (1.0f / (float)n + piece);
+          if (cost < best - 0.04f) {  // a clear gain only: every extra range costs a partial tile written and read
+            best = cost;
+            nsplit = n;
+          }
+        }
+        if (nsplit > 1) first_split = W2n - rest;
       }
     }
     if (nsplit == 1) first_split = W2n;

@@ -289,11 +289,15 @@ SPLIT_CASES = [
     ("shared_limits_the_split", spec_of(T=24, D=128, F=512, E=4, K=2, P=2, n_shared=1, F_sh=64, seed=42), "rate0.25", 2),
     ("one_token_split", spec_of(T=1, D=256, F=2048, E=8, K=2, P=2, seed=43), 0.0, 8),
     ("too_many_tiles_to_split", spec_of(T=1200, D=768, F=128, E=64, K=8, P=2, seed=44), "rate0.25", 1),
-    # 66 row tiles x 4 column tiles = 264 items: the 8 items of the second round are split 4 ways
-    ("last_round_nearly_empty", spec_of(T=8200, D=1024, F=256, E=4, K=2, P=2, seed=45), 0.0, 4),
+    # 66-67 row tiles x 4 column tiles = 264-268 items of 64 K stages: the few items of the second round are split
+    ("last_round_nearly_empty", spec_of(T=8200, D=1024, F=2048, E=4, K=2, P=2, seed=45), 0.0, ">1"),
+    # items of 8 K stages: a piece would be all fill and write-out, nothing is split
+    ("short_items_stay_whole", spec_of(T=8200, D=1024, F=256, E=4, K=2, P=2, seed=45), 0.0, 1),
     # same with shared experts, whose short contraction (2 stages) limits the split
-    ("last_round_with_shared", spec_of(T=5600, D=1024, F=256, E=4, K=2, P=2, n_shared=1, F_sh=64, seed=46), 0.0, 2),
-    ("last_round_under_drop", spec_of(T=8200, D=1024, F=256, E=4, K=2, P=2, seed=45), "rate0.25", None),
+    ("last_round_with_shared", spec_of(T=5600, D=1024, F=2048, E=4, K=2, P=2, n_shared=1, F_sh=64, seed=46), 0.0, 2),
+    ("last_round_under_drop", spec_of(T=8200, D=1024, F=2048, E=4, K=2, P=2, seed=45), "rate0.25", None),
+    # a last round at three quarters of the units (192 of 256 items): four pieces each make three full turns of a quarter
+    ("last_round_three_quarters_full", spec_of(T=7000, D=2048, F=2048, E=8, K=2, P=2, seed=47), 0.0, None),
 ]
 
 
@@ -305,6 +309,9 @@ def test_gemm2_split_k_on_few_row_tiles(oracle, name, spec, tau_kind, nsplit):
     y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
     counters = plan["counters"].cpu().numpy()
     tiles_x_cols = counters[2] * ((spec.D + 255) // 256)
+    if nsplit == ">1":
+        assert counters[3] > 1, counters
+        nsplit = int(counters[3])
     if nsplit is None:  # whatever the plan decided, it must be consistent
         nsplit = int(counters[3])
     assert counters[3] == nsplit, counters
@@ -312,7 +319,7 @@ def test_gemm2_split_k_on_few_row_tiles(oracle, name, spec, tau_kind, nsplit):
         assert counters[1] == tiles_x_cols * nsplit and counters[1] <= 256
     elif nsplit > 1:         # only the items of the last round are
         rest = tiles_x_cols % 256
-        assert counters[1] == tiles_x_cols + rest * (nsplit - 1) and rest * nsplit <= 256
+        assert counters[1] == tiles_x_cols + rest * (nsplit - 1) and rest * (nsplit - 1) <= 768
     else:
         assert counters[1] == tiles_x_cols
 

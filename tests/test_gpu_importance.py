@@ -113,6 +113,27 @@ def test_perm_from_importance_is_the_plain_order(oracle):
     layer.close()
 
 
+def test_perm_from_importance_with_nan_is_still_a_permutation():
+    import torch
+    from paper_2508_18376_amd import DualSparseLayer
+    rng = np.random.default_rng(5)
+    E, F = 2, 1500
+    imp = rng.standard_normal((E, F)).astype(np.float32)
+    bad = rng.choice(F, size=40, replace=False)
+    imp[0, bad] = np.nan
+    imp[1, :] = np.nan
+    layer = DualSparseLayer(d_model=32, d_ff=F, n_experts=E, top_k=1, n_part=1, max_tokens=8, dtype="f32")
+    perm = layer.importance_to_perm(to_dev(imp)).cpu().numpy()
+    torch.cuda.synchronize()
+    for e in range(E):
+        assert sorted(perm[e]) == list(range(F))
+    assert list(perm[0][-40:]) == sorted(bad.tolist())            # NaN neurons last, by id
+    v = imp[0][perm[0][:-40]]
+    assert np.all(v[:-1] >= v[1:])
+    assert list(perm[1]) == list(range(F))
+    layer.close()
+
+
 def test_profile_then_partition_then_forward(oracle):
     """Reconstruction end to end: importance (metric 1) -> perm -> packed weights -> dual-threshold
     forward; the oracle runs the layer with the permutation the GPU produced."""
