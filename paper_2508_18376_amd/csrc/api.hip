@@ -74,7 +74,10 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.row_cap = L.sh_rows + rt * L.BM;
   L.max_tiles = rt + shared_tiles(L, Tm);
   L.max_items1 = items1_whole_bound(L, Tm) + L.split_items / 2;  // a smaller batch may cut its last items in two
-  L.max_items2 = L.max_tiles * L.ND2 + (L.split_items > 0 ? kPoolTiles : 0);
+  // partial-output tiles the K splits of GEMM-2 can need: contexts whose largest batch has so few row
+  // tiles that every item is split (decode sizes) stay within one extra tile per compute unit
+  L.pool_tiles = L.split_items == 0 ? 0 : ((int64_t)L.max_tiles * L.ND2 * 2 <= L.split_items ? kSplitItems : kPoolTiles);
+  L.max_items2 = L.max_tiles * L.ND2 + L.pool_tiles;
 
   int64_t o = 0;
   auto take = [&](int64_t bytes) {
@@ -108,12 +111,12 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   const int64_t helem = L.mfma ? 2 : 4;  // H: half precision on the MFMA path, fp32 on the generic path
   L.o_H = take_big((int64_t)(L.row_cap - L.sh_rows) * L.F * helem);
   L.o_Hs = take_big((int64_t)L.sh_rows * L.F_shT * helem);
-  L.o_Yp = take_big((int64_t)L.row_cap * L.D * 4);
+  L.o_Yp = take_big((int64_t)L.row_cap * L.D * (L.yp_half ? 2 : 4));
   L.o_tau0 = take((int64_t)L.E * L.P * 4);
   L.o_sel = take((int64_t)(L.E + 1) * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both; row E: resident pairs
   L.o_logits = take((int64_t)Tm * L.E * 4);
   L.o_perm_check = take(((int64_t)L.E_res * L.F + 1) * 4);
-  L.o_pool = take_big(L.split_items > 0 ? (int64_t)kPoolTiles * kMfmaBM * kMfmaBN2 * (L.yp_half ? 2 : 4) : 0);  // partial outputs of split K ranges
+  L.o_pool = take_big((int64_t)L.pool_tiles * kMfmaBM * kMfmaBN2 * (L.yp_half ? 2 : 4));  // partial outputs of split K ranges
   L.o_split_of = take(L.split_items > 0 ? (int64_t)L.max_tiles * L.ND2 * 4 : 0);          // (row tile, column tile) -> first pool tile, or -1
   L.ws_bytes = o;
 

@@ -78,6 +78,7 @@ struct Layout {
                               // capacity for max_tokens, the copy a call hands to its kernels the boundary for its T
   int32_t row_cap;            // total row capacity
   int32_t max_tiles, max_items1, max_items2;
+  int32_t pool_tiles;         // partial-output tiles of the workspace (GEMM-2 K splits)
   // workspace byte offsets
   int64_t o_idx, o_w, o_keep, o_pair_row, o_bin_count, o_cursor, o_exp_nrows, o_exp_row0, o_counters;
   int64_t o_tile_bits, o_act_rank, o_items1, o_items2;
@@ -140,7 +141,7 @@ inline int items1_bound(const Layout& L, int T) {
 }
 inline int items2_bound(const Layout& L, int T) {
   const int whole = (routed_tiles_bound(L, T) + shared_tiles(L, T)) * L.ND2;
-  return whole + (L.split_items > 0 ? kPoolTiles : 0);  // every extra K range of a split item is one more item
+  return whole + L.pool_tiles;  // every extra K range of a split item is one more item
 }
 
 // launchers (each returns hipError_t of the launch)

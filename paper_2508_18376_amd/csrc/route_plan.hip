@@ -546,7 +546,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
         const int item_stages = E_res > 0 ? L.P * (L.Fp / kBK) : L.F_shT / kBK;  // K stages of a long item
         const float piece = 8.0f / (float)max(item_stages, 1);                  // per-piece overhead in units of such an item
         for (int n = 2; n <= kMaxTailSplit && n <= ksp; ++n) {
-          if (rest * (n - 1) > kPoolTiles) break;
+          if (rest * (n - 1) > L.pool_tiles) break;
           const int turns = (rest * n + L.split_items - 1) / L.split_items;
           const float cost = (float)turns * (1.0f / (float)n + piece);
           if (cost < best - 0.04f) {  // a clear gain only: every extra range costs a partial tile written and read
