@@ -380,25 +380,27 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     for (int i = 0; i < I; i += 2) {
       const int nb = (a_row0 >> 5) + i + 4 * half;  // weight block index; neurons of the tile: (nb/2)*32 ..
       char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (lane >> 5) * 4) * 2;
+      // one branch per block of sixteen values, so that their chains of dependent operations interleave
+      // (a select per value makes the compiler branch around every single evaluation)
+      if (kept) {
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        float h[4];
+        for (int vq = 0; vq < 4; ++vq) {
+          float h[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float gt = t.acc[i][j][vq * 4 + c], up = t.acc[i + 1][j][vq * 4 + c];
-          h[c] = kept ? epi_value<true>(0, gt, up) : 0.f;  // Swish(gate) * up (Eq. 4)
-        }
-        uint2 pk;
-        {
+          for (int c = 0; c < 4; ++c) h[c] = epi_value<true>(0, t.acc[i][j][vq * 4 + c], t.acc[i + 1][j][vq * 4 + c]);  // Swish(gate) * up (Eq. 4)
           // half precision, round to nearest: half a unit of the kept 10 fraction bits is added to the
           // magnitude (fp32 bit pattern + 2^12), then the packed conversion truncates.  Truncation never
           // yields infinity, so |h| beyond 65504 saturates.
 #pragma unroll
           for (int c = 0; c < 4; ++c) h[c] = __uint_as_float(__float_as_uint(h[c]) + 0x1000u);
+          uint2 pk;
           pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1]));
           pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3]));
+          *(uint2*)(srow + vq * 16) = pk;
         }
-        *(uint2*)(srow + vq * 16) = pk;
+      } else {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) *(uint2*)(srow + vq * 16) = make_uint2(0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);  // one block of rows and 32 neurons at a time: keeps the register pressure of the epilogue low
     }
