@@ -309,6 +309,10 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     else dma16(g.rsX, slot + BOFF + (q - NW) * 4096, g.xoff[q - NW], sX);
   };
   t.mainloop(g.KS1, begin, one, lds);
+  // the epilogue's addresses hang on a fresh opaque copy of the thread id: worked out before the main
+  // loop (where the compiler would move them) they would occupy registers all the way through it
+  asm volatile("" : "+v"(tid));
+  const int le = tid & 63;
 
   if constexpr (PROFILE) {
     // Importance profiling (Sec. 4.2 b): the metric of every (row, neuron) of the tile is summed over
@@ -324,7 +328,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     uint32_t keptmask = 0;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      const int r = b_row0 + j * 32 + (lane & 31);
+      const int r = b_row0 + j * 32 + (le & 31);
       const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
       keptmask |= (kept ? 1u : 0u) << j;
     }
@@ -351,7 +355,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
         for (int v = 0; v < 16; ++v) {
           float x = row_sum(sum[v]);   // over the sixteen lanes of a row, then the two rows of this half of the wavefront
           x += __shfl_xor(x, 16, 64);  // (a + b in one lane, b + a in the other: the same bits)
-          if ((lane & 31) == 0) part[(b_row0 ? 128 : 0) + (nb >> 1) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = x;
+          if ((le & 31) == 0) part[(b_row0 ? 128 : 0) + (nb >> 1) * 32 + 8 * (v >> 2) + 4 * (le >> 5) + (v & 3)] = x;
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -374,12 +378,12 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   block_barrier();  // every wave is done reading the last stage
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int r = b_row0 + j * 32 + (lane & 31);
+    const int r = b_row0 + j * 32 + (le & 31);
     const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
 #pragma unroll
     for (int i = 0; i < I; i += 2) {
       const int nb = (a_row0 >> 5) + i + 4 * half;  // weight block index; neurons of the tile: (nb/2)*32 ..
-      char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (lane >> 5) * 4) * 2;
+      char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (le >> 5) * 4) * 2;
       // one branch per block of sixteen values, so that their chains of dependent operations interleave
       // (a select per value makes the compiler branch around every single evaluation)
       if (kept) {
@@ -408,12 +412,21 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   __syncthreads();
   const int n_in = g.it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
   if (n_in < g.Fp && (!HALF || ((tid & 15) >> 3) == half)) {
-#pragma unroll 4
-    for (int c = 0; c < 16; ++c) {
-      const int r = c * 16 + (tid >> 4);
-      if (r < g.it.nfill) {  // rows [nrows, nfill) of the row tile keep nothing of this partition: zeros
-        const uint4 v = r < g.it.nrows ? *(const uint4*)(lds + r * kHsRow + (tid & 15) * 16) : make_uint4(0, 0, 0, 0);
-        *(uint4*)(g.H + (size_t)(g.hrow0 + r) * g.ld + (size_t)g.it.p * g.Fp + n_in) = v;
+    // four rows at a time: their reads first, whether or not the rows exist (pinned here: inside the
+    // branch each read would wait for its own LDS round trip), then the stores
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+#pragma unroll 1
+    for (int c0 = 0; c0 < 16; c0 += 4) {
+      u32x4_t v[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[c] = *(const u32x4_t*)(lds + ((c0 + c) * 16 + (tid >> 4)) * kHsRow + (tid & 15) * 16);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(v[c]));
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int r = (c0 + c) * 16 + (tid >> 4);
+        if (r < g.it.nfill)  // rows [nrows, nfill) of the row tile keep nothing of this partition: zeros
+          *(u32x4_t*)(g.H + (size_t)(g.hrow0 + r) * g.ld + (size_t)g.it.p * g.Fp + n_in) = r < g.it.nrows ? v[c] : u32x4_t{0, 0, 0, 0};
       }
     }
   }
@@ -532,6 +545,8 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
     else dma16(g.rsH, slot + (q - 4) * 4096, g.hoff[q - 4], sH);
   };
   t.mainloop(g.nstages, begin, one, lds);
+  asm volatile("" : "+v"(tid));  // see gemm1_tile: the epilogue's addresses are worked out after the main loop
+  const int le = tid & 63;
 
   // epilogue.  The weight fragment is the MFMA's A operand, so acc[i][j][v] is pair row
   // a_row0 + i*32 + lane%32, column b_row0 + j*32 + 8*(v/4) + 4*(lane/32) + v%4.  Each wavefront
@@ -547,14 +562,14 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   char* mine = lds + w * (RING::BYTES / 4);
   static_assert(32 * kYsRow <= RING::BYTES / 4, "a block of 32 rows fits a wavefront's quarter of the ring");
   block_barrier();  // every wave is done reading the last stage
-  const int cw = g.it.jd * kMfmaBN2 + b_row0 + (lane % kLanesRow) * kColsLane;  // first of this lane's columns in the write-out
+  const int cw = g.it.jd * kMfmaBN2 + b_row0 + (le % kLanesRow) * kColsLane;  // first of this lane's columns in the write-out
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
 #pragma unroll
     for (int j = 0; j < J; ++j)
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        char* at = mine + (lane & 31) * kYsRow + (j * 32 + vq * 8 + (lane >> 5) * 4) * kEl;
+        char* at = mine + (le & 31) * kYsRow + (j * 32 + vq * 8 + (le >> 5) * 4) * kEl;
         if constexpr (YH) {  // times 2^-10, saturating, round to nearest even
           float v[4];
 #pragma unroll
@@ -577,15 +592,25 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // the reads of up to four passes first, whether or not the row exists (they are pinned here: inside the
+    // branches below each would wait for its own LDS round trip), then the stores of the rows that do
+    constexpr int kPasses = 32 / kRowsPass, kBatch = kPasses < 4 ? kPasses : 4;
 #pragma unroll
-    for (int k = 0; k < 32 / kRowsPass; ++k) {
-      const int rl = k * kRowsPass + lane / kLanesRow;
-      const int r = a_row0 + i * 32 + rl;
-      const f32x4_t o = *(const f32x4_t*)(mine + rl * kYsRow + (lane % kLanesRow) * 16);  // 16 bytes: 4 floats or 8 halves
-      if (r < g.it.nrows && cw < g.D) {
-        f32x4_t* dst = (f32x4_t*)(g.Y + ((size_t)r * g.ldy + b_row0 + (lane % kLanesRow) * kColsLane) * kEl);
-        if (NT) __builtin_nontemporal_store(o, dst);
-        else *dst = o;
+    for (int k0 = 0; k0 < kPasses; k0 += kBatch) {
+      f32x4_t o[kBatch];
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k)
+        o[k] = *(const f32x4_t*)(mine + ((k0 + k) * kRowsPass + le / kLanesRow) * kYsRow + (le % kLanesRow) * 16);  // 16 bytes: 4 floats or 8 halves
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) asm volatile("" : "+v"(o[k]));
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const int r = a_row0 + i * 32 + (k0 + k) * kRowsPass + le / kLanesRow;
+        if (r < g.it.nrows && cw < g.D) {
+          f32x4_t* dst = (f32x4_t*)(g.Y + ((size_t)r * g.ldy + b_row0 + (le % kLanesRow) * kColsLane) * kEl);
+          if (NT) __builtin_nontemporal_store(o[k], dst);
+          else *dst = o[k];
+        }
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
