@@ -275,7 +275,9 @@ struct G1Args {
   bool sh;
   int KS1, Fp, ld, hrow0, epi;
   i32x4 rsW, rsX;
-  uint32_t xoff[4], woff, lds_w;
+  uint32_t woff, lds_w;
+  const int32_t* row_token;  // token of every pair row
+  uint32_t x_row_bytes;
   const uint8_t* row_bits;
   uint16_t* H;
 };
@@ -298,6 +300,15 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   const int half = HALF ? g.it.half - 1 : 0;
   WaveTile<I, J, I, NJ, NW + NX, false, NS, SB, BOFF> t;
   t.init(a_row0, b_row0, lane);
+  // this thread's part of the activation gather: chunk (tid & 3) of rows i * 64 + (tid >> 2).  Worked out
+  // here, per instantiation, for the same reason as the lane offsets above.
+  uint32_t xoff[NX];
+#pragma unroll
+  for (int i = 0; i < NX; ++i) {
+    const int r = i * 64 + (tid >> 2);
+    const int rr = r < g.it.nrows ? r : g.it.nrows - 1;  // rows past the end re-read the last valid row
+    xoff[i] = (uint32_t)g.row_token[g.it.row0 + rr] * g.x_row_bytes + (uint32_t)(swz_chunk(r, tid & 3) * 16);
+  }
   uint32_t slot = 0, sW = 0, sX = 0;
   auto begin = [&](int st) {
     slot = (uint32_t)(st % NS) * SB + g.lds_w;
@@ -306,7 +317,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   };
   auto one = [&](int q) {
     if (q < NW) dma16(g.rsW, slot + q * 4096, g.woff, sW + q * 4096);
-    else dma16(g.rsX, slot + BOFF + (q - NW) * 4096, g.xoff[q - NW], sX);
+    else dma16(g.rsX, slot + BOFF + (q - NW) * 4096, xoff[q - NW], sX);
   };
   t.mainloop(g.KS1, begin, one, lds);
   // the epilogue's addresses hang on a fresh opaque copy of the thread id: worked out before the main
@@ -432,14 +443,13 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   }
 }
 
-// What every GEMM-1 workgroup does first: its item, the buffer descriptors, and this thread's part
-// of the activation gather (chunk (tid & 3) of rows i*64 + (tid >> 2), i < SLABS).
-template <int SLABS>
+// What every GEMM-1 workgroup does first: its item and the buffer descriptors.
 __device__ __forceinline__ void gemm1_setup(G1Args& g, int item_id, const Layout& L, int T, const char* packed, const uint16_t* x, char* ws,
                                             int epi, const char* lds, int tid, int w) {
   g.it = ((const Item1*)(ws + L.o_items1))[item_id];
-  const int32_t* row_token = (const int32_t*)(ws + L.o_row_token);
   g.row_bits = (const uint8_t*)(ws + L.o_row_bits);
+  g.row_token = (const int32_t*)(ws + L.o_row_token);
+  g.x_row_bytes = (uint32_t)(L.D * 2);
   g.sh = g.it.e == L.E_res;
   g.KS1 = L.D / kBK;
   g.Fp = g.sh ? L.F_shT : L.Fp;
@@ -451,13 +461,6 @@ __device__ __forceinline__ void gemm1_setup(G1Args& g, int item_id, const Layout
   g.H = g.sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
   g.hrow0 = g.sh ? g.it.row0 : g.it.row0 - L.sh_rows;
   g.epi = epi;
-#pragma unroll
-  for (int i = 0; i < SLABS; ++i) {
-    const int r = i * 64 + (tid >> 2);
-    const int rr = r < g.it.nrows ? r : g.it.nrows - 1;  // rows past the end re-read the last valid row
-    const int tok = row_token[g.it.row0 + rr];
-    g.xoff[i] = (uint32_t)tok * (uint32_t)(L.D * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
-  }
   g.woff = (uint32_t)tid * 16;
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
 }
@@ -472,7 +475,7 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   if (item_id >= ((const int32_t*)(ws + L.o_counters))[0]) return;  // past the end of the list
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   G1Args g;
-  gemm1_setup<4>(g, item_id, L, T, packed, x, ws, epi, lds, tid, w);
+  gemm1_setup(g, item_id, L, T, packed, x, ws, epi, lds, tid, w);
   if (PROFILE && g.sh) return;  // importance is profiled for the routed experts only
 
   if (g.it.half) {  // at most 128 rows (the plan guarantees it): wavefronts 0 and 1 multiply, 64 weight rows each
@@ -510,7 +513,7 @@ struct G2Args {
   Item2 it;
   int np, KSp, nstages, D;
   i32x4 rsW, rsH;
-  uint32_t hoff[4], woff, lds_w;
+  uint32_t woff, lds_w, h_row_bytes;
   char* Y;       // where row 0, column 0 of this item's output tile goes (float, or half precision: YH)
   int ldy;       // its row stride in elements: D in Yp, 256 in a pool tile
   float yscale;  // YH: the accumulators are stored times this power of two (see kYpHalfScale)
@@ -522,8 +525,17 @@ template <int I, int J, int NI, bool NT, bool YH, class RING = RingWhole>
 __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
   asm volatile("" : "+v"(tid));  // see gemm1_tile
   const int lane = tid & 63;
-  WaveTile<I, J, NI, J, (I == 8 ? 4 + (NI * 32 + 63) / 64 : kLoadsPerStage), true, RING::NS, RING::SB, RING::BOFF, true> t;
+  constexpr int NH = I == 8 ? (NI * 32 + 63) / 64 : 4;  // loads per thread and stage for the rows of H (64 rows each)
+  WaveTile<I, J, NI, J, 4 + NH, true, RING::NS, RING::SB, RING::BOFF, true> t;
   t.init(a_row0, b_row0, lane);
+  // this thread's part of the rows of H: chunk (tid & 3) of rows i * 64 + (tid >> 2) (per instantiation, see gemm1_tile)
+  uint32_t hoff[NH];
+#pragma unroll
+  for (int i = 0; i < NH; ++i) {
+    const int r = i * 64 + (tid >> 2);
+    const int rr = r < g.it.nrows ? r : g.it.nrows - 1;
+    hoff[i] = (uint32_t)rr * g.h_row_bytes + (uint32_t)(swz_chunk(r, tid & 3) * 16);
+  }
   // stages run over the partitions some row of this tile keeps (Sec. 4: dropped units cost nothing);
   // begin() is called with increasing st, so a running cursor maps st -> K position.
   int p_cur = 0, k_in = 0;
@@ -542,7 +554,7 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   };
   auto one = [&](int q) {
     if (q < 4) dma16(g.rsW, slot + RING::BOFF + q * 4096, g.woff, sW + q * 4096);
-    else dma16(g.rsH, slot + (q - 4) * 4096, g.hoff[q - 4], sH);
+    else dma16(g.rsH, slot + (q - 4) * 4096, hoff[q - 4], sH);
   };
   t.mainloop(g.nstages, begin, one, lds);
   asm volatile("" : "+v"(tid));  // see gemm1_tile: the epilogue's addresses are worked out after the main loop
@@ -619,8 +631,7 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   }
 }
 
-// What every GEMM-2 workgroup does first (see gemm1_setup); SLABS: 64-row groups of H it may load.
-template <int SLABS>
+// What every GEMM-2 workgroup does first (see gemm1_setup).
 __device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout& L, const char* packed, char* ws, const char* lds, int tid,
                                             int w) {
   g.it = ((const Item2*)(ws + L.o_items2))[item_id];
@@ -647,12 +658,7 @@ __device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout
     g.ldy = kMfmaBN2;
   }
   g.yscale = kYpHalfScale;
-#pragma unroll
-  for (int i = 0; i < SLABS; ++i) {
-    const int r = i * 64 + (tid >> 2);
-    const int rr = r < g.it.nrows ? r : g.it.nrows - 1;
-    g.hoff[i] = (uint32_t)rr * (uint32_t)(ld * 2) + (uint32_t)(swz_chunk(r, tid & 3) * 16);
-  }
+  g.h_row_bytes = (uint32_t)(ld * 2);
   g.woff = (uint32_t)tid * 16;
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
   g.nstages = 0;
@@ -668,7 +674,7 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   if (item_id >= ((const int32_t*)(ws + L.o_counters))[1]) return;  // past the end of the list
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   G2Args g;
-  gemm2_setup<4>(g, item_id, L, packed, ws, lds, tid, w);
+  gemm2_setup(g, item_id, L, packed, ws, lds, tid, w);
 
   if (g.it.nrows == kMfmaBM) {
     gemm2_tile<4, 4, 4, NT, YH>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
