@@ -36,7 +36,29 @@ def draw_case(seed):
     return spec, max_tokens, tau_kind, bool(rng.random() < 0.3), kind
 
 
-CASES = [draw_case(s) for s in range(32)]
+def draw_medium_case(seed):
+    """Matrix-core path only, several row tiles per expert: full tiles, ragged tails of every length, half
+    neuron tiles, K splits of short item lists, all at once."""
+    rng = np.random.default_rng(5000 + seed)
+    E = int(rng.choice([1, 2, 4, 8, 16]))
+    K = int(rng.integers(1, min(E, 4) + 1))
+    P = int(rng.choice([1, 2, 2, 4, 4, 8]))
+    D = 32 * int(rng.integers(2, 25))
+    Fp = 32 * int(rng.integers(1, 13))
+    F_sh = 32 * int(rng.integers(1, 9))
+    n_shared = int(rng.choice([0, 0, 1, 2]))
+    T = int(rng.integers(200, 3000))
+    max_tokens = T + int(rng.choice([0, 1, 500]))
+    lo = int(rng.integers(0, E)) if E > 1 and rng.random() < 0.3 else 0
+    hi = int(rng.integers(lo + 1, E + 1)) if lo > 0 or (E > 1 and rng.random() < 0.2) else E
+    tau_kind = ["zero", "rate", "ragged", "rate", "ragged", "rate"][int(rng.integers(0, 6))]
+    spec = LayerSpec(name="med%d" % seed, T=T, D=D, F=Fp * P, E=E, K=K, P=P, dtype="bf16", seed=7000 + seed, n_shared=n_shared,
+                     F_sh=F_sh if n_shared else 0, resident=(lo, hi), x_std=1.0, w_std=float(rng.choice([0.05, 0.2])),
+                     perm_kind=str(rng.choice(["random", "identity", "reversed"])))
+    return spec, max_tokens, tau_kind, bool(rng.random() < 0.3), "bf16_mfma"
+
+
+CASES = [draw_case(s) for s in range(32)] + [draw_medium_case(s) for s in range(24)]
 
 
 @pytest.mark.parametrize("spec,max_tokens,tau_kind,renorm,kind", CASES, ids=["%s_%s" % (c[0].name, c[4]) for c in CASES])
