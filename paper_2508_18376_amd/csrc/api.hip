@@ -65,6 +65,9 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   // XCD's L2 from one row tile to the next: the row tiles that share a column tile are then made
   // adjacent so they stream it together (measured: -9 % on d_ff 14336, +7 % on d_ff 1024..1408).
   L.g2_rows_inner = (int64_t)L.F * kMfmaBN2 * 2 >= (1 << 20) ? 1 : 0;
+  // tall items need whole neuron tiles (the variant for a half-full last neuron tile has no tall form)
+  auto whole_tiles = [](int n) { const int m = n % kMfmaNeur; return m == 0 || m > kMfmaNeur / 2; };
+  L.tall_tiles = L.mfma && whole_tiles(L.Fp) && (L.n_shared == 0 || whole_tiles(L.F_shT)) ? 1 : 0;
   const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   L.nsub = 1 << nsub_bits;
   L.nbins = L.E_res * L.nsub;
@@ -490,6 +493,7 @@ int moe_profile_importance(dsmoe_ctx* ctx_, const void* packed, const void* x, c
   if (((uintptr_t)workspace & 255) != 0) return DSMOE_EINVAL;
   if (T > ctx->L.max_tokens) return DSMOE_EINVAL;
   Layout L = ctx->L;  // per-call boundary of the shared rows, as in the forward call
+  L.tall_tiles = 0;   // the profiling variant of GEMM-1 has no tall form
   L.sh_rows = L.n_shared > 0 ? (int)align_up(T, L.BM) : 0;
   ctx->last_sh_rows = L.sh_rows;
   hipStream_t s = (hipStream_t)stream;

@@ -15,6 +15,7 @@ constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
 constexpr int kSplitItems = 256;  // one GEMM-2 item per compute unit: the granularity K splits aim at (measured best)
 constexpr int kMaxSplit = 8;      // most K ranges an item is split into when there are few row tiles (decode-sized batches)
+constexpr int kTallExtra = 64;    // rows beyond a full tile that a tall GEMM-1 item takes along
 constexpr int kMaxTailSplit = 8;  // most K ranges an item of the last, partly filled round of items is split into
 constexpr int kPoolTiles = 768;   // partial-output tiles (256 x 256) the extra K ranges can need at most
 // Half-precision partial outputs hold the GEMM-2 accumulators times 2^-10.  The accumulators are sums
@@ -67,6 +68,7 @@ struct Layout {
   int32_t yp_half;  // MFMA path: GEMM-2 stores its per-pair partial outputs (Yp, pool tiles) in half precision (times kYpHalfScale)
   int32_t h_shift;  // MFMA path: the intermediate activation is stored times 2^h_shift (folded into the packed W3)
   int32_t g2_rows_inner;  // GEMM-2 item order: 1 = (expert, column tile, row tile), 0 = (expert, row tile, column tile)
+  int32_t tall_tiles;     // MFMA path: a GEMM-1 item of a full row tile also takes the expert's last row tile if that has at most kTallExtra rows
   int32_t split_items;  // kSplitItems if GEMM-2 may split K (MFMA path), else 0
   int32_t max_tokens;
   // plan geometry

@@ -49,7 +49,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 
 constexpr int kStages = 4;                          // LDS ring depth
 constexpr int kStagePair = 2 * kStageBytes;         // A tile + B tile of one stage: 32 KiB
-constexpr int kLdsBytes = kStages * kStagePair;     // 128 KiB
+constexpr int kLdsBytes = kStages * (kStagePair + 64 * kBK * 2);  // 144 KiB: four stages of the tallest tile (16 KiB A + 320 rows of B)
 // An LDS ring: NS stages, SB bytes apart, the MFMA B tile BOFF bytes into a stage.
 template <int NS_, int SB_, int BOFF_>
 struct Ring {
@@ -59,6 +59,10 @@ using RingWhole = Ring<kStages, kStagePair, kStageBytes>;  // 16 KiB A tile + 16
 // half-tile items of GEMM-1 (at most 128 rows): 8 KiB of weights + 8 KiB of rows, twice as deep
 using RingHalf = Ring<8, kStageBytes, kStageBytes / 2>;
 static_assert(RingHalf::BYTES <= kLdsBytes, "same allocation");
+// tall tiles of GEMM-1 (a full row tile that also takes the expert's last 1..64 rows): 16 KiB A tile + 320 rows of B
+constexpr int kTallRows = kMfmaBM + 64;
+using RingTall = Ring<kStages, kStageBytes + kTallRows * (kBK * 2), kStageBytes>;
+static_assert(RingTall::BYTES <= kLdsBytes, "same allocation");
 constexpr int64_t kStreamOutBytes = 192ll << 20;    // GEMM-2 outputs larger than this bypass the caches (256 MiB of last-level cache, shared with H)
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
@@ -99,6 +103,16 @@ __device__ __forceinline__ void wait_vm() {
 }
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// This thread's index in the workgroup, worked out anew from the wavefront's index (a scalar) and the lane id.
+// The tile functions below start from it instead of from a value handed down: a thread index that lives
+// in one register from the top of the kernel through all of its variants is what the register allocator
+// parks in scratch first (volatile, so that the copies are not merged back into one).
+__device__ __forceinline__ int fresh_tid(int w) {
+  int lane;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+  return (w << 6) | lane;
+}
+
 // XCD-aware order: consecutive block ids land on different XCDs (round robin over 8), so give
 // each XCD a run of 32 consecutive work items out of every 256: items that share a weight tile
 // then share an L2.
@@ -111,6 +125,7 @@ __device__ __forceinline__ int xcd_remap(int b) {
 template <int I, int J>
 struct Frags {
   bf16x8 a[I], b[J];
+  bf16x8 bx;  // tall tiles: one more block of B rows
 };
 
 // One wavefront's share of the tile product.
@@ -129,20 +144,42 @@ struct Frags {
 // an instruction that stalls the stream, so the reads and loads are threaded between the MFMAs by
 // hand and pinned with scheduling barriers.
 // F16: the operands are half precision (GEMM-2) instead of bf16; the fragments are 16 bytes either way.
+// EX (tall tiles): the wavefront also multiplies its A blocks with one more block of 32 B rows (bx).  The 256
+// accumulation registers are taken, so these I products accumulate in ordinary registers, which the
+// compiler only allows for all matrix instructions of a kernel or none: they are written as inline
+// assembly.  Nothing but the next such instruction (and, much later, the epilogue) touches their registers.
 template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false, int NS = kStages, int SB = kStagePair, int BOFF = kStageBytes,
-          bool F16 = false>
+          bool F16 = false, bool EX = false>
 struct WaveTile {
   static_assert(I * J == 16 || I * J == 8, "256 or 128 accumulator registers");
+  static_assert(!EX || (!SWAP && !F16 && NI == I), "extra block: GEMM-1, full tiles");
   static constexpr int M = I * J;  // MFMAs per K substep
-  static_assert(NLOADS >= 1 && NLOADS <= kLoadsPerStage, "DMA loads per thread and stage");
+  static_assert(NLOADS >= 1 && NLOADS <= kLoadsPerStage + (EX ? 1 : 0), "DMA loads per thread and stage");
   f32x16 acc[I][J];
+  f32x16 accx[EX ? I : 1];  // EX: A block i x the extra B block
   uint32_t offA, offB;  // byte offset of this lane's row in the A / B tile of a stage (block 0)
+  uint32_t offBx;       // EX: the same for the extra B block
+  int bx_mode;          // EX, the same for the whole wavefront: 0 no extra block; 3: all four A blocks x the extra block;
+                        // 1: only a[0] and a[1] (the wavefront that shares the A blocks takes the other two)
+  uint32_t offA2;       // EX: byte offset of A blocks 2 and 3.  a[i] is A block (i + arot) & 3 of the wavefront's four:
+                        // with arot = 2 the wavefront's "first two" blocks are the other wavefront's last two
   uint32_t c0, c1;      // swizzled chunk offset of substep 0 / 1
 
-  __device__ __forceinline__ void init(int a_row0, int b_row0, int lane) {
+  // bx_row0: first row of the extra B block (mode != 0)
+  __device__ __forceinline__ void init(int a_row0, int b_row0, int lane, int bx_row0 = 0, int mode = 0, int arot = 0) {
+    bx_mode = EX ? mode : 0;
+    offBx = (uint32_t)(bx_row0 + (lane & 31)) * kRowBytes + BOFF;
+    if (EX) {
+#pragma unroll
+      for (int i = 0; i < I; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accx[i][v] = 0.f;
+    }
     const int r32 = lane & 31, half = lane >> 5;
     const int sw = (r32 >> 2) & 3;
     offA = (uint32_t)(a_row0 + r32) * kRowBytes;
+    offA2 = offA + (uint32_t)(((2 + arot) & 3) * 32 * kRowBytes);  // a[2], a[3] sit at offA2 + (i - 2) * 2 KiB
+    if (EX) offA += (uint32_t)(arot * 32 * kRowBytes);
     offB = (uint32_t)(b_row0 + r32) * kRowBytes + BOFF;
     c0 = (uint32_t)((half ^ sw) * 16);
     c1 = (uint32_t)(((2 + half) ^ sw) * 16);
@@ -165,15 +202,17 @@ struct WaveTile {
     } else if (k <= J) {
       const int j = k - 1;
       if (act_j(j)) f.b[j] = *(const bf16x8*)(stage + offB + c + j * (32 * kRowBytes));
-    } else {
+    } else if (k < I + J) {
       const int i = k - J;
-      if (act_i(i)) f.a[i] = *(const bf16x8*)(stage + offA + c + i * (32 * kRowBytes));
+      if (act_i(i)) f.a[i] = *(const bf16x8*)(stage + (EX && i >= 2 ? offA2 + (i - 2) * (32 * kRowBytes) : offA + i * (32 * kRowBytes)) + c);
+    } else if (EX) {
+      if (bx_mode) f.bx = *(const bf16x8*)(stage + offBx + c);
     }
   }
 
   __device__ __forceinline__ void read_all(Frags<I, J>& f, const char* stage, uint32_t c) const {
 #pragma unroll
-    for (int k = 0; k < I + J; ++k) read_k(f, stage, c, k);
+    for (int k = 0; k < I + J + (EX ? 1 : 0); ++k) read_k(f, stage, c, k);
   }
 
   // 16 MFMAs on `cur`; between them the I+J reads of the next substep into `nxt` and, if DMA,
@@ -181,7 +220,7 @@ struct WaveTile {
   template <bool READS, bool DMA, class One>
   __device__ __forceinline__ void half_stage(const Frags<I, J>& cur, Frags<I, J>& nxt, const char* nxt_stage, uint32_t nxt_c,
                                             One&& one) {
-    constexpr int R = I + J;
+    constexpr int R = I + J + (EX ? 1 : 0);
 #pragma unroll
     for (int m = 0; m < M; ++m) {
       const int i = m / J, j = m % J;
@@ -194,6 +233,7 @@ struct WaveTile {
       }
       if (M == 16) {  // a DMA slot after every second MFMA, or after every one of 8
         if (DMA && (m & 1) && (m >> 1) < NLOADS) one(m >> 1);
+        if (DMA && m == 0 && NLOADS > 8) one(8);  // the ninth load of a tall tile
       } else {
         if (DMA && m < NLOADS) one(m);
       }
@@ -202,6 +242,19 @@ struct WaveTile {
         for (int k = (m * R) / M; k < ((m + 1) * R) / M; ++k) read_k(nxt, nxt_stage, nxt_c, k);
       }
       if (m & 1) __builtin_amdgcn_sched_barrier(0);
+    }
+    // the extra block's products last: their operands have long arrived (first, they would wait for the
+    // LDS reads issued at the end of the half stage before)
+    if constexpr (EX) {
+      static_assert(!EX || I == 4, "mode 1 splits four A blocks between two wavefronts");
+#define DSMOE_EXTRA_MFMA(C, A) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(C) : "v"(A), "v"(cur.bx))
+      DSMOE_EXTRA_MFMA(accx[0], cur.a[0]);
+      DSMOE_EXTRA_MFMA(accx[1], cur.a[1]);
+      if (bx_mode == 3) {
+        DSMOE_EXTRA_MFMA(accx[2], cur.a[2]);
+        DSMOE_EXTRA_MFMA(accx[3], cur.a[3]);
+      }
+#undef DSMOE_EXTRA_MFMA
     }
   }
 
@@ -275,7 +328,7 @@ struct G1Args {
   bool sh;
   int KS1, Fp, ld, hrow0, epi;
   i32x4 rsW, rsX;
-  uint32_t woff, lds_w;
+  uint32_t lds_w;
   const int32_t* row_token;  // token of every pair row
   uint32_t x_row_bytes;
   const uint8_t* row_bits;
@@ -285,12 +338,17 @@ struct G1Args {
 // MFMA A = weight rows, B = pair rows.  Weight rows come in blocks of 32: block 2b is the gate
 // projection of neurons 32b .. 32b+31 of the tile, block 2b+1 their up projection.
 // NW / NX: 4 KiB loads per thread and stage for the weight tile / for the rows (64 rows each).
-template <int I, int J, int NJ, bool PROFILE, int NW = 4, bool HALF = false, class RING = RingWhole, int NX = (J == 8 ? (NJ * 32 + 63) / 64 : 4)>
-__device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int tid) {
-  // Each instantiation derives its lane-dependent offsets from its own opaque copy of the thread
-  // id: shared, they would stay live across all the instantiations of the kernel and be parked in
+// TALL: a full row tile that also takes the 1..64 rows its expert has beyond it (rows 256..319 of the item: each
+// wavefront multiplies its four weight blocks with one more block of 32 rows, see WaveTile), so that those
+// rows do not pull the whole weight tile through a second compute unit.
+template <int I, int J, int NJ, bool PROFILE, int NW = 4, bool HALF = false, class RING = RingWhole, int NX = (J == 8 ? (NJ * 32 + 63) / 64 : 4),
+          bool TALL = false>
+__device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row0, int b_row0, int w) {
+  static_assert(!TALL || (I == 4 && J == 4 && NJ == 4 && NW == 4 && !HALF && NX == 5 && !PROFILE), "tall tiles: 2 x 2 wavefronts, 320 rows, the layer's pass only");
+  // Each instantiation derives its lane-dependent offsets from its own copy of the thread id:
+  // shared, they would stay live across all the instantiations of the kernel and be parked in
   // scratch, and a scratch reload inside a main loop waits for vmcnt(0), which drains the DMA queue.
-  asm volatile("" : "+v"(tid));
+  int tid = fresh_tid(w);
   const int lane = tid & 63;
   // the ragged layout (J == 8) walks all pair rows: only the 64-row groups that exist are loaded
   // HALF: one half (64 neurons) of a neuron tile under at most 128 pair rows, in the streaming
@@ -298,8 +356,13 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
   // flight as with whole tiles; wavefronts 2 and 3 only help to load (NJ == 0).
   constexpr int NS = RING::NS, SB = RING::SB, BOFF = RING::BOFF;
   const int half = HALF ? g.it.half - 1 : 0;
-  WaveTile<I, J, I, NJ, NW + NX, false, NS, SB, BOFF> t;
-  t.init(a_row0, b_row0, lane);
+  WaveTile<I, J, I, NJ, NW + NX, false, NS, SB, BOFF, false, TALL> t;
+  // tall tiles, up to 32 extra rows: both wavefronts of a weight half take rows 256..287, two weight blocks each;
+  // up to 64: the wavefronts of the first / second half of the rows take rows 256..287 / 288..319, all four blocks
+  const bool two_blocks = g.it.nrows > kMfmaBM + 32;
+  const int bx_row0 = kMfmaBM + (two_blocks ? b_row0 >> 2 : 0);
+  const int arot = TALL && !two_blocks && b_row0 ? 2 : 0;  // which two of the four weight blocks are this wavefront's "first two"
+  t.init(a_row0, b_row0, lane, bx_row0, !TALL ? 0 : two_blocks ? 3 : 1, arot);
   // this thread's part of the activation gather: chunk (tid & 3) of rows i * 64 + (tid >> 2).  Worked out
   // here, per instantiation, for the same reason as the lane offsets above.
   uint32_t xoff[NX];
@@ -309,6 +372,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     const int rr = r < g.it.nrows ? r : g.it.nrows - 1;  // rows past the end re-read the last valid row
     xoff[i] = (uint32_t)g.row_token[g.it.row0 + rr] * g.x_row_bytes + (uint32_t)(swz_chunk(r, tid & 3) * 16);
   }
+  const uint32_t woff = (uint32_t)tid * 16;  // the weight tile is a linear stream: 16 bytes per thread and 4 KiB slab
   uint32_t slot = 0, sW = 0, sX = 0;
   auto begin = [&](int st) {
     slot = (uint32_t)(st % NS) * SB + g.lds_w;
@@ -316,13 +380,13 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     sX = (uint32_t)(st * kRowBytes);
   };
   auto one = [&](int q) {
-    if (q < NW) dma16(g.rsW, slot + q * 4096, g.woff, sW + q * 4096);
+    if (q < NW) dma16(g.rsW, slot + q * 4096, woff, sW + q * 4096);
     else dma16(g.rsX, slot + BOFF + (q - NW) * 4096, xoff[q - NW], sX);
   };
   t.mainloop(g.KS1, begin, one, lds);
-  // the epilogue's addresses hang on a fresh opaque copy of the thread id: worked out before the main
+  // the epilogue's addresses hang on a fresh copy of the thread id: worked out before the main
   // loop (where the compiler would move them) they would occupy registers all the way through it
-  asm volatile("" : "+v"(tid));
+  tid = fresh_tid(w);
   const int le = tid & 63;
 
   if constexpr (PROFILE) {
@@ -383,42 +447,50 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
 
   // epilogue.  acc[i][j][v]: weight row a_row0 + i*32 + 8*(v/4) + 4*(lane/32) + v%4, pair row
   // b_row0 + j*32 + lane%32.  Swish(gate) * up is rounded to half precision and parked in LDS as a
-  // [256 rows][128 neurons] tile (rows padded to 272 bytes against bank conflicts), then written
+  // [256 rows][128 neurons] tile (320 rows in a tall tile; rows padded to 272 bytes against bank conflicts), then written
   // out in whole 256-byte row segments: 16 lanes per row, 16 bytes per lane.
   constexpr int kHsRow = kMfmaNeur * 2 + 16;
   block_barrier();  // every wave is done reading the last stage
+  // one block of 32 rows x 32 neurons: gate and up accumulators of weight blocks i and i + 1, pair row r of this lane
+  auto emit = [&](const f32x16& gate, const f32x16& up, int r, bool kept, int i) {
+    const int nb = (a_row0 >> 5) + ((i + arot) & 3) + 4 * half;  // weight block index; neurons of the tile: (nb/2)*32 ..
+    char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (le >> 5) * 4) * 2;
+    // one branch per block of sixteen values, so that their chains of dependent operations interleave
+    // (a select per value makes the compiler branch around every single evaluation)
+    if (kept) {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        float h[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) h[c] = epi_value<true>(0, gate[vq * 4 + c], up[vq * 4 + c]);  // Swish(gate) * up (Eq. 4)
+        // half precision, round to nearest: half a unit of the kept 10 fraction bits is added to the
+        // magnitude (fp32 bit pattern + 2^12), then the packed conversion truncates.  Truncation never
+        // yields infinity, so |h| beyond 65504 saturates.
+#pragma unroll
+        for (int c = 0; c < 4; ++c) h[c] = __uint_as_float(__float_as_uint(h[c]) + 0x1000u);
+        uint2 pk;
+        pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1]));
+        pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3]));
+        *(uint2*)(srow + vq * 16) = pk;
+      }
+    } else {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) *(uint2*)(srow + vq * 16) = make_uint2(0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // one block of rows and 32 neurons at a time: keeps the register pressure of the epilogue low
+  };
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int r = b_row0 + j * 32 + (le & 31);
     const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
 #pragma unroll
-    for (int i = 0; i < I; i += 2) {
-      const int nb = (a_row0 >> 5) + i + 4 * half;  // weight block index; neurons of the tile: (nb/2)*32 ..
-      char* srow = lds + r * kHsRow + ((nb >> 1) * 32 + (le >> 5) * 4) * 2;
-      // one branch per block of sixteen values, so that their chains of dependent operations interleave
-      // (a select per value makes the compiler branch around every single evaluation)
-      if (kept) {
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          float h[4];
-#pragma unroll
-          for (int c = 0; c < 4; ++c) h[c] = epi_value<true>(0, t.acc[i][j][vq * 4 + c], t.acc[i + 1][j][vq * 4 + c]);  // Swish(gate) * up (Eq. 4)
-          // half precision, round to nearest: half a unit of the kept 10 fraction bits is added to the
-          // magnitude (fp32 bit pattern + 2^12), then the packed conversion truncates.  Truncation never
-          // yields infinity, so |h| beyond 65504 saturates.
-#pragma unroll
-          for (int c = 0; c < 4; ++c) h[c] = __uint_as_float(__float_as_uint(h[c]) + 0x1000u);
-          uint2 pk;
-          pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[0], h[1]));
-          pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(h[2], h[3]));
-          *(uint2*)(srow + vq * 16) = pk;
-        }
-      } else {
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) *(uint2*)(srow + vq * 16) = make_uint2(0, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);  // one block of rows and 32 neurons at a time: keeps the register pressure of the epilogue low
-    }
+    for (int i = 0; i < I; i += 2) emit(t.acc[i][j], t.acc[i + 1][j], r, kept, i);
+  }
+  if constexpr (TALL) {
+    const int r = bx_row0 + (le & 31);
+    const bool kept = r < g.it.nrows && ((g.row_bits[g.it.row0 + (r < g.it.nrows ? r : 0)] >> g.it.p) & 1);
+    emit(t.accx[0], t.accx[1], r, kept, 0);
+    if (t.bx_mode == 3) emit(t.accx[2], t.accx[3], r, kept, 2);
   }
   __syncthreads();
   const int n_in = g.it.jt * kMfmaNeur + (tid & 15) * 8;  // first of this lane's 8 neurons, inside the partition
@@ -427,7 +499,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     // branch each read would wait for its own LDS round trip), then the stores
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 #pragma unroll 1
-    for (int c0 = 0; c0 < 16; c0 += 4) {
+    for (int c0 = 0; c0 < (TALL ? kTallRows : kMfmaBM) / 16; c0 += 4) {
       u32x4_t v[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) v[c] = *(const u32x4_t*)(lds + ((c0 + c) * 16 + (tid >> 4)) * kHsRow + (tid & 15) * 16);
@@ -461,7 +533,7 @@ __device__ __forceinline__ void gemm1_setup(G1Args& g, int item_id, const Layout
   g.H = g.sh ? (uint16_t*)(ws + L.o_Hs) : (uint16_t*)(ws + L.o_H);
   g.hrow0 = g.sh ? g.it.row0 : g.it.row0 - L.sh_rows;
   g.epi = epi;
-  g.woff = (uint32_t)tid * 16;
+
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);  // this wavefront's 1 KiB slice of each 4 KiB slab
 }
 
@@ -481,29 +553,31 @@ __global__ __launch_bounds__(256) void gemm1_mfma_kernel(Layout L, int T, const 
   if (g.it.half) {  // at most 128 rows (the plan guarantees it): wavefronts 0 and 1 multiply, 64 weight rows each
     if (w < 2) {
       switch ((g.it.nrows + 31) >> 5) {
-        case 1: gemm1_tile<2, 4, 1, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
-        case 2: gemm1_tile<2, 4, 2, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
-        case 3: gemm1_tile<2, 4, 3, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
-        default: gemm1_tile<2, 4, 4, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, tid); break;
+        case 1: gemm1_tile<2, 4, 1, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, w); break;
+        case 2: gemm1_tile<2, 4, 2, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, w); break;
+        case 3: gemm1_tile<2, 4, 3, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, w); break;
+        default: gemm1_tile<2, 4, 4, PROFILE, 2, true, RingHalf, 2>(g, lds, w * 64, 0, w); break;
       }
     } else {
-      gemm1_tile<2, 4, 0, PROFILE, 2, true, RingHalf, 2>(g, lds, 0, 0, tid);
+      gemm1_tile<2, 4, 0, PROFILE, 2, true, RingHalf, 2>(g, lds, 0, 0, w);
     }
+  } else if (!PROFILE && g.it.nrows > kMfmaBM) {  // a full row tile and the expert's last 1..64 rows (the profiling pass plans without them)
+    gemm1_tile<4, 4, 4, false, 4, false, RingTall, 5, true>(g, lds, (w >> 1) * 128, (w & 1) * 128, w);
   } else if (g.it.nrows == kMfmaBM) {
     // 2 x 2 wavefronts, 128 weight rows x 128 pair rows each; a last neuron tile that is at most half
     // full takes the first 128 weight rows only (64 x 128 per wavefront)
-    if (g.Fp - g.it.jt * kMfmaNeur <= kMfmaNeur / 2) gemm1_tile<2, 4, 4, PROFILE, 2>(g, lds, (w >> 1) * 64, (w & 1) * 128, tid);
-    else gemm1_tile<4, 4, 4, PROFILE>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);
+    if (g.Fp - g.it.jt * kMfmaNeur <= kMfmaNeur / 2) gemm1_tile<2, 4, 4, PROFILE, 2>(g, lds, (w >> 1) * 64, (w & 1) * 128, w);
+    else gemm1_tile<4, 4, 4, PROFILE>(g, lds, (w >> 1) * 128, (w & 1) * 128, w);
   } else {  // 4 x 1: 64 weight rows x the ceil(nrows/32) blocks of pair rows that exist
     switch ((g.it.nrows + 31) >> 5) {
-      case 1: gemm1_tile<2, 8, 1, PROFILE>(g, lds, w * 64, 0, tid); break;
-      case 2: gemm1_tile<2, 8, 2, PROFILE>(g, lds, w * 64, 0, tid); break;
-      case 3: gemm1_tile<2, 8, 3, PROFILE>(g, lds, w * 64, 0, tid); break;
-      case 4: gemm1_tile<2, 8, 4, PROFILE>(g, lds, w * 64, 0, tid); break;
-      case 5: gemm1_tile<2, 8, 5, PROFILE>(g, lds, w * 64, 0, tid); break;
-      case 6: gemm1_tile<2, 8, 6, PROFILE>(g, lds, w * 64, 0, tid); break;
-      case 7: gemm1_tile<2, 8, 7, PROFILE>(g, lds, w * 64, 0, tid); break;
-      default: gemm1_tile<2, 8, 8, PROFILE>(g, lds, w * 64, 0, tid); break;
+      case 1: gemm1_tile<2, 8, 1, PROFILE>(g, lds, w * 64, 0, w); break;
+      case 2: gemm1_tile<2, 8, 2, PROFILE>(g, lds, w * 64, 0, w); break;
+      case 3: gemm1_tile<2, 8, 3, PROFILE>(g, lds, w * 64, 0, w); break;
+      case 4: gemm1_tile<2, 8, 4, PROFILE>(g, lds, w * 64, 0, w); break;
+      case 5: gemm1_tile<2, 8, 5, PROFILE>(g, lds, w * 64, 0, w); break;
+      case 6: gemm1_tile<2, 8, 6, PROFILE>(g, lds, w * 64, 0, w); break;
+      case 7: gemm1_tile<2, 8, 7, PROFILE>(g, lds, w * 64, 0, w); break;
+      default: gemm1_tile<2, 8, 8, PROFILE>(g, lds, w * 64, 0, w); break;
     }
   }
 }
@@ -513,7 +587,7 @@ struct G2Args {
   Item2 it;
   int np, KSp, nstages, D;
   i32x4 rsW, rsH;
-  uint32_t woff, lds_w, h_row_bytes;
+  uint32_t lds_w, h_row_bytes;
   char* Y;       // where row 0, column 0 of this item's output tile goes (float, or half precision: YH)
   int ldy;       // its row stride in elements: D in Yp, 256 in a pool tile
   float yscale;  // YH: the accumulators are stored times this power of two (see kYpHalfScale)
@@ -522,8 +596,8 @@ struct G2Args {
 // MFMA A = pair rows of H, B = output columns of W2 (both half precision).
 // YH: the partial outputs are stored in half precision (see launch_gemm2_mfma)
 template <int I, int J, int NI, bool NT, bool YH, class RING = RingWhole>
-__device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int tid) {
-  asm volatile("" : "+v"(tid));  // see gemm1_tile
+__device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int w) {
+  int tid = fresh_tid(w);  // see gemm1_tile
   const int lane = tid & 63;
   constexpr int NH = I == 8 ? (NI * 32 + 63) / 64 : 4;  // loads per thread and stage for the rows of H (64 rows each)
   WaveTile<I, J, NI, J, 4 + NH, true, RING::NS, RING::SB, RING::BOFF, true> t;
@@ -540,6 +614,7 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   // begin() is called with increasing st, so a running cursor maps st -> K position.
   int p_cur = 0, k_in = 0;
   while (p_cur < g.np && !((g.it.kmask >> p_cur) & 1)) ++p_cur;
+  const uint32_t woff = (uint32_t)tid * 16;
   uint32_t slot = 0, sW = 0, sH = 0;
   auto begin = [&](int st) {
     const int kt = p_cur * g.KSp + g.it.ks_lo + k_in;
@@ -553,11 +628,11 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
     sW = (uint32_t)(kt * kStageBytes);
   };
   auto one = [&](int q) {
-    if (q < 4) dma16(g.rsW, slot + RING::BOFF + q * 4096, g.woff, sW + q * 4096);
+    if (q < 4) dma16(g.rsW, slot + RING::BOFF + q * 4096, woff, sW + q * 4096);
     else dma16(g.rsH, slot + (q - 4) * 4096, hoff[q - 4], sH);
   };
   t.mainloop(g.nstages, begin, one, lds);
-  asm volatile("" : "+v"(tid));  // see gemm1_tile: the epilogue's addresses are worked out after the main loop
+  tid = fresh_tid(w);  // see gemm1_tile: the epilogue's addresses are worked out after the main loop
   const int le = tid & 63;
 
   // epilogue.  The weight fragment is the MFMA's A operand, so acc[i][j][v] is pair row
@@ -570,7 +645,6 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   constexpr int kLanesRow = J * 2 * kEl;         // lanes that share a row in the write-out (16 bytes each)
   constexpr int kColsLane = 16 / kEl;            // columns a lane writes out
   constexpr int kRowsPass = 64 / kLanesRow;      // rows per store instruction
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   char* mine = lds + w * (RING::BYTES / 4);
   static_assert(32 * kYsRow <= RING::BYTES / 4, "a block of 32 rows fits a wavefront's quarter of the ring");
   block_barrier();  // every wave is done reading the last stage
@@ -659,7 +733,7 @@ __device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout
   }
   g.yscale = kYpHalfScale;
   g.h_row_bytes = (uint32_t)(ld * 2);
-  g.woff = (uint32_t)tid * 16;
+
   g.lds_w = lds_offset(lds) + (uint32_t)(w * 1024);
   g.nstages = 0;
   for (int p = 0; p < g.np; ++p) g.nstages += ((g.it.kmask >> p) & 1) ? g.it.ks_n : 0;
@@ -677,17 +751,17 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   gemm2_setup(g, item_id, L, packed, ws, lds, tid, w);
 
   if (g.it.nrows == kMfmaBM) {
-    gemm2_tile<4, 4, 4, NT, YH>(g, lds, (w >> 1) * 128, (w & 1) * 128, tid);  // 2 x 2 wavefronts
+    gemm2_tile<4, 4, 4, NT, YH>(g, lds, (w >> 1) * 128, (w & 1) * 128, w);  // 2 x 2 wavefronts
   } else {  // 1 x 4: the ceil(nrows/32) blocks of pair rows that exist x 64 columns
     switch ((g.it.nrows + 31) >> 5) {
-      case 1: gemm2_tile<8, 2, 1, NT, YH>(g, lds, 0, w * 64, tid); break;
-      case 2: gemm2_tile<8, 2, 2, NT, YH>(g, lds, 0, w * 64, tid); break;
-      case 3: gemm2_tile<8, 2, 3, NT, YH>(g, lds, 0, w * 64, tid); break;
-      case 4: gemm2_tile<8, 2, 4, NT, YH>(g, lds, 0, w * 64, tid); break;
-      case 5: gemm2_tile<8, 2, 5, NT, YH>(g, lds, 0, w * 64, tid); break;
-      case 6: gemm2_tile<8, 2, 6, NT, YH>(g, lds, 0, w * 64, tid); break;
-      case 7: gemm2_tile<8, 2, 7, NT, YH>(g, lds, 0, w * 64, tid); break;
-      default: gemm2_tile<8, 2, 8, NT, YH>(g, lds, 0, w * 64, tid); break;
+      case 1: gemm2_tile<8, 2, 1, NT, YH>(g, lds, 0, w * 64, w); break;
+      case 2: gemm2_tile<8, 2, 2, NT, YH>(g, lds, 0, w * 64, w); break;
+      case 3: gemm2_tile<8, 2, 3, NT, YH>(g, lds, 0, w * 64, w); break;
+      case 4: gemm2_tile<8, 2, 4, NT, YH>(g, lds, 0, w * 64, w); break;
+      case 5: gemm2_tile<8, 2, 5, NT, YH>(g, lds, 0, w * 64, w); break;
+      case 6: gemm2_tile<8, 2, 6, NT, YH>(g, lds, 0, w * 64, w); break;
+      case 7: gemm2_tile<8, 2, 7, NT, YH>(g, lds, 0, w * 64, w); break;
+      default: gemm2_tile<8, 2, 8, NT, YH>(g, lds, 0, w * 64, w); break;
     }
   }
 }

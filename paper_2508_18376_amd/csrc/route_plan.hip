@@ -517,6 +517,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     }
     return last;
   };
+  // Tall GEMM-1 items: when an expert's last row tile has at most kTallExtra rows, the item of the tile
+  // before it (if that is full for the partition) computes them too, and the last tile gets no item of
+  // its own: a few rows would otherwise pull the whole weight tile through another compute unit.
+  auto absorbed = [&](int e, int i, int p) {
+    if (!L.tall_tiles || i == 0) return false;
+    if (i != (ne[e] + BM - 1) / BM - 1 || ne[e] - i * BM > kTallExtra) return false;
+    if (!((tbits[ts[e] + i] >> p) & 1)) return false;
+    return tile_rows_for(e, i - 1, p) == BM;
+  };
   // 5. GEMM-2 items: every tile x every output column tile.  The compute units take the items in
   //    list order, one each.  Where that leaves units idle, items are split along K: every extra K
   //    range is an item of its own that writes a partial-output tile into a pool, and the combine
@@ -603,7 +612,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       const int e = tile_expert(g);
       int cnt = 0;
       for (int j = ts[e]; j < g; ++j) cnt += (tbits[j] >> p) & 1;
-      const int act = (tbits[g] >> p) & 1;
+      const int act = ((tbits[g] >> p) & 1) && !absorbed(e, g - ts[e], p) ? 1 : 0;
       act_rank[(size_t)g * L.P + p] = act ? cnt : -1;
       if (g - ts[e] == (ne[e] + BM - 1) / BM - 1) {  // the expert's last tile closes the group
         ga[e * L.P + p] = cnt + act;
@@ -616,7 +625,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       int nt = (ne[e] + BM - 1) / BM;
       int cnt = 0;
       for (int i = 0; i < nt; ++i) {
-        bool act = (tbits[ts[e] + i] >> p) & 1;
+        bool act = ((tbits[ts[e] + i] >> p) & 1) && !absorbed(e, i, p);
         act_rank[(size_t)(ts[e] + i) * L.P + p] = act ? cnt : -1;
         cnt += act ? 1 : 0;
       }
@@ -657,6 +666,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     v.row0 = rs[e] + i * BM;
     v.nfill = min(ne[e] - i * BM, BM);
     v.nrows = tile_rows_for(e, i, p);
+    if (absorbed(e, i + 1, p)) {  // a tall item: the rows of the expert's short last tile follow directly
+      v.nrows += tile_rows_for(e, i + 1, p);
+      v.nfill += ne[e] - (i + 1) * BM;
+    }
     v.e = e;
     v.p = p;
     v.pad = 0;

@@ -383,6 +383,50 @@ def test_gemm1_items_of_a_sparse_last_round_are_halved(oracle, name, spec, tau_k
         assert whole <= counters[0] <= whole + rest, (counters, whole, rest)
 
 
+# ------------------------------------------------- tall GEMM-1 items: a full row tile + the expert's short last tile
+TALL_CASES = [
+    # name, spec, tau.  Rows per expert = T * K / E on average, spread by the random routing
+    ("one_tile_and_a_few_rows", spec_of(T=540, D=128, F=512, E=4, K=2, P=2, seed=60), 0.0),       # ~270 rows per expert
+    ("up_to_64_extra_rows", spec_of(T=600, D=192, F=512, E=4, K=2, P=2, seed=61), 0.0),            # ~300
+    ("several_tiles_then_a_few_rows", spec_of(T=1060, D=128, F=256, E=4, K=2, P=1, seed=62), 0.0),  # ~530
+    ("extra_rows_under_drop", spec_of(T=560, D=128, F=1024, E=4, K=2, P=4, seed=63), "rate0.25"),
+    ("extra_rows_general_masks", spec_of(T=373, D=128, F=1024, E=4, K=3, P=4, seed=64), "ragged"),
+    ("shared_rows_beyond_a_tile", spec_of(T=270, D=128, F=256, E=4, K=2, P=2, n_shared=1, F_sh=256, seed=65), 0.0),
+    ("half_full_last_neuron_tile_stays_plain", spec_of(T=540, D=128, F=384, E=4, K=2, P=2, seed=66), 0.0),  # Fp = 192 = 1.5 tiles
+]
+
+
+@pytest.mark.parametrize("name,spec,tau_kind", TALL_CASES, ids=[c[0] for c in TALL_CASES])
+def test_gemm1_tall_items(oracle, name, spec, tau_kind):
+    """When an expert's last row tile has at most 64 rows, the GEMM-1 item of the full tile before it computes
+    them too (for every partition whose rows fill that tile) and the short tile gets no item.  Same result
+    as the oracle either way; with no drop the item count shows the rule."""
+    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
+    if tau_kind != 0.0:
+        return
+    counters = plan["counters"].cpu().numpy()
+    Fp = spec.F // spec.P
+    nt1 = (Fp + 127) // 128
+    tall_ok = Fp % 128 == 0 or Fp % 128 > 64
+    if spec.n_shared:
+        F_sh = spec.n_shared * spec.F_sh
+        tall_ok = tall_ok and (F_sh % 128 == 0 or F_sh % 128 > 64)
+    def tiles(n):  # GEMM-1 items per neuron tile for n rows that all keep the partition
+        nt = (n + 255) // 256
+        return nt - 1 if tall_ok and nt >= 2 and n - (nt - 1) * 256 <= 64 else nt
+    rows = np.bincount(r.idx.ravel(), minlength=spec.E)[spec.lo:spec.hi]
+    expect = sum(tiles(int(n)) for n in rows) * spec.P * nt1
+    merged = sum(1 for n in rows if tiles(int(n)) < (int(n) + 255) // 256)
+    if spec.n_shared:
+        expect += tiles(spec.T) * ((spec.n_shared * spec.F_sh + 127) // 128)
+        merged += tiles(spec.T) < (spec.T + 255) // 256
+    if name != "half_full_last_neuron_tile_stays_plain":
+        assert merged > 0, rows  # the case is meant to have short last tiles
+    else:
+        assert merged == 0
+    assert counters[0] == expect, (counters, expect, rows)
+
+
 @pytest.mark.parametrize("dtype,T", [("bf16", 16), ("bf16", 300), ("f32", 40)])
 def test_shared_experts_with_a_batch_smaller_than_max_tokens(oracle, dtype, T):
     """The routed rows start right after the shared experts' rows of THIS batch: a context sized
