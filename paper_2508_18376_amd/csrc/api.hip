@@ -119,7 +119,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_sel = take((int64_t)(L.E + 1) * (kSelBins + 2) * 4);  // directly behind tau0: one fill clears both; row E: resident pairs
   L.o_logits = take((int64_t)Tm * L.E * 4);
   L.o_perm_check = take(((int64_t)L.E_res * L.F + 1) * 4);
-  L.o_pool = take_big((int64_t)L.pool_tiles * kMfmaBM * kMfmaBN2 * (L.yp_half ? 2 : 4));  // partial outputs of split K ranges
+  L.o_pool = take_big((int64_t)L.pool_tiles * kPoolRows * kMfmaBN2 * (L.yp_half ? 2 : 4));  // partial outputs of split K ranges
   L.o_split_of = take(L.split_items > 0 ? (int64_t)L.max_tiles * L.ND2 * 4 : 0);          // (row tile, column tile) -> first pool tile, or -1
   L.ws_bytes = o;
 

@@ -15,7 +15,9 @@ constexpr int kMaxPart = 8;
 constexpr int kSubBits = 4;  // partitions that take part in the row sort key
 constexpr int kSplitItems = 256;  // one GEMM-2 item per compute unit: the granularity K splits aim at (measured best)
 constexpr int kMaxSplit = 8;      // most K ranges an item is split into when there are few row tiles (decode-sized batches)
-constexpr int kTallExtra = 64;    // rows beyond a full tile that a tall GEMM-1 item takes along
+constexpr int kTallExtra = 64;    // rows beyond a full tile that a tall GEMM item takes along
+constexpr int kPoolRows = 256 + kTallExtra;  // rows of a partial-output tile of the pool (kMfmaBM + kTallExtra)
+constexpr int kSplitRowsOffset = 1 << 30;    // flag in the (row tile, column tile) -> pool tile table: the tile's rows sit kMfmaBM rows down
 constexpr int kMaxTailSplit = 8;  // most K ranges an item of the last, partly filled round of items is split into
 constexpr int kPoolTiles = 768;   // partial-output tiles (256 x 256) the extra K ranges can need at most
 // Half-precision partial outputs hold the GEMM-2 accumulators times 2^-10.  The accumulators are sums

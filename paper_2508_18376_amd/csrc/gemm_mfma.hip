@@ -63,6 +63,8 @@ static_assert(RingHalf::BYTES <= kLdsBytes, "same allocation");
 constexpr int kTallRows = kMfmaBM + 64;
 using RingTall = Ring<kStages, kStageBytes + kTallRows * (kBK * 2), kStageBytes>;
 static_assert(RingTall::BYTES <= kLdsBytes, "same allocation");
+// the same for GEMM-2, whose A tile holds the rows: 320 rows of A + 16 KiB B tile
+using RingTall2 = Ring<kStages, kStageBytes + kTallRows * (kBK * 2), kTallRows * (kBK * 2)>;
 constexpr int64_t kStreamOutBytes = 192ll << 20;    // GEMM-2 outputs larger than this bypass the caches (256 MiB of last-level cache, shared with H)
 constexpr int kLoadsPerStage = 2 * (kStageBytes / 16 / 256);  // per thread: 4 (A) + 4 (B)
 constexpr uint32_t kRsrcFlags = 0x00020000u;        // raw buffer, 32-bit elements
@@ -144,43 +146,45 @@ struct Frags {
 // an instruction that stalls the stream, so the reads and loads are threaded between the MFMAs by
 // hand and pinned with scheduling barriers.
 // F16: the operands are half precision (GEMM-2) instead of bf16; the fragments are 16 bytes either way.
-// EX (tall tiles): the wavefront also multiplies its A blocks with one more block of 32 B rows (bx).  The 256
-// accumulation registers are taken, so these I products accumulate in ordinary registers, which the
-// compiler only allows for all matrix instructions of a kernel or none: they are written as inline
-// assembly.  Nothing but the next such instruction (and, much later, the epilogue) touches their registers.
+// EX (tall tiles): the wavefront also multiplies its four weight blocks (the A blocks of GEMM-1, the B blocks
+// of GEMM-2) with one more block of 32 pair rows (bx).  The 256 accumulation registers are taken, so these
+// products accumulate in ordinary registers, which the compiler only allows for all matrix instructions of a
+// kernel or none: they are written as inline assembly.  Nothing but the next such instruction (and, much
+// later, the epilogue) touches their registers.
 template <int I, int J, int NI, int NJ, int NLOADS, bool SWAP = false, int NS = kStages, int SB = kStagePair, int BOFF = kStageBytes,
           bool F16 = false, bool EX = false>
 struct WaveTile {
   static_assert(I * J == 16 || I * J == 8, "256 or 128 accumulator registers");
-  static_assert(!EX || (!SWAP && !F16 && NI == I), "extra block: GEMM-1, full tiles");
+  static_assert(!EX || (I == 4 && J == 4 && NI == I && NJ == J && SWAP == F16), "extra block: full tiles of GEMM-1 (bf16) or GEMM-2 (f16, operands swapped)");
   static constexpr int M = I * J;  // MFMAs per K substep
   static_assert(NLOADS >= 1 && NLOADS <= kLoadsPerStage + (EX ? 1 : 0), "DMA loads per thread and stage");
   f32x16 acc[I][J];
-  f32x16 accx[EX ? I : 1];  // EX: A block i x the extra B block
+  f32x16 accx[EX ? 4 : 1];  // EX: weight block k x the extra block of pair rows
   uint32_t offA, offB;  // byte offset of this lane's row in the A / B tile of a stage (block 0)
-  uint32_t offBx;       // EX: the same for the extra B block
-  int bx_mode;          // EX, the same for the whole wavefront: 0 no extra block; 3: all four A blocks x the extra block;
-                        // 1: only a[0] and a[1] (the wavefront that shares the A blocks takes the other two)
-  uint32_t offA2;       // EX: byte offset of A blocks 2 and 3.  a[i] is A block (i + arot) & 3 of the wavefront's four:
-                        // with arot = 2 the wavefront's "first two" blocks are the other wavefront's last two
+  uint32_t offBx;       // EX: the same for the extra block of pair rows (in the B tile of GEMM-1, the A tile of GEMM-2)
+  int bx_mode;          // EX, the same for the whole wavefront: 0 no extra block; 3: all four weight blocks x the extra block;
+                        // 1: only the first two (the wavefront that shares the weight blocks takes the other two)
+  uint32_t offW2;       // EX: byte offset of weight blocks 2 and 3.  Weight fragment k is block (k + rot) & 3 of the wavefront's
+                        // four: with rot = 2 the wavefront's "first two" blocks are the other wavefront's last two
   uint32_t c0, c1;      // swizzled chunk offset of substep 0 / 1
 
-  // bx_row0: first row of the extra B block (mode != 0)
-  __device__ __forceinline__ void init(int a_row0, int b_row0, int lane, int bx_row0 = 0, int mode = 0, int arot = 0) {
+  // bx_row0: first row of the extra block of pair rows (mode != 0); rot: see offW2
+  __device__ __forceinline__ void init(int a_row0, int b_row0, int lane, int bx_row0 = 0, int mode = 0, int rot = 0) {
     bx_mode = EX ? mode : 0;
-    offBx = (uint32_t)(bx_row0 + (lane & 31)) * kRowBytes + BOFF;
+    offBx = (uint32_t)(bx_row0 + (lane & 31)) * kRowBytes + (SWAP ? 0 : BOFF);
     if (EX) {
 #pragma unroll
-      for (int i = 0; i < I; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) accx[i][v] = 0.f;
     }
     const int r32 = lane & 31, half = lane >> 5;
     const int sw = (r32 >> 2) & 3;
     offA = (uint32_t)(a_row0 + r32) * kRowBytes;
-    offA2 = offA + (uint32_t)(((2 + arot) & 3) * 32 * kRowBytes);  // a[2], a[3] sit at offA2 + (i - 2) * 2 KiB
-    if (EX) offA += (uint32_t)(arot * 32 * kRowBytes);
     offB = (uint32_t)(b_row0 + r32) * kRowBytes + BOFF;
+    // weight fragments 2, 3 sit at offW2 + (k - 2) * 2 KiB, fragments 0, 1 at the (rotated) block offset + k * 2 KiB
+    offW2 = (SWAP ? offB : offA) + (uint32_t)(((2 + rot) & 3) * 32 * kRowBytes);
+    if (EX) (SWAP ? offB : offA) += (uint32_t)(rot * 32 * kRowBytes);
     c0 = (uint32_t)((half ^ sw) * 16);
     c1 = (uint32_t)(((2 + half) ^ sw) * 16);
 #pragma unroll
@@ -201,10 +205,10 @@ struct WaveTile {
       f.a[0] = *(const bf16x8*)(stage + offA + c);
     } else if (k <= J) {
       const int j = k - 1;
-      if (act_j(j)) f.b[j] = *(const bf16x8*)(stage + offB + c + j * (32 * kRowBytes));
+      if (act_j(j)) f.b[j] = *(const bf16x8*)(stage + (EX && SWAP && j >= 2 ? offW2 + (j - 2) * (32 * kRowBytes) : offB + j * (32 * kRowBytes)) + c);
     } else if (k < I + J) {
       const int i = k - J;
-      if (act_i(i)) f.a[i] = *(const bf16x8*)(stage + (EX && i >= 2 ? offA2 + (i - 2) * (32 * kRowBytes) : offA + i * (32 * kRowBytes)) + c);
+      if (act_i(i)) f.a[i] = *(const bf16x8*)(stage + (EX && !SWAP && i >= 2 ? offW2 + (i - 2) * (32 * kRowBytes) : offA + i * (32 * kRowBytes)) + c);
     } else if (EX) {
       if (bx_mode) f.bx = *(const bf16x8*)(stage + offBx + c);
     }
@@ -246,13 +250,15 @@ struct WaveTile {
     // the extra block's products last: their operands have long arrived (first, they would wait for the
     // LDS reads issued at the end of the half stage before)
     if constexpr (EX) {
-      static_assert(!EX || I == 4, "mode 1 splits four A blocks between two wavefronts");
-#define DSMOE_EXTRA_MFMA(C, A) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(C) : "v"(A), "v"(cur.bx))
-      DSMOE_EXTRA_MFMA(accx[0], cur.a[0]);
-      DSMOE_EXTRA_MFMA(accx[1], cur.a[1]);
+      // the weight fragment is the MFMA's first operand in both GEMMs (a[k] of GEMM-1, b[k] of GEMM-2)
+#define DSMOE_EXTRA_MFMA(K)                                                                                                      \
+  if (F16) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(accx[K]) : "v"(cur.b[K]), "v"(cur.bx));                \
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(accx[K]) : "v"(cur.a[K]), "v"(cur.bx))
+      DSMOE_EXTRA_MFMA(0);
+      DSMOE_EXTRA_MFMA(1);
       if (bx_mode == 3) {
-        DSMOE_EXTRA_MFMA(accx[2], cur.a[2]);
-        DSMOE_EXTRA_MFMA(accx[3], cur.a[3]);
+        DSMOE_EXTRA_MFMA(2);
+        DSMOE_EXTRA_MFMA(3);
       }
 #undef DSMOE_EXTRA_MFMA
     }
@@ -499,7 +505,7 @@ __device__ __forceinline__ void gemm1_tile(const G1Args& g, char* lds, int a_row
     // branch each read would wait for its own LDS round trip), then the stores
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 #pragma unroll 1
-    for (int c0 = 0; c0 < (TALL ? kTallRows : kMfmaBM) / 16; c0 += 4) {
+    for (int c0 = 0; c0 < kTallRows / 16; c0 += 4) {  // up to 320 rows: the tile before an expert's short last tile zero-fills that one's rows too
       u32x4_t v[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) v[c] = *(const u32x4_t*)(lds + ((c0 + c) * 16 + (tid >> 4)) * kHsRow + (tid & 15) * 16);
@@ -595,13 +601,20 @@ struct G2Args {
 
 // MFMA A = pair rows of H, B = output columns of W2 (both half precision).
 // YH: the partial outputs are stored in half precision (see launch_gemm2_mfma)
-template <int I, int J, int NI, bool NT, bool YH, class RING = RingWhole>
+// TALL: a full row tile that also takes the 1..64 rows of its expert's short last tile (see gemm1_tile): rows
+// 256..319 of the item, one more block of 32 rows per wavefront, times all four of its column blocks or, when
+// there is only one such block, times two of them (the wavefront that shares the columns takes the other two).
+template <int I, int J, int NI, bool NT, bool YH, class RING = RingWhole, bool TALL = false>
 __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row0, int b_row0, int w) {
+  static_assert(!TALL || (I == 4 && J == 4 && NI == 4), "tall tiles: 2 x 2 wavefronts, 320 rows");
   int tid = fresh_tid(w);  // see gemm1_tile
   const int lane = tid & 63;
-  constexpr int NH = I == 8 ? (NI * 32 + 63) / 64 : 4;  // loads per thread and stage for the rows of H (64 rows each)
-  WaveTile<I, J, NI, J, 4 + NH, true, RING::NS, RING::SB, RING::BOFF, true> t;
-  t.init(a_row0, b_row0, lane);
+  constexpr int NH = TALL ? 5 : I == 8 ? (NI * 32 + 63) / 64 : 4;  // loads per thread and stage for the rows of H (64 rows each)
+  WaveTile<I, J, NI, J, 4 + NH, true, RING::NS, RING::SB, RING::BOFF, true, TALL> t;
+  const bool two_blocks = g.it.nrows > kMfmaBM + 32;
+  const int bx_row0 = kMfmaBM + (two_blocks ? a_row0 >> 2 : 0);
+  const int rot = TALL && !two_blocks && a_row0 ? 2 : 0;  // column block of accumulator j: (j + rot) & 3
+  t.init(a_row0, b_row0, lane, bx_row0, !TALL ? 0 : two_blocks ? 3 : 1, rot);
   // this thread's part of the rows of H: chunk (tid & 3) of rows i * 64 + (tid >> 2) (per instantiation, see gemm1_tile)
   uint32_t hoff[NH];
 #pragma unroll
@@ -649,17 +662,19 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
   static_assert(32 * kYsRow <= RING::BYTES / 4, "a block of 32 rows fits a wavefront's quarter of the ring");
   block_barrier();  // every wave is done reading the last stage
   const int cw = g.it.jd * kMfmaBN2 + b_row0 + (le % kLanesRow) * kColsLane;  // first of this lane's columns in the write-out
+  // one block of 32 rows: accumulators A[0..nj) (column block (j + rot) & 3 each), first row row_blk of the item
+  auto out_block = [&](const f32x16* A, int nj, int row_blk) {
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
-#pragma unroll
-    for (int j = 0; j < J; ++j)
+    for (int j = 0; j < J; ++j) {
+      if (j >= nj) continue;
+      const int jc = TALL ? (j + rot) & 3 : j;
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        char* at = mine + (le & 31) * kYsRow + (j * 32 + vq * 8 + (le >> 5) * 4) * kEl;
+        char* at = mine + (le & 31) * kYsRow + (jc * 32 + vq * 8 + (le >> 5) * 4) * kEl;
         if constexpr (YH) {  // times 2^-10, saturating, round to nearest even
           float v[4];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_fmed3f(t.acc[i][j][vq * 4 + c] * g.yscale, -kHalfMax, kHalfMax);
+          for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_fmed3f(A[j][vq * 4 + c] * g.yscale, -kHalfMax, kHalfMax);
           f16x2 lo, hi;
           lo[0] = (_Float16)v[0], lo[1] = (_Float16)v[1], hi[0] = (_Float16)v[2], hi[1] = (_Float16)v[3];
           uint2 pk;
@@ -668,16 +683,19 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
           *(uint2*)at = pk;
         } else {
           f32x4_t o;
-          o.x = t.acc[i][j][vq * 4 + 0];
-          o.y = t.acc[i][j][vq * 4 + 1];
-          o.z = t.acc[i][j][vq * 4 + 2];
-          o.w = t.acc[i][j][vq * 4 + 3];
+          o.x = A[j][vq * 4 + 0];
+          o.y = A[j][vq * 4 + 1];
+          o.z = A[j][vq * 4 + 2];
+          o.w = A[j][vq * 4 + 3];
           *(f32x4_t*)at = o;
         }
       }
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // this lane's columns of the write-out belong to column block (first column / 32): written above?
+    const bool cols_here = nj == J || ((((le % kLanesRow) * kColsLane >> 5) - rot) & 3) < nj;
     // the reads of up to four passes first, whether or not the row exists (they are pinned here: inside the
     // branches below each would wait for its own LDS round trip), then the stores of the rows that do
     constexpr int kPasses = 32 / kRowsPass, kBatch = kPasses < 4 ? kPasses : 4;
@@ -691,8 +709,8 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
       for (int k = 0; k < kBatch; ++k) asm volatile("" : "+v"(o[k]));
 #pragma unroll
       for (int k = 0; k < kBatch; ++k) {
-        const int r = a_row0 + i * 32 + (k0 + k) * kRowsPass + le / kLanesRow;
-        if (r < g.it.nrows && cw < g.D) {
+        const int r = row_blk + (k0 + k) * kRowsPass + le / kLanesRow;
+        if (r < g.it.nrows && cw < g.D && cols_here) {
           f32x4_t* dst = (f32x4_t*)(g.Y + ((size_t)r * g.ldy + b_row0 + (le % kLanesRow) * kColsLane) * kEl);
           if (NT) __builtin_nontemporal_store(o[k], dst);
           else *dst = o[k];
@@ -702,7 +720,10 @@ __device__ __forceinline__ void gemm2_tile(const G2Args& g, char* lds, int a_row
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_sched_barrier(0);
-  }
+  };
+#pragma unroll
+  for (int i = NI - 1; i >= 0; --i) out_block(t.acc[i], J, a_row0 + i * 32);
+  if constexpr (TALL) out_block(t.accx, t.bx_mode == 3 ? 4 : 2, bx_row0);
 }
 
 // What every GEMM-2 workgroup does first (see gemm1_setup).
@@ -728,7 +749,7 @@ __device__ __forceinline__ void gemm2_setup(G2Args& g, int item_id, const Layout
     g.Y = ws + L.o_Yp + ((size_t)g.it.row0 * L.D + g.it.jd * kMfmaBN2) * yel;
     g.ldy = L.D;
   } else {  // an extra K range of a split item: a partial-output tile of the pool
-    g.Y = ws + L.o_pool + (size_t)(g.it.split - 1) * kMfmaBM * kMfmaBN2 * yel;
+    g.Y = ws + L.o_pool + (size_t)(g.it.split - 1) * kPoolRows * kMfmaBN2 * yel;
     g.ldy = kMfmaBN2;
   }
   g.yscale = kYpHalfScale;
@@ -750,7 +771,9 @@ __global__ __launch_bounds__(256) void gemm2_mfma_kernel(Layout L, int T, const 
   G2Args g;
   gemm2_setup(g, item_id, L, packed, ws, lds, tid, w);
 
-  if (g.it.nrows == kMfmaBM) {
+  if (g.it.nrows > kMfmaBM) {  // a full row tile and the expert's last 1..64 rows
+    gemm2_tile<4, 4, 4, NT, YH, RingTall2, true>(g, lds, (w >> 1) * 128, (w & 1) * 128, w);
+  } else if (g.it.nrows == kMfmaBM) {
     gemm2_tile<4, 4, 4, NT, YH>(g, lds, (w >> 1) * 128, (w & 1) * 128, w);  // 2 x 2 wavefronts
   } else {  // 1 x 4: the ceil(nrows/32) blocks of pair rows that exist x 64 columns
     switch ((g.it.nrows + 31) >> 5) {

@@ -413,7 +413,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   int32_t* pt = ts + E_tot + 1;     // [E_tot+1] first tile by POSITION in the row space
   int32_t* ga = pt + E_tot + 2;     // [NG] active tiles of each group
   int32_t* gb = ga + NG + 1;        // [NG+1] item base of each group
-  int32_t* tmp = gb + NG + 1;       // [kPlanThreads]
+  int32_t* abp = gb + NG + 1;       // [E_tot+1] by POSITION: short last tiles (absorbed by tall items) of the experts before
+  int32_t* tmp = abp + E_tot + 2;   // [kPlanThreads]
 
   int32_t* cursor = (int32_t*)(ws + L.o_cursor);
   int32_t* exp_nrows = (int32_t*)(ws + L.o_exp_nrows);
@@ -535,7 +536,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   //        within one item per unit;
   //    (b) the last round of a longer list is only partly full -> its items are split where the shorter
   //        pieces fill the units better (see below).
-  const int W2n = total_tiles * L.ND2;
+  //    A short last tile of an expert (at most kTallExtra rows) has no items of its own: the items of the
+  //    tile before it are tall and compute its rows too (as in GEMM-1; here for all partitions at once).
+  //    Only if both tiles keep the same partitions: a short tile that keeps fewer is a short item already
+  //    (dropped partitions are skipped), cheaper than the extra rows of a tall one over all of them.
+  for (int i = tid; i < E_tot; i += kPlanThreads) {
+    const int e = has_sh ? (i == 0 ? E_res : i - 1) : i;
+    const int nt = (ne[e] + BM - 1) / BM;
+    int s = 0;
+    if (L.tall_tiles && nt >= 2 && ne[e] - (nt - 1) * BM <= kTallExtra) s = (tbits[ts[e] + nt - 1] & ~tbits[ts[e] + nt - 2]) == 0 ? 1 : 0;
+    abp[i] = s;
+  }
+  if (tid == 0) abp[E_tot] = 0;
+  __syncthreads();
+  const int total_short = block_excl_scan(abp, E_tot + 1, tmp);  // abp[E_tot] = total
+  auto short_last = [&](int e) {  // read back from the scanned flags
+    const int pos = has_sh ? (e == E_res ? 0 : e + 1) : e;
+    return abp[pos + 1] - abp[pos];
+  };
+  const int W2n = (total_tiles - total_short) * L.ND2;
   int nsplit = 1, first_split = W2n;  // items first_split .. W2n-1 (in list order) are split nsplit ways
   if (L.split_items > 0 && W2n > 0) {
     int ksp = L.Fp / kBK;
@@ -569,28 +588,35 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     if (nsplit == 1) first_split = W2n;
   }
   int32_t* split_of = (int32_t*)(ws + L.o_split_of);
-  for (int gj = tid; gj < W2n; gj += kPlanThreads) {
+  for (int gj = tid; gj < total_tiles * L.ND2; gj += kPlanThreads) {
     const int g = gj / L.ND2, jd = gj % L.ND2;
     const int e = tile_expert(g);
     const int i = g - ts[e];
     const int ksp = (e < E_res ? L.Fp : L.F_shT) / kBK;
+    const int nt_all = (ne[e] + BM - 1) / BM, sl = short_last(e);
+    if (sl && i == nt_all - 1) continue;         // the short last tile: computed by the items of the tile before
+    const bool tall = sl && i == nt_all - 2;
     Item2 v;
     v.row0 = rs[e] + i * BM;
-    v.nrows = min(ne[e] - i * BM, BM);
+    v.nrows = min(ne[e] - i * BM, BM) + (tall ? ne[e] - (i + 1) * BM : 0);
     v.e = e;
     v.jd = jd;
-    v.kmask = tbits[g];
+    v.kmask = tbits[g] | (tall ? tbits[g + 1] : 0);
     // list order (expert, column tile, row tile) if g2_rows_inner: the row tiles that share one column
     // tile of W2 are adjacent, run at the same time on one XCD and fetch the weights once;
     // else (row tile, column tile)
-    const int nt_e = (ne[e] + BM - 1) / BM;
-    const int slot = L.g2_rows_inner ? ts[e] * L.ND2 + jd * nt_e + i : gj;
+    const int nt_e = nt_all - sl;                                         // tiles of the expert that have items
+    const int ts_e = ts[e] - abp[has_sh ? (e == E_res ? 0 : e + 1) : e];  // and of the experts before it
+    const int slot = L.g2_rows_inner ? ts_e * L.ND2 + jd * nt_e + i : (ts_e + i) * L.ND2 + jd;
     if (slot < first_split) {
       v.ks_lo = 0;
       v.ks_n = ksp;
       v.split = 0;
       items2[slot] = v;
-      if (L.split_items > 0) split_of[gj] = -1;
+      if (L.split_items > 0) {
+        split_of[gj] = -1;
+        if (tall) split_of[gj + L.ND2] = -1;
+      }
     } else {
       const int q = slot - first_split;  // q-th split item: its extra ranges use pool tiles q*(nsplit-1) ..
       for (int sp = 0; sp < nsplit; ++sp) {
@@ -600,6 +626,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
         items2[first_split + q * nsplit + sp] = v;
       }
       split_of[gj] = q * (nsplit - 1);
+      if (tall) split_of[gj + L.ND2] = q * (nsplit - 1) | kSplitRowsOffset;  // rows of the short tile: BM further down the pool tiles
     }
   }
   // 6. per (expert, partition): rank of each active tile among the active tiles of its group
@@ -669,6 +696,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     if (absorbed(e, i + 1, p)) {  // a tall item: the rows of the expert's short last tile follow directly
       v.nrows += tile_rows_for(e, i + 1, p);
       v.nfill += ne[e] - (i + 1) * BM;
+    } else if (i + 2 == (ne[e] + BM - 1) / BM && short_last(e) && !((tbits[g + 1] >> p) & 1)) {
+      // the tall GEMM-2 items of this tile multiply partition p over the short last tile's rows too, none
+      // of which keeps it: their part of H is zeros, written by this item
+      v.nfill += ne[e] - (i + 1) * BM;
     }
     v.e = e;
     v.p = p;
@@ -721,7 +752,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   if (tid == 0) {
     counters[0] = total_slots;
     counters[1] = first_split + (W2n - first_split) * nsplit;
-    counters[2] = total_tiles;
+    counters[2] = total_tiles - total_short;  // row tiles that have GEMM-2 items
     counters[3] = nsplit;
   }
 }
@@ -729,7 +760,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
   const int E_tot = L.E_res + (L.n_shared > 0 ? 1 : 0);
   const int NG = E_tot * L.P;
-  size_t sh = sizeof(int32_t) * (size_t)(L.nbins + 4 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + kPlanTilesLds + 8);
+  size_t sh = sizeof(int32_t) * (size_t)(L.nbins + 5 * (E_tot + 2) + 2 * (NG + 1) + kPlanThreads + kPlanTilesLds + 8);
   if (sh > 48 * 1024) {  // hundreds of experts x 8 parts: up to ~78 KB, above what a launch gets without asking
     static PerDeviceOnce once;
     hipError_t e = once.run([] { return hipFuncSetAttribute((const void*)plan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 104 * 1024); });
@@ -877,15 +908,17 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
   // GEMM-2 split K: the partial-output tiles of the extra K ranges of row r are added in range order
   auto add_extra = [&](int r, float (&into)[VEC]) {
     const int tile = r / L.BM;
-    const int first = split_of[(size_t)tile * L.ND2 + jd];
+    int first = split_of[(size_t)tile * L.ND2 + jd];
     if (first < 0) return;
-    size_t src = ((size_t)first * L.BM + (r - tile * L.BM)) * kMfmaBN2 + dc;
+    const int rofs = first & kSplitRowsOffset ? L.BM : 0;  // a short last tile: its rows follow those of the tile before
+    first &= ~kSplitRowsOffset;
+    size_t src = ((size_t)first * kPoolRows + (r - tile * L.BM) + rofs) * kMfmaBN2 + dc;
     for (int sp = 1; sp < nsplit; ++sp) {
       float u[VEC];
       PT::widen(PT::load(pool, src), u);
 #pragma unroll
       for (int i = 0; i < VEC; ++i) into[i] += u[i];
-      src += (size_t)L.BM * kMfmaBN2;
+      src += (size_t)kPoolRows * kMfmaBN2;
     }
   };
   if (L.n_shared > 0) {  // the shared experts' rows sit first in the row space (weight 1)

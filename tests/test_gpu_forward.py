@@ -289,8 +289,11 @@ SPLIT_CASES = [
     ("shared_limits_the_split", spec_of(T=24, D=128, F=512, E=4, K=2, P=2, n_shared=1, F_sh=64, seed=42), "rate0.25", 2),
     ("one_token_split", spec_of(T=1, D=256, F=2048, E=8, K=2, P=2, seed=43), 0.0, 8),
     ("too_many_tiles_to_split", spec_of(T=1200, D=768, F=128, E=64, K=8, P=2, seed=44), "rate0.25", 1),
-    # 66-67 row tiles x 4 column tiles = 264-268 items of 64 K stages: the few items of the second round are split
-    ("last_round_nearly_empty", spec_of(T=8200, D=1024, F=2048, E=4, K=2, P=2, seed=45), 0.0, ">1"),
+    # 4 x 17 row tiles (the last of each some 150 rows: no tall items) x 4 column tiles = 272 items of 64 K stages:
+    # the few items of the second round are split
+    ("last_round_nearly_empty", spec_of(T=8500, D=1024, F=2048, E=4, K=2, P=2, seed=45), 0.0, ">1"),
+    # 4 x 16 row tiles + a few rows each, which the last full tiles take along: 256 items, one round, no split
+    ("short_last_tiles_leave_one_round", spec_of(T=8200, D=1024, F=2048, E=4, K=2, P=2, seed=45), 0.0, 1),
     # items of 8 K stages: a piece would be all fill and write-out, nothing is split
     ("short_items_stay_whole", spec_of(T=8200, D=1024, F=256, E=4, K=2, P=2, seed=45), 0.0, 1),
     # same with shared experts, whose short contraction (2 stages) limits the split
@@ -383,7 +386,7 @@ def test_gemm1_items_of_a_sparse_last_round_are_halved(oracle, name, spec, tau_k
         assert whole <= counters[0] <= whole + rest, (counters, whole, rest)
 
 
-# ------------------------------------------------- tall GEMM-1 items: a full row tile + the expert's short last tile
+# ------------------------------------------------- tall items: a full row tile + the expert's short last tile
 TALL_CASES = [
     # name, spec, tau.  Rows per expert = T * K / E on average, spread by the random routing
     ("one_tile_and_a_few_rows", spec_of(T=540, D=128, F=512, E=4, K=2, P=2, seed=60), 0.0),       # ~270 rows per expert
@@ -397,10 +400,11 @@ TALL_CASES = [
 
 
 @pytest.mark.parametrize("name,spec,tau_kind", TALL_CASES, ids=[c[0] for c in TALL_CASES])
-def test_gemm1_tall_items(oracle, name, spec, tau_kind):
+def test_tall_items(oracle, name, spec, tau_kind):
     """When an expert's last row tile has at most 64 rows, the GEMM-1 item of the full tile before it computes
-    them too (for every partition whose rows fill that tile) and the short tile gets no item.  Same result
-    as the oracle either way; with no drop the item count shows the rule."""
+    them too (for every partition whose rows fill that tile) and the short tile gets no item; the GEMM-2 items
+    of that tile do the same when the short tile keeps no partition that the full one drops.  Same result as
+    the oracle either way; with no drop the item counts show the rule."""
     y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
     if tau_kind != 0.0:
         return
@@ -425,6 +429,8 @@ def test_gemm1_tall_items(oracle, name, spec, tau_kind):
     else:
         assert merged == 0
     assert counters[0] == expect, (counters, expect, rows)
+    tiles2 = sum(tiles(int(n)) for n in rows) + (tiles(spec.T) if spec.n_shared else 0)
+    assert counters[2] == tiles2, (counters, tiles2, rows)  # row tiles that have GEMM-2 items
 
 
 @pytest.mark.parametrize("dtype,T", [("bf16", 16), ("bf16", 300), ("f32", 40)])
