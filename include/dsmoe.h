@@ -81,6 +81,10 @@ typedef struct {
                              seven decades below their typical size, saturation a factor 60 and more above it.
                              They are the largest memory stream of layers with many experts per token.
                              1: they are kept in fp32.  Sums are fp32 either way. */
+  int32_t tall_items;     /* Matrix-core path only; the results are the same either way.  An expert's last tile of at
+                             most 64 rows can be computed by the work items of the full tile before it ("tall" items)
+                             instead of by items of its own.  0 (normal): the plan decides per batch, from the number
+                             and length of the items either list would have; 1: wherever it is possible; -1: never. */
 } dsmoe_config;
 
 /* Validates cfg and builds the host-side context.  No GPU call is made. */
@@ -275,7 +279,8 @@ int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx, const float* logits, int32_t T,
  *   5 row_bits uint8[rows]     6 expert_nrows int32[E_res] 7 expert_row0 int32[E_res]
  *   8 row capacity (a count, not an offset)                9 row tile height (a count)
  *  10 rows at the start of the row space that the last call gave to the shared experts (a count)
- *  11 counters int32[4]: items of GEMM-1, items of GEMM-2, row tiles, K ranges GEMM-2 is split into
+ *  11 counters int32[5]: items of GEMM-1, items of GEMM-2, row tiles that have GEMM-2 items, K ranges GEMM-2 is
+ *     split into, first row tile (in row order) with a split item
  */
 #define DSMOE_PLAN_FIELDS 12
 int dsmoe_plan_layout(const dsmoe_ctx* ctx, int64_t* out);

@@ -24,7 +24,7 @@ class DsmoeError(RuntimeError):
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "d_model", "d_ff", "n_experts", "top_k", "n_part", "n_shared", "d_ff_shared", "expert_lo", "expert_hi",
-        "renorm_combine", "max_tokens", "dtype", "y_fp32", "h_scale_log2", "partial_fp32")]
+        "renorm_combine", "max_tokens", "dtype", "y_fp32", "h_scale_log2", "partial_fp32", "tall_items")]
 
 
 def lib_path() -> str:
@@ -109,10 +109,10 @@ def dsmoe_strerror(status: int) -> str:
 
 def dsmoe_create(*, d_model, d_ff, n_experts, top_k, n_part, max_tokens, dtype, n_shared=0, d_ff_shared=0,
                  expert_lo=0, expert_hi=None, renorm_combine=0, y_fp32=0, h_scale_log2=0,
-                 partial_fp32=0) -> ctypes.c_void_p:
+                 partial_fp32=0, tall_items=0) -> ctypes.c_void_p:
     cfg = _Config(d_model, d_ff, n_experts, top_k, n_part, n_shared, d_ff_shared, expert_lo,
                   n_experts if expert_hi is None else expert_hi, int(renorm_combine), max_tokens, dtype, int(y_fp32),
-                  int(h_scale_log2), int(partial_fp32))
+                  int(h_scale_log2), int(partial_fp32), int(tall_items))
     out = ctypes.c_void_p()
     rc = _lib.dsmoe_create(ctypes.byref(cfg), ctypes.byref(out))
     if rc != 0:
@@ -250,7 +250,7 @@ class DualSparseLayer:
 
     def __init__(self, *, d_model, d_ff, n_experts, top_k, n_part, max_tokens, dtype="bf16", n_shared=0, d_ff_shared=0,
                  expert_lo=0, expert_hi=None, renorm_combine=False, y_fp32=False, h_scale_log2=0,
-                 partial_fp32=False, device="cuda:0"):
+                 partial_fp32=False, tall_items=0, device="cuda:0"):
         self.device = torch.device(device)
         self.dtype = dtype
         self.D, self.F, self.E, self.K, self.P = d_model, d_ff, n_experts, top_k, n_part
@@ -261,7 +261,7 @@ class DualSparseLayer:
                                 max_tokens=max_tokens, dtype=DSMOE_BF16 if dtype == "bf16" else DSMOE_F32,
                                 n_shared=n_shared, d_ff_shared=d_ff_shared, expert_lo=expert_lo, expert_hi=self.hi,
                                 renorm_combine=int(bool(renorm_combine)), y_fp32=int(bool(y_fp32)),
-                                h_scale_log2=h_scale_log2, partial_fp32=int(bool(partial_fp32)))
+                                h_scale_log2=h_scale_log2, partial_fp32=int(bool(partial_fp32)), tall_items=int(tall_items))
         self.packed = torch.empty(dsmoe_packed_bytes(self.ctx), dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(dsmoe_workspace_bytes(self.ctx), dtype=torch.uint8, device=self.device)
         self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32  # of x and the weights
@@ -382,7 +382,7 @@ class DualSparseLayer:
             "row_cap": rows,
             "tile_rows": lay[9],
             "shared_rows": lay[10],
-            "counters": view(lay[11], 4, torch.int32),
+            "counters": view(lay[11], 5, torch.int32),
         }
 
     def close(self) -> None:

@@ -28,6 +28,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   if (c.y_fp32 != 0 && c.y_fp32 != 1) return false;
   if (c.h_scale_log2 < -40 || c.h_scale_log2 > 40) return false;
   if (c.partial_fp32 != 0 && c.partial_fp32 != 1) return false;
+  if (c.tall_items < -1 || c.tall_items > 1) return false;
   if ((int64_t)c.max_tokens * c.top_k * c.n_part > (int64_t)1 << 30) return false;
   if ((int64_t)c.n_shared * c.d_ff_shared > (int64_t)1 << 30) return false;
 
@@ -67,7 +68,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.g2_rows_inner = (int64_t)L.F * kMfmaBN2 * 2 >= (1 << 20) ? 1 : 0;
   // tall items need whole neuron tiles (the variant for a half-full last neuron tile has no tall form)
   auto whole_tiles = [](int n) { const int m = n % kMfmaNeur; return m == 0 || m > kMfmaNeur / 2; };
-  L.tall_tiles = L.mfma && whole_tiles(L.Fp) && (L.n_shared == 0 || whole_tiles(L.F_shT)) ? 1 : 0;
+  L.tall_tiles = L.mfma && c.tall_items >= 0 && whole_tiles(L.Fp) && (L.n_shared == 0 || whole_tiles(L.F_shT)) ? 1 + c.tall_items : 0;
   const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
   L.nsub = 1 << nsub_bits;
   L.nbins = L.E_res * L.nsub;
@@ -100,7 +101,7 @@ bool build_layout(const dsmoe_config& c, Layout& L) {
   L.o_cursor = take((int64_t)L.nbins * 4);
   L.o_exp_nrows = take((int64_t)L.E_res * 4);
   L.o_exp_row0 = take((int64_t)L.E_res * 4);
-  L.o_counters = take(16);
+  L.o_counters = take(32);
   L.o_tile_bits = take((int64_t)L.max_tiles * 4);
   L.o_act_rank = take((int64_t)L.max_tiles * L.P * 4);
   L.o_items1 = take((int64_t)L.max_items1 * sizeof(Item1));

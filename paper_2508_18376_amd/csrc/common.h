@@ -70,7 +70,8 @@ struct Layout {
   int32_t yp_half;  // MFMA path: GEMM-2 stores its per-pair partial outputs (Yp, pool tiles) in half precision (times kYpHalfScale)
   int32_t h_shift;  // MFMA path: the intermediate activation is stored times 2^h_shift (folded into the packed W3)
   int32_t g2_rows_inner;  // GEMM-2 item order: 1 = (expert, column tile, row tile), 0 = (expert, row tile, column tile)
-  int32_t tall_tiles;     // MFMA path: a GEMM-1 item of a full row tile also takes the expert's last row tile if that has at most kTallExtra rows
+  int32_t tall_tiles;     // MFMA path: a GEMM item of a full row tile may also take the expert's last row tile if that has at most
+                          // kTallExtra rows: 0 never, 1 where the plan's estimate says it pays (GEMM-1; always in GEMM-2), 2 wherever possible
   int32_t split_items;  // kSplitItems if GEMM-2 may split K (MFMA path), else 0
   int32_t max_tokens;
   // plan geometry

@@ -521,12 +521,73 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // Tall GEMM-1 items: when an expert's last row tile has at most kTallExtra rows, the item of the tile
   // before it (if that is full for the partition) computes them too, and the last tile gets no item of
   // its own: a few rows would otherwise pull the whole weight tile through another compute unit.
-  auto absorbed = [&](int e, int i, int p) {
-    if (!L.tall_tiles || i == 0) return false;
+  auto absorbable = [&](int e, int i, int p) {
+    if (i == 0) return false;
     if (i != (ne[e] + BM - 1) / BM - 1 || ne[e] - i * BM > kTallExtra) return false;
     if (!((tbits[ts[e] + i] >> p) & 1)) return false;
     return tile_rows_for(e, i - 1, p) == BM;
   };
+  // Whether the batch gets them is decided by pricing both lists.  Items in 1/256 of a full one: a ragged
+  // item of r rows 128 + r / 2 (half of every stage is its weight tile), a tall one 256 + 33 with up to 32
+  // extra rows and 256 + 56 beyond (measured).  A list of N items of mean cost c is taken to last
+  // ceil(N / units) * c, whole rounds of one item per compute unit: removing a tenth of the items is worth
+  // a round or nothing, and the longer items of a list that still needs the same rounds make it slower.
+  __shared__ int est[4];  // items and summed cost of the list without / with tall items
+  bool use_tall1 = L.tall_tiles == 2;
+  if (L.tall_tiles == 1) {
+    if (tid < 4) est[tid] = 0;
+    __syncthreads();
+    // one thread per (expert, partition): the rows that need p are a prefix of the expert's rows (exactly so
+    // with thresholds that grow with p; an estimate otherwise), so the group's items follow from one count
+    int n0 = 0, w0 = 0, n1 = 0, w1 = 0;
+    for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
+      const int e = gidx / L.P, p = gidx % L.P;
+      if (e >= E_res && p > 0) continue;
+      int rows = ne[e];
+      if (e < E_res && p < nsub_bits) {
+        rows = 0;
+        int off = 0;
+        for (int sb = 0; sb < L.nsub; ++sb) {
+          const int c = bin_count[e * L.nsub + sb];
+          const int rev = L.nsub - 1 - sb;
+          if (c > 0 && ((rev >> (nsub_bits - 1 - p)) & 1)) rows = off + c;
+          off += c;
+        }
+      }
+      if (rows == 0) continue;
+      const int nt1 = e < E_res ? L.NT1 : L.NT1_sh;
+      const int full = rows / BM, rem = rows % BM;
+      const int n = full + (rem ? 1 : 0), w = full * 256 + (rem ? 128 + rem / 2 : 0);
+      n0 += nt1 * n;
+      w0 += nt1 * w;
+      const int nt = (ne[e] + BM - 1) / BM;
+      if (nt >= 2 && ne[e] - (nt - 1) * BM <= kTallExtra && rows > (nt - 1) * BM) {  // the last tile's item goes into the one before
+        n1 += nt1 * (n - 1);
+        w1 += nt1 * (full * 256 + (rem <= 32 ? 33 : 56));
+      } else {
+        n1 += nt1 * n;
+        w1 += nt1 * w;
+      }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      n0 += __shfl_down(n0, o, 64);
+      w0 += __shfl_down(w0, o, 64);
+      n1 += __shfl_down(n1, o, 64);
+      w1 += __shfl_down(w1, o, 64);
+    }
+    if ((tid & 63) == 0) {  // integer sums: the same in any order
+      atomicAdd(&est[0], n0);
+      atomicAdd(&est[1], w0);
+      atomicAdd(&est[2], n1);
+      atomicAdd(&est[3], w1);
+    }
+    __syncthreads();
+    const int units = max(L.split_items, 1);
+    const float t0 = est[0] > 0 ? (float)((est[0] + units - 1) / units) * (float)est[1] / (float)est[0] : 0.f;
+    const float t1 = est[2] > 0 ? (float)((est[2] + units - 1) / units) * (float)est[3] / (float)est[2] : 0.f;
+    use_tall1 = est[2] < est[0] && t1 <= t0;
+  }
+  auto absorbed = [&](int e, int i, int p) { return use_tall1 && absorbable(e, i, p); };
   // 5. GEMM-2 items: every tile x every output column tile.  The compute units take the items in
   //    list order, one each.  Where that leaves units idle, items are split along K: every extra K
   //    range is an item of its own that writes a partial-output tile into a pool, and the combine
@@ -588,6 +649,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     if (nsplit == 1) first_split = W2n;
   }
   int32_t* split_of = (int32_t*)(ws + L.o_split_of);
+  __shared__ int first_split_tile;  // first row tile (in row order) that has a split item: the combine kernel looks no tile before it up
+  if (tid == 0) first_split_tile = total_tiles;
+  __syncthreads();
   for (int gj = tid; gj < total_tiles * L.ND2; gj += kPlanThreads) {
     const int g = gj / L.ND2, jd = gj % L.ND2;
     const int e = tile_expert(g);
@@ -619,6 +683,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       }
     } else {
       const int q = slot - first_split;  // q-th split item: its extra ranges use pool tiles q*(nsplit-1) ..
+      atomicMin(&first_split_tile, g);
       for (int sp = 0; sp < nsplit; ++sp) {
         v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
         v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
@@ -754,6 +819,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     counters[1] = first_split + (W2n - first_split) * nsplit;
     counters[2] = total_tiles - total_short;  // row tiles that have GEMM-2 items
     counters[3] = nsplit;
+    counters[4] = first_split_tile;
   }
 }
 
@@ -902,6 +968,7 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   const int32_t* counters = (const int32_t*)(ws + L.o_counters);
   const int nsplit = counters[3];
+  const int split_row0 = counters[4] * L.BM;  // rows before it belong to tiles without split items
   const int32_t* split_of = (const int32_t*)(ws + L.o_split_of);
   const char* pool = ws + L.o_pool;
   const int jd = d / kMfmaBN2, dc = d - jd * kMfmaBN2;
@@ -923,7 +990,7 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
   };
   if (L.n_shared > 0) {  // the shared experts' rows sit first in the row space (weight 1)
     PT::widen(PT::load(Yp, (size_t)t * L.D + d), acc);
-    if (nsplit > 1) add_extra(t, acc);
+    if (nsplit > 1 && t >= split_row0) add_extra(t, acc);
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] *= w2_inv;
   }
@@ -932,7 +999,7 @@ __global__ __launch_bounds__(256) void combine_kernel(Layout L, int T, const cha
     if (row[k] >= 0) {
       float v[VEC];
       PT::widen(raw[k], v);
-      if (nsplit > 1) add_extra(row[k], v);
+      if (nsplit > 1 && row[k] >= split_row0) add_extra(row[k], v);
 #pragma unroll
       for (int i = 0; i < VEC; ++i) acc[i] += g[k] * v[i];
     }

@@ -24,12 +24,12 @@ def to_host64(t, dtype: str) -> np.ndarray:
     return t.cpu().numpy().astype(np.float64)
 
 
-def make_gpu_layer(spec: LayerSpec, tensors, max_tokens=None, renorm=False, y_fp32=False, h_scale_log2=0, partial_fp32=False):
+def make_gpu_layer(spec: LayerSpec, tensors, max_tokens=None, renorm=False, y_fp32=False, h_scale_log2=0, partial_fp32=False, tall_items=0):
     from paper_2508_18376_amd import DualSparseLayer
     layer = DualSparseLayer(d_model=spec.D, d_ff=spec.F, n_experts=spec.E, top_k=spec.K, n_part=spec.P,
                             max_tokens=max_tokens or max(spec.T, 1), dtype=spec.dtype, n_shared=spec.n_shared,
                             d_ff_shared=spec.F_sh, expert_lo=spec.lo, expert_hi=spec.hi, renorm_combine=renorm,
-                            y_fp32=y_fp32, h_scale_log2=h_scale_log2, partial_fp32=partial_fp32)
+                            y_fp32=y_fp32, h_scale_log2=h_scale_log2, partial_fp32=partial_fp32, tall_items=tall_items)
     dev = {k: to_dev(v) for k, v in tensors.items() if v is not None}
     layer.partition_weights(dev["w1"], dev["w3"], dev["w2"], perm=dev.get("perm"), sh_w1=dev.get("sh_w1"),
                             sh_w3=dev.get("sh_w3"), sh_w2=dev.get("sh_w2"))

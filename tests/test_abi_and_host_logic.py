@@ -55,7 +55,7 @@ def create(lib, **kw):
 BAD = [dict(d_ff=255), dict(n_part=0), dict(n_part=9), dict(top_k=0), dict(top_k=9), dict(top_k=17, n_experts=32, expert_hi=32),
        dict(n_experts=0, expert_hi=0), dict(n_experts=513, expert_hi=513), dict(expert_lo=3, expert_hi=3), dict(expert_hi=9),
        dict(expert_lo=-1), dict(max_tokens=0), dict(dtype=2), dict(n_shared=1, d_ff_shared=0), dict(n_shared=-1),
-       dict(renorm_combine=2), dict(d_model=0)]
+       dict(renorm_combine=2), dict(d_model=0), dict(tall_items=2), dict(tall_items=-2)]
 
 
 @pytest.mark.parametrize("kw", BAD, ids=[str(b) for b in BAD])

@@ -43,7 +43,7 @@ def resolve_tau(oracle, spec, t, tau_kind):
     return tau_table(spec, tau_kind)
 
 
-def run_case(oracle, spec, tau_kind, renorm=False, expect_mfma=None):
+def run_case(oracle, spec, tau_kind, renorm=False, expect_mfma=None, tall_items=0):
     import torch
     t = make_layer(spec)
     tau = resolve_tau(oracle, spec, t, tau_kind)
@@ -51,7 +51,7 @@ def run_case(oracle, spec, tau_kind, renorm=False, expect_mfma=None):
     if ref_r.keep.size and 0 < ref_r.keep.sum() < ref_r.keep.size and spec.K > 1:
         assert ref_r.min_margin > GUARD, ref_r.min_margin
     y_ref = oracle_forward(oracle, spec, t, tau, renorm=renorm)
-    layer, dev = make_gpu_layer(spec, t, renorm=renorm)
+    layer, dev = make_gpu_layer(spec, t, renorm=renorm, tall_items=tall_items)
     if expect_mfma is not None:
         assert layer.uses_mfma == expect_mfma
     y = layer.forward(dev["x"], dev["logits"], to_dev(tau))
@@ -405,7 +405,7 @@ def test_tall_items(oracle, name, spec, tau_kind):
     them too (for every partition whose rows fill that tile) and the short tile gets no item; the GEMM-2 items
     of that tile do the same when the short tile keeps no partition that the full one drops.  Same result as
     the oracle either way; with no drop the item counts show the rule."""
-    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True)
+    y, y_ref, r, plan = run_case(oracle, spec, tau_kind, expect_mfma=True, tall_items=1)  # wherever possible: these lists are short
     if tau_kind != 0.0:
         return
     counters = plan["counters"].cpu().numpy()
@@ -431,6 +431,31 @@ def test_tall_items(oracle, name, spec, tau_kind):
     assert counters[0] == expect, (counters, expect, rows)
     tiles2 = sum(tiles(int(n)) for n in rows) + (tiles(spec.T) if spec.n_shared else 0)
     assert counters[2] == tiles2, (counters, tiles2, rows)  # row tiles that have GEMM-2 items
+
+
+def gemm1_item_counts(spec, r):
+    """GEMM-1 items with no drop: (without tall items, with them wherever possible)"""
+    nt1 = (spec.F // spec.P + 127) // 128
+    rows = np.bincount(r.idx.ravel(), minlength=spec.E)[spec.lo:spec.hi]
+    plain = sum((int(n) + 255) // 256 for n in rows) * spec.P * nt1
+    merged = sum(1 for n in rows if n > 256 and (int(n) - 1) % 256 < 64)
+    return plain, plain - merged * spec.P * nt1
+
+
+@pytest.mark.parametrize("name,spec,tall_items,expect_tall", [
+    # ~270 rows per expert, 8 neuron tiles x 4 partitions: 512 items in two rounds of 256, or 256 tall ones in one
+    ("fewer_rounds_pay", spec_of(T=1080, D=128, F=4096, E=8, K=2, P=4, seed=67), 0, True),
+    # the same experts with one neuron tile per partition: either list fits one round, and the plain items are the shorter ones
+    ("one_round_either_way", spec_of(T=1080, D=128, F=512, E=8, K=2, P=4, seed=67), 0, False),
+    ("switched_off", spec_of(T=1080, D=128, F=4096, E=8, K=2, P=4, seed=67), -1, False),
+], ids=["fewer_rounds_pay", "one_round_either_way", "switched_off"])
+def test_tall_items_are_planned_per_batch(oracle, name, spec, tall_items, expect_tall):
+    """cfg.tall_items = 0: the plan prices the GEMM-1 list with and without tall items (items x mean length, in
+    whole rounds of one item per compute unit) and takes the cheaper one; -1 switches them off.  Same output."""
+    y, y_ref, r, plan = run_case(oracle, spec, 0.0, expect_mfma=True, tall_items=tall_items)
+    plain, tall = gemm1_item_counts(spec, r)
+    assert tall < plain, (plain, tall)  # the case has short last tiles
+    assert int(plan["counters"][0]) == (tall if expect_tall else plain), (plan["counters"], plain, tall)
 
 
 @pytest.mark.parametrize("dtype,T", [("bf16", 16), ("bf16", 300), ("f32", 40)])
