@@ -161,7 +161,7 @@ int moe_dualsparse_forward(dsmoe_ctx* ctx, const void* packed, const void* x, co
  *   - The workspace is laid out for this call's T (not for cfg.max_tokens); a batch that needs more
  *     than the array returns DSMOE_ENOSPC and launches nothing.  dsmoe_static_workspace_need(ctx, T)
  *     tells the bytes a batch of T tokens takes (0 for an invalid argument).  Decode-sized batches of
- *     the large layers fit (a Mixtral-shaped layer up to about a thousand tokens).
+ *     the large layers fit (a Mixtral-shaped layer up to about 900 tokens).
  *   - The first call on a device looks the array's address up (no allocation, but a runtime query):
  *     make one call with T = 0 before a graph capture starts.
  *   - Every call on a GPU uses that GPU's one array and overwrites what the last call left: calls
