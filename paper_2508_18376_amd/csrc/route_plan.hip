@@ -424,6 +424,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   Item1* items1 = (Item1*)(ws + L.o_items1);
   Item2* items2 = (Item2*)(ws + L.o_items2);
   const int BM = L.BM;
+  const int bm_sh = 31 - __clz(BM);  // the tile heights are powers of two
+  auto tiles_of = [&](int rows) { return (rows + BM - 1) >> bm_sh; };
   const int nsub_bits = L.P < kSubBits ? L.P : kSubBits;
 
   // 1. rows per expert.  Order of the experts in the row space: the shared pseudo-expert first
@@ -441,7 +443,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // 2. tile-aligned row starts: exclusive scan of the tile counts in position order
   for (int i = tid; i < E_tot; i += kPlanThreads) {
     int e = has_sh ? (i == 0 ? E_res : i - 1) : i;
-    pt[i] = (ne[e] + BM - 1) / BM;
+    pt[i] = tiles_of(ne[e]);
   }
   __syncthreads();
   const int total_tiles = block_excl_scan(pt, E_tot, tmp);
@@ -501,6 +503,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     const int e = tile_expert(g);
     tbits[g] = tile_bits_of(e, g - ts[e]);
   }
+  __shared__ int est[4];  // see "tall GEMM-1 items" below
+  if (tid < 4) est[tid] = 0;
   __syncthreads();
   // rows of tile i of expert e up to the last one that keeps partition p.  The rows are sorted by
   // keep pattern, so with thresholds that grow with p this is exactly the number of rows that need
@@ -523,7 +527,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // its own: a few rows would otherwise pull the whole weight tile through another compute unit.
   auto absorbable = [&](int e, int i, int p) {
     if (i == 0) return false;
-    if (i != (ne[e] + BM - 1) / BM - 1 || ne[e] - i * BM > kTallExtra) return false;
+    if (i != tiles_of(ne[e]) - 1 || ne[e] - i * BM > kTallExtra) return false;
     if (!((tbits[ts[e] + i] >> p) & 1)) return false;
     return tile_rows_for(e, i - 1, p) == BM;
   };
@@ -532,11 +536,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // extra rows and 256 + 56 beyond (measured).  A list of N items of mean cost c is taken to last
   // ceil(N / units) * c, whole rounds of one item per compute unit: removing a tenth of the items is worth
   // a round or nothing, and the longer items of a list that still needs the same rounds make it slower.
-  __shared__ int est[4];  // items and summed cost of the list without / with tall items
+  // est[]: items and summed cost of the list without / with tall items
   bool use_tall1 = L.tall_tiles == 2;
-  if (L.tall_tiles == 1) {
-    if (tid < 4) est[tid] = 0;
-    __syncthreads();
+  const bool price_lists = L.tall_tiles == 1 && (int64_t)T * L.K > BM;  // (no expert of a smaller batch has a second tile)
+  if (price_lists) {
     // one thread per (expert, partition): the rows that need p are a prefix of the expert's rows (exactly so
     // with thresholds that grow with p; an estimate otherwise), so the group's items follow from one count
     int n0 = 0, w0 = 0, n1 = 0, w1 = 0;
@@ -556,11 +559,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       }
       if (rows == 0) continue;
       const int nt1 = e < E_res ? L.NT1 : L.NT1_sh;
-      const int full = rows / BM, rem = rows % BM;
+      const int full = rows >> bm_sh, rem = rows & (BM - 1);
       const int n = full + (rem ? 1 : 0), w = full * 256 + (rem ? 128 + rem / 2 : 0);
       n0 += nt1 * n;
       w0 += nt1 * w;
-      const int nt = (ne[e] + BM - 1) / BM;
+      const int nt = tiles_of(ne[e]);
       if (nt >= 2 && ne[e] - (nt - 1) * BM <= kTallExtra && rows > (nt - 1) * BM) {  // the last tile's item goes into the one before
         n1 += nt1 * (n - 1);
         w1 += nt1 * (full * 256 + (rem <= 32 ? 33 : 56));
@@ -581,11 +584,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       atomicAdd(&est[2], n1);
       atomicAdd(&est[3], w1);
     }
-    __syncthreads();
-    const int units = max(L.split_items, 1);
-    const float t0 = est[0] > 0 ? (float)((est[0] + units - 1) / units) * (float)est[1] / (float)est[0] : 0.f;
-    const float t1 = est[2] > 0 ? (float)((est[2] + units - 1) / units) * (float)est[3] / (float)est[2] : 0.f;
-    use_tall1 = est[2] < est[0] && t1 <= t0;
   }
   auto absorbed = [&](int e, int i, int p) { return use_tall1 && absorbable(e, i, p); };
   // 5. GEMM-2 items: every tile x every output column tile.  The compute units take the items in
@@ -603,13 +601,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   //    (dropped partitions are skipped), cheaper than the extra rows of a tall one over all of them.
   for (int i = tid; i < E_tot; i += kPlanThreads) {
     const int e = has_sh ? (i == 0 ? E_res : i - 1) : i;
-    const int nt = (ne[e] + BM - 1) / BM;
+    const int nt = tiles_of(ne[e]);
     int s = 0;
     if (L.tall_tiles && nt >= 2 && ne[e] - (nt - 1) * BM <= kTallExtra) s = (tbits[ts[e] + nt - 1] & ~tbits[ts[e] + nt - 2]) == 0 ? 1 : 0;
     abp[i] = s;
   }
-  if (tid == 0) abp[E_tot] = 0;
-  __syncthreads();
+  __shared__ int first_split_tile;  // first row tile (in row order) that has a split item: the combine kernel looks no tile before it up
+  if (tid == 0) {
+    abp[E_tot] = 0;
+    first_split_tile = total_tiles;
+  }
+  __syncthreads();  // the sums of the pricing pass are complete too
+  if (price_lists) {
+    const int units = max(L.split_items, 1);
+    const float t0 = est[0] > 0 ? (float)((est[0] + units - 1) / units) * (float)est[1] / (float)est[0] : 0.f;
+    const float t1 = est[2] > 0 ? (float)((est[2] + units - 1) / units) * (float)est[3] / (float)est[2] : 0.f;
+    use_tall1 = est[2] < est[0] && t1 <= t0;
+  }
   const int total_short = block_excl_scan(abp, E_tot + 1, tmp);  // abp[E_tot] = total
   auto short_last = [&](int e) {  // read back from the scanned flags
     const int pos = has_sh ? (e == E_res ? 0 : e + 1) : e;
@@ -649,15 +657,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     if (nsplit == 1) first_split = W2n;
   }
   int32_t* split_of = (int32_t*)(ws + L.o_split_of);
-  __shared__ int first_split_tile;  // first row tile (in row order) that has a split item: the combine kernel looks no tile before it up
-  if (tid == 0) first_split_tile = total_tiles;
-  __syncthreads();
   for (int gj = tid; gj < total_tiles * L.ND2; gj += kPlanThreads) {
     const int g = gj / L.ND2, jd = gj % L.ND2;
     const int e = tile_expert(g);
     const int i = g - ts[e];
     const int ksp = (e < E_res ? L.Fp : L.F_shT) / kBK;
-    const int nt_all = (ne[e] + BM - 1) / BM, sl = short_last(e);
+    const int nt_all = tiles_of(ne[e]), sl = short_last(e);
     if (sl && i == nt_all - 1) continue;         // the short last tile: computed by the items of the tile before
     const bool tall = sl && i == nt_all - 2;
     Item2 v;
@@ -685,8 +690,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       const int q = slot - first_split;  // q-th split item: its extra ranges use pool tiles q*(nsplit-1) ..
       atomicMin(&first_split_tile, g);
       for (int sp = 0; sp < nsplit; ++sp) {
-        v.ks_lo = (int)((int64_t)ksp * sp / nsplit);
-        v.ks_n = (int)((int64_t)ksp * (sp + 1) / nsplit) - v.ks_lo;
+        v.ks_lo = ksp * sp / nsplit;  // (at most a few thousand stages times 8)
+        v.ks_n = ksp * (sp + 1) / nsplit - v.ks_lo;
         v.split = sp == 0 ? 0 : 1 + q * (nsplit - 1) + (sp - 1);
         items2[first_split + q * nsplit + sp] = v;
       }
@@ -706,7 +711,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
       for (int j = ts[e]; j < g; ++j) cnt += (tbits[j] >> p) & 1;
       const int act = ((tbits[g] >> p) & 1) && !absorbed(e, g - ts[e], p) ? 1 : 0;
       act_rank[(size_t)g * L.P + p] = act ? cnt : -1;
-      if (g - ts[e] == (ne[e] + BM - 1) / BM - 1) {  // the expert's last tile closes the group
+      if (g - ts[e] == tiles_of(ne[e]) - 1) {  // the expert's last tile closes the group
         ga[e * L.P + p] = cnt + act;
         gb[e * L.P + p] = (cnt + act) * (e < E_res ? L.NT1 : L.NT1_sh);
       }
@@ -714,7 +719,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   } else {  // very many tiles: one thread walks the tiles of a group
     for (int gidx = tid; gidx < NG; gidx += kPlanThreads) {
       int e = gidx / L.P, p = gidx % L.P;
-      int nt = (ne[e] + BM - 1) / BM;
+      int nt = tiles_of(ne[e]);
       int cnt = 0;
       for (int i = 0; i < nt; ++i) {
         bool act = ((tbits[ts[e] + i] >> p) & 1) && !absorbed(e, i, p);
@@ -761,7 +766,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     if (absorbed(e, i + 1, p)) {  // a tall item: the rows of the expert's short last tile follow directly
       v.nrows += tile_rows_for(e, i + 1, p);
       v.nfill += ne[e] - (i + 1) * BM;
-    } else if (i + 2 == (ne[e] + BM - 1) / BM && short_last(e) && !((tbits[g + 1] >> p) & 1)) {
+    } else if (i + 2 == tiles_of(ne[e]) && short_last(e) && !((tbits[g + 1] >> p) & 1)) {
       // the tall GEMM-2 items of this tile multiply partition p over the short last tile's rows too, none
       // of which keeps it: their part of H is zeros, written by this item
       v.nfill += ne[e] - (i + 1) * BM;
