@@ -86,7 +86,9 @@ def test_random_layer(oracle, spec, max_tokens, tau_kind, renorm, kind):
     y_ref = oracle.forward(t["x"], t["logits"], t["w1"], t["w3"], t["w2"], tau, spec.K, spec.P, perm=t["perm"],
                            sh_w1=t.get("sh_w1"), sh_w3=t.get("sh_w3"), sh_w2=t.get("sh_w2"), lo=spec.lo, hi=spec.hi,
                            renorm=renorm)
-    layer, dev = make_gpu_layer(spec, t, max_tokens=max_tokens, renorm=renorm)
+    # tall work items: left to the plan, forced, forbidden, forced (these lists are mostly too short for the plan to want them)
+    tall_items = (0, 1, -1, 1)[spec.seed % 4]
+    layer, dev = make_gpu_layer(spec, t, max_tokens=max_tokens, renorm=renorm, tall_items=tall_items)
     assert layer.uses_mfma == (kind == "bf16_mfma")
     y = layer.forward(dev["x"], dev["logits"], to_dev(tau))
     torch.cuda.synchronize()
