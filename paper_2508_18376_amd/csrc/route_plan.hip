@@ -597,8 +597,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   //        pieces fill the units better (see below).
   //    A short last tile of an expert (at most kTallExtra rows) has no items of its own: the items of the
   //    tile before it are tall and compute its rows too (as in GEMM-1; here for all partitions at once).
-  //    Only if both tiles keep the same partitions: a short tile that keeps fewer is a short item already
-  //    (dropped partitions are skipped), cheaper than the extra rows of a tall one over all of them.
+  //    Only if the short tile keeps no partition that the tile before it drops: the tall items run over the
+  //    partitions of the full tile, and where the short tile lacks one of them its rows of H are zeros
+  //    (written by the GEMM-1 item of the full tile, see step 7).
   for (int i = tid; i < E_tot; i += kPlanThreads) {
     const int e = has_sh ? (i == 0 ? E_res : i - 1) : i;
     const int nt = tiles_of(ne[e]);
