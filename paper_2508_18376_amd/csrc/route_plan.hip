@@ -331,9 +331,31 @@ constexpr int kPlanTilesLds = 2048;  // row tiles whose keep patterns fit in the
 
 // exclusive scan of a[0..n) in LDS (n <= 8 * kPlanThreads); returns the total. tmp: kPlanThreads ints.
 // Each thread owns a run of elements; the runs are scanned inside each wavefront with lane shifts
-// and the sixteen wavefront totals by the first wavefront: three barriers in all.
+// and the sixteen wavefront totals by the first wavefront: three barriers in all (one for short arrays).
 __device__ int block_excl_scan(int32_t* a, int n, int32_t* tmp) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (n <= 512) {  // short arrays (experts, groups): the first wavefront alone, one barrier
+    if (wv == 0) {
+      const int per = (n + 63) >> 6;
+      const int lo = lane * per, hi = min(n, lo + per);
+      int sum = 0;
+      for (int i = lo; i < hi; ++i) sum += a[i];
+      int incl = sum;
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      int run = incl - sum;
+      for (int i = lo; i < hi; ++i) {
+        const int v = a[i];
+        a[i] = run;
+        run += v;
+      }
+      if (lane == 63) tmp[128] = incl;
+    }
+    __syncthreads();
+    return tmp[128];
+  }
   const int per = (n + kPlanThreads - 1) / kPlanThreads;
   const int lo = tid * per, hi = min(n, lo + per);
   int sum = 0;
