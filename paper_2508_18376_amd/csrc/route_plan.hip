@@ -425,6 +425,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     __syncthreads();
   }
   const int tid = threadIdx.x;
+  // Two workgroups: both work out the tables that the lists are made from (row counts, tile patterns, short
+  // last tiles); then workgroup 0 writes the GEMM-2 list and workgroup 1 the GEMM-1 list, side by side.
+  const bool lists2 = blockIdx.x == 0, lists1 = !lists2;
   const int E_res = L.E_res;
   const int has_sh = L.n_shared > 0 ? 1 : 0;
   const int E_tot = E_res + has_sh;
@@ -476,16 +479,20 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     rs[e] = pt[i] * BM;
   }
   __syncthreads();
-  for (int e = tid; e < E_res; e += kPlanThreads) {
-    exp_nrows[e] = ne[e];
-    exp_row0[e] = rs[e];
+  if (lists2) {
+    for (int e = tid; e < E_res; e += kPlanThreads) {
+      exp_nrows[e] = ne[e];
+      exp_row0[e] = rs[e];
+    }
   }
   // 3. first row of every bin; the scatter kernel's cursors start there
-  for (int b = tid; b < L.nbins; b += kPlanThreads) {
-    int e = b / L.nsub, sb = b % L.nsub;
-    int off = rs[e];
-    for (int s2 = 0; s2 < sb; ++s2) off += bin_count[e * L.nsub + s2];
-    cursor[b] = off;
+  if (lists2) {
+    for (int b = tid; b < L.nbins; b += kPlanThreads) {
+      int e = b / L.nsub, sb = b % L.nsub;
+      int off = rs[e];
+      for (int s2 = 0; s2 < sb; ++s2) off += bin_count[e * L.nsub + s2];
+      cursor[b] = off;
+    }
   }
   // 4. row tiles are described on the fly from the LDS tables (no round trip through global memory):
   //    tile g belongs to the expert at the last position whose first tile is <= g
@@ -560,7 +567,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
   // a round or nothing, and the longer items of a list that still needs the same rounds make it slower.
   // est[]: items and summed cost of the list without / with tall items
   bool use_tall1 = L.tall_tiles == 2;
-  const bool price_lists = L.tall_tiles == 1 && (int64_t)T * L.K > BM;  // (no expert of a smaller batch has a second tile)
+  const bool price_lists = lists1 && L.tall_tiles == 1 && (int64_t)T * L.K > BM;  // (no expert of a smaller batch has a second tile)
   if (price_lists) {
     // one thread per (expert, partition): the rows that need p are a prefix of the expert's rows (exactly so
     // with thresholds that grow with p; an estimate otherwise), so the group's items follow from one count
@@ -646,81 +653,91 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     const int pos = has_sh ? (e == E_res ? 0 : e + 1) : e;
     return abp[pos + 1] - abp[pos];
   };
-  const int W2n = (total_tiles - total_short) * L.ND2;
-  int nsplit = 1, first_split = W2n;  // items first_split .. W2n-1 (in list order) are split nsplit ways
-  if (L.split_items > 0 && W2n > 0) {
-    int ksp = L.Fp / kBK;
-    if (has_sh) ksp = min(ksp, L.F_shT / kBK);
-    if (W2n * 2 <= L.split_items) {
-      while (nsplit < kMaxSplit && W2n * nsplit * 2 <= L.split_items && nsplit * 2 <= ksp) nsplit *= 2;
-      first_split = 0;
-    } else {
-      // The last round holds `rest` items for split_items compute units.  Cut n ways they are rest * n
-      // shorter items, which take ceil(rest * n / units) turns of 1/n of a round each (plus a fill and a
-      // write-out per piece, worth about eight K stages): 192 items cut in four are three turns of a
-      // quarter instead of a whole round at three quarters of the units.  The cheapest n that the pool
-      // of partial tiles can hold wins; n = 1 (cost: one round) if none is cheaper.
-      const int rest = W2n % L.split_items;
-      if (rest > 0) {
-        float best = 1.0f;
-        const int item_stages = E_res > 0 ? L.P * (L.Fp / kBK) : L.F_shT / kBK;  // K stages of a long item
-        const float piece = 8.0f / (float)max(item_stages, 1);                  // per-piece overhead in units of such an item
-        for (int n = 2; n <= kMaxTailSplit && n <= ksp; ++n) {
-          if (rest * (n - 1) > L.pool_tiles) break;
-          const int turns = (rest * n + L.split_items - 1) / L.split_items;
-          const float cost = (float)turns * (1.0f / (float)n + piece);
-          if (cost < best - 0.04f) {  // a clear gain only: every extra range costs a partial tile written and read
-            best = cost;
-            nsplit = n;
+  if (lists2) {
+    const int W2n = (total_tiles - total_short) * L.ND2;
+    int nsplit = 1, first_split = W2n;  // items first_split .. W2n-1 (in list order) are split nsplit ways
+    if (L.split_items > 0 && W2n > 0) {
+      int ksp = L.Fp / kBK;
+      if (has_sh) ksp = min(ksp, L.F_shT / kBK);
+      if (W2n * 2 <= L.split_items) {
+        while (nsplit < kMaxSplit && W2n * nsplit * 2 <= L.split_items && nsplit * 2 <= ksp) nsplit *= 2;
+        first_split = 0;
+      } else {
+        // The last round holds `rest` items for split_items compute units.  Cut n ways they are rest * n
+        // shorter items, which take ceil(rest * n / units) turns of 1/n of a round each (plus a fill and a
+        // write-out per piece, worth about eight K stages): 192 items cut in four are three turns of a
+        // quarter instead of a whole round at three quarters of the units.  The cheapest n that the pool
+        // of partial tiles can hold wins; n = 1 (cost: one round) if none is cheaper.
+        const int rest = W2n % L.split_items;
+        if (rest > 0) {
+          float best = 1.0f;
+          const int item_stages = E_res > 0 ? L.P * (L.Fp / kBK) : L.F_shT / kBK;  // K stages of a long item
+          const float piece = 8.0f / (float)max(item_stages, 1);                  // per-piece overhead in units of such an item
+          for (int n = 2; n <= kMaxTailSplit && n <= ksp; ++n) {
+            if (rest * (n - 1) > L.pool_tiles) break;
+            const int turns = (rest * n + L.split_items - 1) / L.split_items;
+            const float cost = (float)turns * (1.0f / (float)n + piece);
+            if (cost < best - 0.04f) {  // a clear gain only: every extra range costs a partial tile written and read
+              best = cost;
+              nsplit = n;
+            }
           }
+          if (nsplit > 1) first_split = W2n - rest;
         }
-        if (nsplit > 1) first_split = W2n - rest;
+      }
+      if (nsplit == 1) first_split = W2n;
+    }
+    int32_t* split_of = (int32_t*)(ws + L.o_split_of);
+    for (int gj = tid; gj < total_tiles * L.ND2; gj += kPlanThreads) {
+      const int g = gj / L.ND2, jd = gj % L.ND2;
+      const int e = tile_expert(g);
+      const int i = g - ts[e];
+      const int ksp = (e < E_res ? L.Fp : L.F_shT) / kBK;
+      const int nt_all = tiles_of(ne[e]), sl = short_last(e);
+      if (sl && i == nt_all - 1) continue;         // the short last tile: computed by the items of the tile before
+      const bool tall = sl && i == nt_all - 2;
+      Item2 v;
+      v.row0 = rs[e] + i * BM;
+      v.nrows = min(ne[e] - i * BM, BM) + (tall ? ne[e] - (i + 1) * BM : 0);
+      v.e = e;
+      v.jd = jd;
+      v.kmask = tbits[g] | (tall ? tbits[g + 1] : 0);
+      // list order (expert, column tile, row tile) if g2_rows_inner: the row tiles that share one column
+      // tile of W2 are adjacent, run at the same time on one XCD and fetch the weights once;
+      // else (row tile, column tile)
+      const int nt_e = nt_all - sl;                                         // tiles of the expert that have items
+      const int ts_e = ts[e] - abp[has_sh ? (e == E_res ? 0 : e + 1) : e];  // and of the experts before it
+      const int slot = L.g2_rows_inner ? ts_e * L.ND2 + jd * nt_e + i : (ts_e + i) * L.ND2 + jd;
+      if (slot < first_split) {
+        v.ks_lo = 0;
+        v.ks_n = ksp;
+        v.split = 0;
+        items2[slot] = v;
+        if (L.split_items > 0) {
+          split_of[gj] = -1;
+          if (tall) split_of[gj + L.ND2] = -1;
+        }
+      } else {
+        const int q = slot - first_split;  // q-th split item: its extra ranges use pool tiles q*(nsplit-1) ..
+        atomicMin(&first_split_tile, g);
+        for (int sp = 0; sp < nsplit; ++sp) {
+          v.ks_lo = ksp * sp / nsplit;  // (at most a few thousand stages times 8)
+          v.ks_n = ksp * (sp + 1) / nsplit - v.ks_lo;
+          v.split = sp == 0 ? 0 : 1 + q * (nsplit - 1) + (sp - 1);
+          items2[first_split + q * nsplit + sp] = v;
+        }
+        split_of[gj] = q * (nsplit - 1);
+        if (tall) split_of[gj + L.ND2] = q * (nsplit - 1) | kSplitRowsOffset;  // rows of the short tile: BM further down the pool tiles
       }
     }
-    if (nsplit == 1) first_split = W2n;
-  }
-  int32_t* split_of = (int32_t*)(ws + L.o_split_of);
-  for (int gj = tid; gj < total_tiles * L.ND2; gj += kPlanThreads) {
-    const int g = gj / L.ND2, jd = gj % L.ND2;
-    const int e = tile_expert(g);
-    const int i = g - ts[e];
-    const int ksp = (e < E_res ? L.Fp : L.F_shT) / kBK;
-    const int nt_all = tiles_of(ne[e]), sl = short_last(e);
-    if (sl && i == nt_all - 1) continue;         // the short last tile: computed by the items of the tile before
-    const bool tall = sl && i == nt_all - 2;
-    Item2 v;
-    v.row0 = rs[e] + i * BM;
-    v.nrows = min(ne[e] - i * BM, BM) + (tall ? ne[e] - (i + 1) * BM : 0);
-    v.e = e;
-    v.jd = jd;
-    v.kmask = tbits[g] | (tall ? tbits[g + 1] : 0);
-    // list order (expert, column tile, row tile) if g2_rows_inner: the row tiles that share one column
-    // tile of W2 are adjacent, run at the same time on one XCD and fetch the weights once;
-    // else (row tile, column tile)
-    const int nt_e = nt_all - sl;                                         // tiles of the expert that have items
-    const int ts_e = ts[e] - abp[has_sh ? (e == E_res ? 0 : e + 1) : e];  // and of the experts before it
-    const int slot = L.g2_rows_inner ? ts_e * L.ND2 + jd * nt_e + i : (ts_e + i) * L.ND2 + jd;
-    if (slot < first_split) {
-      v.ks_lo = 0;
-      v.ks_n = ksp;
-      v.split = 0;
-      items2[slot] = v;
-      if (L.split_items > 0) {
-        split_of[gj] = -1;
-        if (tall) split_of[gj + L.ND2] = -1;
-      }
-    } else {
-      const int q = slot - first_split;  // q-th split item: its extra ranges use pool tiles q*(nsplit-1) ..
-      atomicMin(&first_split_tile, g);
-      for (int sp = 0; sp < nsplit; ++sp) {
-        v.ks_lo = ksp * sp / nsplit;  // (at most a few thousand stages times 8)
-        v.ks_n = ksp * (sp + 1) / nsplit - v.ks_lo;
-        v.split = sp == 0 ? 0 : 1 + q * (nsplit - 1) + (sp - 1);
-        items2[first_split + q * nsplit + sp] = v;
-      }
-      split_of[gj] = q * (nsplit - 1);
-      if (tall) split_of[gj + L.ND2] = q * (nsplit - 1) | kSplitRowsOffset;  // rows of the short tile: BM further down the pool tiles
+    __syncthreads();  // first_split_tile is final
+    if (tid == 0) {
+      counters[1] = first_split + (W2n - first_split) * nsplit;
+      counters[2] = total_tiles - total_short;  // row tiles that have GEMM-2 items
+      counters[3] = nsplit;
+      counters[4] = first_split_tile;
     }
+    return;
   }
   // 6. per (expert, partition): rank of each active tile among the active tiles of its group
   if (total_tiles <= kPlanTilesLds) {
@@ -842,13 +859,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Layout L, int T, cha
     __syncthreads();
     total_slots = slots_all;
   }
-  if (tid == 0) {
-    counters[0] = total_slots;
-    counters[1] = first_split + (W2n - first_split) * nsplit;
-    counters[2] = total_tiles - total_short;  // row tiles that have GEMM-2 items
-    counters[3] = nsplit;
-    counters[4] = first_split_tile;
-  }
+  if (tid == 0) counters[0] = total_slots;
 }
 
 hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
@@ -860,7 +871,7 @@ hipError_t launch_plan(const Layout& L, int T, char* ws, hipStream_t s) {
     hipError_t e = once.run([] { return hipFuncSetAttribute((const void*)plan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 104 * 1024); });
     if (e != hipSuccess) return e;
   }
-  plan_kernel<<<dim3(1), dim3(kPlanThreads), sh, s>>>(L, T, ws);
+  plan_kernel<<<dim3(2), dim3(kPlanThreads), sh, s>>>(L, T, ws);  // workgroup 0: GEMM-2 list, workgroup 1: GEMM-1 list
   return hipGetLastError();
 }
 
