@@ -58,7 +58,27 @@ def draw_medium_case(seed):
     return spec, max_tokens, tau_kind, bool(rng.random() < 0.3), "bf16_mfma"
 
 
-CASES = [draw_case(s) for s in range(32)] + [draw_medium_case(s) for s in range(24)]
+def draw_large_case(seed):
+    """Matrix-core path, work lists of many rounds of items (thousands of tokens): where the plan prices
+    lists with and without tall items, splits the last round of GEMM-2 and orders items for the XCDs."""
+    rng = np.random.default_rng(9000 + seed)
+    E = int(rng.choice([4, 8, 16, 32]))
+    K = int(rng.integers(1, 5))
+    P = int(rng.choice([1, 2, 4]))
+    D = 64 * int(rng.integers(2, 9))
+    Fp = 128 * int(rng.integers(1, 7)) + int(rng.choice([0, 0, 96]))
+    F_sh = 128 * int(rng.integers(1, 5))
+    n_shared = int(rng.choice([0, 0, 1]))
+    T = int(rng.integers(1500, 7000))
+    max_tokens = T + int(rng.choice([0, 300]))
+    tau_kind = ["zero", "rate", "rate", "ragged"][int(rng.integers(0, 4))]
+    spec = LayerSpec(name="big%d" % seed, T=T, D=D, F=Fp * P, E=E, K=K, P=P, dtype="bf16", seed=9500 + seed, n_shared=n_shared,
+                     F_sh=F_sh if n_shared else 0, resident=(0, E), x_std=1.0, w_std=float(rng.choice([0.05, 0.2])),
+                     perm_kind=str(rng.choice(["random", "identity"])))
+    return spec, max_tokens, tau_kind, bool(rng.random() < 0.3), "bf16_mfma"
+
+
+CASES = [draw_case(s) for s in range(32)] + [draw_medium_case(s) for s in range(24)] + [draw_large_case(s) for s in range(12)]
 
 
 @pytest.mark.parametrize("spec,max_tokens,tau_kind,renorm,kind", CASES, ids=["%s_%s" % (c[0].name, c[4]) for c in CASES])
