@@ -281,8 +281,15 @@ int moe_thresholds_for_drop_rate(dsmoe_ctx* ctx, const float* logits, int32_t T,
  *  10 rows at the start of the row space that the last call gave to the shared experts (a count)
  *  11 counters int32[5]: items of GEMM-1, items of GEMM-2, row tiles that have GEMM-2 items, K ranges GEMM-2 is
  *     split into, first row tile (in row order) with a split item
+ *  12 work list of the first grouped GEMM, counters[0] records of 8 int32: first row, rows the item multiplies, expert
+ *     (resident index; the number of resident experts = the shared experts), partition, neuron tile, rows it writes
+ *     (the rest zeros), half (0 whole neuron tile, 1 / 2 its first / second 64 neurons), unused
+ *  13 work list of the second grouped GEMM, counters[1] records of 8 int32: first row, rows, expert, output column
+ *     tile, bit mask of the partitions it sums over, first K stage and number of K stages inside every such
+ *     partition, 0 or 1 + the partial-output tile it writes instead of the rows of the per-pair output
+ * (fields 12 and 13 describe the lists of the matrix-core path and of the generic path alike)
  */
-#define DSMOE_PLAN_FIELDS 12
+#define DSMOE_PLAN_FIELDS 14
 int dsmoe_plan_layout(const dsmoe_ctx* ctx, int64_t* out);
 
 /*

@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdsmoe.so")  # the in-tree build, nothing else
 
 DSMOE_F32, DSMOE_BF16 = 0, 1
-DSMOE_PLAN_FIELDS = 12
+DSMOE_PLAN_FIELDS = 14
 
 
 class DsmoeError(RuntimeError):
@@ -383,6 +383,8 @@ class DualSparseLayer:
             "tile_rows": lay[9],
             "shared_rows": lay[10],
             "counters": view(lay[11], 5, torch.int32),
+            "items1": view(lay[12], 8 * int(view(lay[11], 1, torch.int32)[0]), torch.int32).view(-1, 8),
+            "items2": view(lay[13], 8 * int(view(lay[11], 2, torch.int32)[1]), torch.int32).view(-1, 8),
         }
 
     def close(self) -> None:

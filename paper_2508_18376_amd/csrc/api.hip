@@ -583,6 +583,8 @@ int dsmoe_plan_layout(const dsmoe_ctx* ctx_, int64_t* out) {
   out[9] = L.BM;
   out[10] = ctx->last_sh_rows;
   out[11] = L.o_counters;
+  out[12] = L.o_items1;
+  out[13] = L.o_items2;
   return DSMOE_PLAN_FIELDS;
 }
 

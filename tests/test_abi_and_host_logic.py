@@ -115,10 +115,13 @@ def test_plan_layout_is_inside_the_workspace(lib):
     lib.dsmoe_plan_layout.restype = ctypes.c_int
     lib.dsmoe_workspace_bytes.restype = ctypes.c_size_t
     rc, ctx = create(lib, d_model=256, d_ff=512, max_tokens=1000, dtype=1)
-    out = (ctypes.c_int64 * 12)()
-    assert lib.dsmoe_plan_layout(ctx, out) == 12
+    from paper_2508_18376_amd.binding import DSMOE_PLAN_FIELDS
+    header = open(os.path.join(ROOT, "include", "dsmoe.h")).read()
+    assert "#define DSMOE_PLAN_FIELDS %d" % DSMOE_PLAN_FIELDS in header  # the binding sizes its buffer by this
+    out = (ctypes.c_int64 * DSMOE_PLAN_FIELDS)()
+    assert lib.dsmoe_plan_layout(ctx, out) == DSMOE_PLAN_FIELDS == 14
     ws = lib.dsmoe_workspace_bytes(ctx)
-    offs = [out[i] for i in (0, 1, 2, 3, 4, 5, 6, 7, 11)]
+    offs = [out[i] for i in (0, 1, 2, 3, 4, 5, 6, 7, 11, 12, 13)]
     assert all(0 <= o < ws and o % 256 == 0 for o in offs) and len(set(offs)) == len(offs)
     assert out[9] == 256 and out[8] % out[9] == 0 and out[8] >= 1000 * 2
 
