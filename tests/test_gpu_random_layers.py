@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from synth import LayerSpec, make_layer
+from plan_cover import check_cover
 from gpu_util import GUARD, make_gpu_layer, to_dev, to_host64, pick_tau, tau_table, assert_output_close
 
 pytestmark = pytest.mark.gpu
@@ -116,4 +117,7 @@ def test_random_layer(oracle, spec, max_tokens, tau_kind, renorm, kind):
     np.testing.assert_array_equal(plan["topk_idx"].cpu().numpy(), r.idx)
     np.testing.assert_array_equal(plan["keep_bits"].cpu().numpy(), r.keep_bits)
     assert_output_close(to_host64(y, spec.dtype), y_ref, spec.dtype)
+    if kind == "bf16_mfma":  # and the work lists behind that result cover every kept unit exactly once
+        check_cover({k: (v.cpu().numpy() if hasattr(v, "cpu") else v) for k, v in plan.items()}, name=spec.name, T=spec.T, D=spec.D,
+                    F=spec.F, P=spec.P, E_res=spec.hi - spec.lo, n_shared=spec.n_shared, F_sh=spec.F_sh)
     layer.close()
